@@ -1,0 +1,152 @@
+"""Seeded synthetic workloads shaped like the paper's evaluation datasets.
+
+This module only draws inputs.  It contains none of the method's arithmetic
+(no distances, no graph code, no quantisation) so that the CPU oracle and the
+HIP library can both be fed from it without sharing any logic.
+
+The paper evaluates on public benchmark sets (Sec. 6.1: 128-d uint8 SIFT-like
+vectors, 960-d float GIST-like vectors, 1536-d unit-norm embedding vectors).
+None of those sets is available here, so Gaussian-mixture generators of the
+same dimension, dtype and rough spectrum stand in for them.
+
+Workloads
+---------
+1  N=10,000  d=128  float32  64 isotropic Gaussians (centres N(0,1), sigma 0.3)
+2  N=1,000,000 d=128 uint8   256 Gaussians, mean 64 / std 30 overall, rounded, clipped
+3  N=1,000,000 d=960 float32 128 Gaussians, anisotropic spectrum lambda_i ~ i^-0.5
+4  N=1,000,000 d=1536 float32 512 Gaussians, lambda_i ~ 1/i, L2-normalised
+5  stream of workload 2's generator, N grows to 10,000,000
+
+Every generator is *prefix stable*: point i depends only on (workload, stream,
+i), never on how many points are requested, because points are drawn in fixed
+chunks of CHUNK rows, each from its own counter-derived PCG64 stream.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+CHUNK = 16384
+SEED0 = 20260107
+
+_SPEC = {
+    1: dict(d=128, dtype=np.float32, comps=64, kind="iso", centre_std=1.0, sigma=0.3),
+    2: dict(d=128, dtype=np.uint8, comps=256, kind="u8", centre_mean=64.0, centre_std=24.0, sigma=18.0),
+    3: dict(d=960, dtype=np.float32, comps=128, kind="aniso", centre_std=0.25, sigma=0.3, decay=0.5, normalise=False),
+    4: dict(d=1536, dtype=np.float32, comps=512, kind="aniso", centre_std=0.25, sigma=0.3, decay=1.0, normalise=True),
+}
+_SPEC[5] = _SPEC[2]
+
+_STREAM = {"base": 0, "query": 1000}
+
+
+def spec(workload: int) -> dict:
+    """Static description (dimension, dtype, generator family) of a workload."""
+    return dict(_SPEC[workload])
+
+
+def _seed(workload: int) -> int:
+    # workload 5 is a longer stream of workload 2's generator
+    return SEED0 + (2 if workload == 5 else workload)
+
+
+def random_orthogonal(d: int, seed: int) -> np.ndarray:
+    """Haar-distributed d x d orthogonal matrix: Q factor of a seeded Gaussian
+    matrix with the sign convention diag(R) > 0; computed in float64."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    g = rng.standard_normal((d, d))
+    q, r = np.linalg.qr(g)
+    q = q * np.sign(np.diag(r))[None, :]
+    return q
+
+
+_param_cache: dict = {}
+
+
+def _params(workload: int) -> dict:
+    key = 2 if workload == 5 else workload
+    if key in _param_cache:
+        return _param_cache[key]
+    sp = _SPEC[key]
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([_seed(key), 7777])))
+    d, c = sp["d"], sp["comps"]
+    p = {}
+    if sp["kind"] == "u8":
+        p["centres"] = sp["centre_mean"] + sp["centre_std"] * rng.standard_normal((c, d))
+    else:
+        p["centres"] = sp["centre_std"] * rng.standard_normal((c, d))
+    if sp["kind"] == "aniso":
+        lam = np.arange(1, d + 1, dtype=np.float64) ** (-sp["decay"])
+        lam *= (sp["sigma"] ** 2) / lam.mean()
+        u = random_orthogonal(d, _seed(key) + 4242)
+        # x = mu + (z * sqrt(lam)) @ U^T
+        p["mix"] = (np.sqrt(lam)[:, None] * u.T).astype(np.float32)
+    _param_cache[key] = p
+    return p
+
+
+def _chunk(workload: int, stream: str, chunk_idx: int) -> np.ndarray:
+    key = 2 if workload == 5 else workload
+    sp = _SPEC[key]
+    p = _params(key)
+    rng = np.random.Generator(
+        np.random.PCG64(np.random.SeedSequence([_seed(key), _STREAM[stream], chunk_idx]))
+    )
+    d = sp["d"]
+    comp = rng.integers(0, sp["comps"], size=CHUNK)
+    z = rng.standard_normal((CHUNK, d), dtype=np.float32)
+    mu = p["centres"][comp]
+    if sp["kind"] == "iso":
+        x = mu + sp["sigma"] * z
+        return x.astype(np.float32)
+    if sp["kind"] == "u8":
+        x = mu + sp["sigma"] * z
+        return np.clip(np.rint(x), 0, 255).astype(np.uint8)
+    x = mu.astype(np.float32) + z @ p["mix"]
+    if sp["normalise"]:
+        x /= np.linalg.norm(x.astype(np.float64), axis=1, keepdims=True).astype(np.float32)
+    return x.astype(np.float32)
+
+
+def points(workload: int, count: int, start: int = 0, stream: str = "base") -> np.ndarray:
+    """Rows [start, start+count) of the given stream of a workload."""
+    sp = _SPEC[workload]
+    out = np.empty((count, sp["d"]), dtype=sp["dtype"])
+    pos = start
+    end = start + count
+    while pos < end:
+        ci = pos // CHUNK
+        lo = pos - ci * CHUNK
+        take = min(CHUNK - lo, end - pos)
+        out[pos - start : pos - start + take] = _chunk(workload, stream, ci)[lo : lo + take]
+        pos += take
+    return out
+
+
+def base(workload: int, n: int, start: int = 0) -> np.ndarray:
+    return points(workload, n, start, "base")
+
+
+def queries(workload: int, nq: int) -> np.ndarray:
+    """Fresh draws from the same mixture; never members of the base stream."""
+    return points(workload, nq, 0, "query")
+
+
+def rotation(workload: int) -> np.ndarray:
+    """The random orthogonal matrix P (float32, row-major d x d) applied before
+    scalar quantisation (Sec. 5.1).  It is an input to both implementations."""
+    return random_orthogonal(_SPEC[workload]["d"], _seed(workload) + 2000).astype(np.float32)
+
+
+def insertion_order(workload: int, n: int) -> np.ndarray:
+    """Seeded permutation used for workload 1's random insertion order."""
+    rng = np.random.Generator(np.random.PCG64(_seed(workload) + 3000))
+    return rng.permutation(n)
+
+
+def dyadic_grid(n: int, d: int, seed: int, step: float = 0.125, lim: float = 4.0) -> np.ndarray:
+    """float32 points on a coarse dyadic grid.  Squared-L2 partial sums of such
+    points are exact in float32 in any summation order, which lets a float path
+    be compared bit for bit."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    k = int(round(lim / step))
+    return (rng.integers(-k, k + 1, size=(n, d)) * step).astype(np.float32)
