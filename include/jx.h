@@ -1,0 +1,203 @@
+/*
+ * jx.h -- C ABI of libjx: a single-GPU (gfx950 / MI355X) implementation of the
+ * Vamana-graph approximate nearest-neighbour path of "GPU-Accelerated ANNS:
+ * Quantized for Speed, Built for Change" (Jasper): batched beamSearch for
+ * queries and for batch insertion, robustPrune, reverse-edge merge, RaBitQ
+ * codes with estimated distances, exact re-ranking.
+ *
+ * General rules
+ *   - Every pointer named d_* is DEVICE memory, every h_* is HOST memory.
+ *   - The library never allocates or frees device memory: the caller hands in
+ *     one arena (jx_arena_bytes / jx_create) and owns it, and owns every input
+ *     and output buffer.  The arena must stay alive and untouched until
+ *     jx_destroy.
+ *   - All work is enqueued on the caller's stream (`stream` is a hipStream_t
+ *     passed as void*; NULL = the default stream).  Calls return after
+ *     enqueueing unless stated otherwise ("blocks" = synchronises the stream).
+ *   - A handle is not thread-safe.  Inserts, quantisation and searches on one
+ *     index run in phases and must not overlap (Sec. 4.5: a batch of inserts
+ *     completes before queries resume, and vice versa).
+ *   - Ids are uint32, assigned in insertion order starting at 0; at most
+ *     2^31 - 2 points.  0xFFFFFFFF (JX_NONE) marks an empty slot.
+ *   - Distances are SQUARED Euclidean distances (App. B: the square root is
+ *     monotone and is elided).  Results are sorted ascending by (distance, id).
+ *   - Return value: 0 on success, a negative JX_E* code otherwise; nothing
+ *     throws or aborts across the boundary.  jx_last_error() gives the text of
+ *     the last failure on the calling thread.
+ */
+#ifndef JX_H
+#define JX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define JX_NONE 0xFFFFFFFFu
+
+/* element types of the stored vectors and of the queries */
+#define JX_U8 0  /* uint8, distances accumulated exactly in int32 */
+#define JX_F32 1 /* float32 */
+
+/* search modes */
+#define JX_EXACT 0  /* distances on the stored full-precision vectors */
+#define JX_RABITQ 1 /* RaBitQ-estimated distances on the codes (needs jx_quantize) */
+
+/* what beamSearch hands to robustPrune during insertion */
+#define JX_CAND_FRONTIER 0 /* the final frontier F (Alg. 2's output) */
+
+/* rule that picks the m-bit code for m > 1 (Sec. 5.1 says only "simple scalar
+ * quantization") */
+#define JX_RULE_MAXABS 1 /* grid scale t = (2^(m-1) - 1/2) / max_i |r_i| */
+
+/* error codes */
+#define JX_OK 0
+#define JX_EINVAL (-1)    /* bad argument: dim, k > L, L too large, NULL pointer, dtype */
+#define JX_ECAPACITY (-2) /* insert beyond capacity, batch beyond max_batch, arena too small */
+#define JX_ESTATE (-3)    /* search on an empty index, RaBitQ search before jx_quantize */
+#define JX_EHIP (-4)      /* a HIP call failed; see jx_last_error() */
+
+/* limits */
+#define JX_MAX_L 512    /* largest beam width L / L_build */
+#define JX_MAX_R 256    /* largest out-degree R */
+#define JX_MAX_BF_K 128 /* largest k of jx_bruteforce */
+
+typedef struct jx_index jx_index; /* opaque, host side */
+
+typedef struct {
+    int32_t dim;       /* d.  uint8: multiple of 16; float32: multiple of 4 */
+    int32_t dtype;     /* JX_U8 | JX_F32 */
+    int32_t R;         /* maximum out-degree (Sec. 3.1), 1..JX_MAX_R */
+    int32_t L_build;   /* beam width used by insertion (Alg. 4), R.. JX_MAX_L is not required; 1..JX_MAX_L */
+    float alpha;       /* robustPrune factor, applied to squared distances (Alg. 3) */
+    int32_t cand_mode; /* JX_CAND_FRONTIER */
+    int64_t capacity;  /* maximum number of points; rows are preallocated */
+    int64_t max_batch; /* largest number of points linked by one internal batch
+                          and largest number of queries processed at once
+                          (larger query batches are processed in slices) */
+    int32_t quant_bits; /* 0: never quantised; 1 or 4: reserve room for RaBitQ codes */
+    int32_t reserved;
+} jx_params;
+
+/* Counters of one jx_search call, summed over its queries. */
+typedef struct {
+    uint64_t hops;         /* expansions (adjacency rows read) */
+    uint64_t dist_evals;   /* distance evaluations in beamSearch */
+    uint64_t adj_bytes;    /* hops * 4R */
+    uint64_t vec_bytes;    /* dist_evals * bytes fetched per evaluation */
+    uint64_t rerank_bytes; /* exact re-rank reads */
+} jx_stats;
+
+/* Bytes of device memory jx_create needs for these parameters (256-aligned
+ * sub-buffers: vectors, adjacency, codes, rotation, workspaces). <0: JX_EINVAL. */
+int64_t jx_arena_bytes(const jx_params* p);
+
+/* Create an empty index inside the caller's arena (device memory, at least
+ * jx_arena_bytes(p) bytes, 256-byte aligned).  Enqueues a fill of the
+ * adjacency table with JX_NONE on `stream`.  *out is a host object freed by
+ * jx_destroy. */
+int jx_create(const jx_params* p, void* d_arena, int64_t arena_bytes, void* stream, jx_index** out);
+
+/* Frees the host object only. */
+int jx_destroy(jx_index* idx);
+
+/*
+ * Batch insertion (Alg. 4 with the changes of Sec. 4.3 and 4.5).
+ * d_vecs: n vectors of the index's dtype, row-major [n][dim]; they receive ids
+ * [N, N+n) in the given order.  The call (1) appends them to the store, (2) on
+ * the first call picks the entry point = the point of that call nearest to the
+ * call's coordinate-wise mean (the paper's "medoid"), which joins the graph
+ * first with an empty row, (3) links the remaining points in id order in
+ * internal batches of size min(remaining, number of points already linked), so
+ * the linked set at most doubles per batch; each batch runs beamSearch
+ * (L_build, from the entry point, exact distances) for all its points against
+ * the graph as it stood before the batch, robustPrune of the final frontier
+ * (Alg. 3), emission of reverse edges to the kept neighbours only, one global
+ * sort by (target, distance, source), and per target either an append (row
+ * still fits) or robustPrune of row U new edges.  If the index is quantised
+ * the new vectors are encoded as well.
+ * Errors: JX_ECAPACITY if N+n > capacity or an internal batch > max_batch.
+ * Blocks only on the first call (reads the entry id back).
+ */
+int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream);
+
+/*
+ * RaBitQ quantisation of the current base set (Sec. 5.1), float32 data only.
+ * bits: 1 or 4 (must equal params.quant_bits).  d_rotation: orthogonal matrix P,
+ * float32 [dim][dim] row-major, applied as r = P (v - c).  d_centroid: c
+ * (float32 [dim]) or NULL = mean of the current base set.  query_bits: width
+ * B_q of the integer query (4 or 8).  rule: JX_RULE_MAXABS.
+ * Per vector the record is  dim*bits/8 code bytes, zero padding to a multiple
+ * of 16, then data_add = ||r||^2 and data_rescale = -2||r||^2/<xbar,r> as two
+ * floats, then padding to a multiple of 16 bytes.  The matrix, centroid and
+ * parameters are copied into the arena and frozen; later inserts are encoded
+ * with them.  dim must be a multiple of 32.
+ */
+int jx_quantize(jx_index* idx, int32_t bits, const float* d_rotation, const float* d_centroid, int32_t query_bits,
+                int32_t rule, void* stream);
+
+/*
+ * beamSearch for a batch of queries (Alg. 1 / Alg. 2) + optional exact re-rank.
+ * d_queries: [nq][dim] of the index's dtype.  k <= L <= JX_MAX_L.
+ * mode JX_EXACT: distances on the stored vectors.  mode JX_RABITQ: queries are
+ * centred, rotated (MFMA GEMM) and turned into integer records; beamSearch runs
+ * on estimated distances.  rerank == 0: the first k frontier entries are
+ * returned (distance = the estimate in RaBitQ mode).  rerank > 0 (k <= rerank
+ * <= L): the first `rerank` frontier entries are re-scored with the exact
+ * squared L2 against the original query, sorted by (distance, id), and the
+ * first k returned.
+ * d_out_ids [nq][k], d_out_dist [nq][k]; slots beyond the number of reachable
+ * points hold JX_NONE / +inf.  h_stats: NULL, or a host struct that receives
+ * the counters -- in that case the call BLOCKS until the stream has drained.
+ * Errors: JX_ESTATE on an empty index or RaBitQ mode before jx_quantize.
+ */
+int jx_search(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, int32_t L, int32_t mode, int32_t rerank,
+              uint32_t* d_out_ids, float* d_out_dist, jx_stats* h_stats, void* stream);
+
+/*
+ * The beamSearch stage alone: whole final frontier of every query, as used by
+ * insertion (Alg. 4, step 1).  d_out_ids / d_out_dist: [nq][L]; unused slots
+ * JX_NONE / +inf.  mode as in jx_search.
+ */
+int jx_beam_frontier(jx_index* idx, const void* d_queries, int64_t nq, int32_t L, int32_t mode, uint32_t* d_out_ids,
+                     float* d_out_dist, jx_stats* h_stats, void* stream);
+
+/* Exact k nearest neighbours of every query by exhaustive search (the recall
+ * ground truth of Sec. 6.1).  k <= JX_MAX_BF_K. */
+int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, uint32_t* d_out_ids,
+                  float* d_out_dist, void* stream);
+
+/* Number of points and entry id (host values; no device work). */
+int jx_size(const jx_index* idx, int64_t* n, uint32_t* entry_id);
+
+/* Copy out the adjacency table (d_adj [N][R], JX_NONE padded) and the row
+ * degrees (d_deg [N]; may be NULL). */
+int jx_export_graph(jx_index* idx, uint32_t* d_adj, uint32_t* d_deg, void* stream);
+
+/* Replace the index content by n vectors and a ready-made graph (used to
+ * search a graph built elsewhere, e.g. by a reference implementation).
+ * Rows must be filled from the left and padded with JX_NONE. */
+int jx_import_graph(jx_index* idx, const void* d_vecs, int64_t n, const uint32_t* d_adj, uint32_t entry_id,
+                    void* stream);
+
+/* Copy out codes (d_codes [N][dim*bits/8], unpadded), the two floats per
+ * vector (d_meta [N][2]) and the centroid (d_centroid [dim], may be NULL). */
+int jx_export_codes(jx_index* idx, uint8_t* d_codes, float* d_meta, float* d_centroid, void* stream);
+
+/* Stage entry points of the RaBitQ pipeline (Sec. 5.1), used to test each
+ * stage against injected inputs.
+ *   jx_rotate: d_out[n][dim] = (d_in[n][dim] - c) P^T with the index's frozen
+ *   P and c (the GEMM used for queries and for encoding).
+ *   jx_encode_rotated: encode n already-rotated vectors into unpadded codes
+ *   and meta, with the index's bits and rule. */
+int jx_rotate(jx_index* idx, const float* d_in, int64_t n, float* d_out, void* stream);
+int jx_encode_rotated(jx_index* idx, const float* d_rot, int64_t n, uint8_t* d_codes, float* d_meta, void* stream);
+
+const char* jx_strerror(int code);
+const char* jx_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JX_H */

@@ -1,0 +1,248 @@
+// Exhaustive k-nearest-neighbour search: the recall ground truth (Sec. 6.1).
+//
+// A 256-thread workgroup owns a tile of 64 queries and streams a slice of the
+// base set through LDS in tiles of 64 vectors.  Each thread accumulates a 4x4
+// block of the 64x64 distance tile (uint8: packed dot products, the distance is
+// ||a||^2 + ||q||^2 - 2<a,q> in exact integers; float32: sum of squared
+// differences).  A wavefront then folds each row of the tile into that query's
+// sorted top-k list in LDS; only candidates that beat the current k-th key do
+// any work.  A second kernel merges the per-slice lists.
+#include "jx_device.h"
+#include "jx_internal.h"
+
+namespace jx {
+
+#define BF_TQ 64
+#define BF_TB 64
+#define BF_KS 16  // dwords of the vector dimension per slab
+
+template <int DT>
+__global__ void __launch_bounds__(256) bruteforce_tile_kernel(BfArgs a) {
+    __shared__ uint32_t Qs[BF_KS][BF_TQ + 1];
+    __shared__ uint32_t Bs[BF_KS][BF_TB + 1];
+    __shared__ uint32_t Dt[BF_TQ][BF_TB + 1];
+    __shared__ uint32_t qn[BF_TQ], bn[BF_TB];
+    extern __shared__ __align__(16) unsigned char dyn[];
+    uint64_t* topk = reinterpret_cast<uint64_t*>(dyn);  // [BF_TQ][k]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int k = a.k;
+    const long long q0 = (long long)blockIdx.x * BF_TQ;
+    const int dw = (DT == JX_U8) ? a.d / 4 : a.d;  // dwords per vector
+    const long long per = (a.n + a.nsplit - 1) / a.nsplit;
+    const long long b_begin = (long long)blockIdx.y * per;
+    const long long b_end = b_begin + per < a.n ? b_begin + per : a.n;
+    const uint32_t* Q = reinterpret_cast<const uint32_t*>(a.queries);
+    const uint32_t* B = reinterpret_cast<const uint32_t*>(a.base);
+
+    for (int i = tid; i < BF_TQ * k; i += 256) topk[i] = JX_EMPTY_KEY;
+    __syncthreads();
+
+    for (long long b0 = b_begin; b0 < b_end; b0 += BF_TB) {
+        uint32_t acc_u[4][4];
+        float acc_f[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                acc_u[i][j] = 0;
+                acc_f[i][j] = 0.f;
+            }
+        uint32_t nacc = 0;  // threads 0..63: ||b||^2, threads 64..127: ||q||^2
+        for (int ks = 0; ks < dw; ks += BF_KS) {
+            // stage one slab of both tiles, transposed to [kk][row]
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                int idx = tid + t * 256;
+                int row = idx / BF_KS, kk = idx % BF_KS;
+                uint32_t qv = 0, bv = 0;
+                if (ks + kk < dw) {
+                    if (q0 + row < a.nq) qv = Q[(size_t)(q0 + row) * dw + ks + kk];
+                    if (b0 + row < b_end) bv = B[(size_t)(b0 + row) * dw + ks + kk];
+                }
+                Qs[kk][row] = qv;
+                Bs[kk][row] = bv;
+            }
+            __syncthreads();
+            if (DT == JX_U8 && tid < 128) {
+#pragma unroll
+                for (int kk = 0; kk < BF_KS; kk++) {
+                    uint32_t v = tid < 64 ? Bs[kk][tid] : Qs[kk][tid - 64];
+                    nacc = __builtin_amdgcn_udot4(v, v, nacc, false);
+                }
+            }
+#pragma unroll
+            for (int kk = 0; kk < BF_KS; kk++) {
+                uint32_t qv[4], bv[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    qv[i] = Qs[kk][ty * 4 + i];
+                    bv[i] = Bs[kk][tx * 4 + i];
+                }
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        if (DT == JX_U8) {
+                            acc_u[i][j] = __builtin_amdgcn_udot4(qv[i], bv[j], acc_u[i][j], false);
+                        } else {
+                            float df = __uint_as_float(qv[i]) - __uint_as_float(bv[j]);
+                            acc_f[i][j] = fmaf(df, df, acc_f[i][j]);
+                        }
+                    }
+            }
+            __syncthreads();
+        }
+        if (DT == JX_U8) {
+            if (tid < 64) bn[tid] = nacc;
+            else if (tid < 128) qn[tid - 64] = nacc;
+            __syncthreads();
+        }
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                uint32_t code;
+                if (DT == JX_U8)
+                    code = qn[ty * 4 + i] + bn[tx * 4 + j] - 2u * acc_u[i][j];
+                else
+                    code = f32_to_ordered(acc_f[i][j]);
+                Dt[ty * 4 + i][tx * 4 + j] = code;
+            }
+        __syncthreads();
+        // fold the tile into the per-query lists: wave w owns rows 16w..16w+15
+        for (int rr = 0; rr < 16; rr++) {
+            const int row = wave * 16 + rr;
+            if (q0 + row >= a.nq) break;
+            uint64_t* list = topk + (size_t)row * k;
+            const long long bid = b0 + lane;
+            uint64_t key = JX_EMPTY_KEY;
+            if (bid < b_end) key = ((uint64_t)Dt[row][lane] << 32) | (uint64_t)(uint32_t)bid;
+            uint64_t thr = list[k - 1];
+            uint64_t sm = ballot(key < thr);
+            while (sm) {
+                const int j = __builtin_ctzll(sm);
+                sm &= sm - 1;
+                const uint64_t s = readlane64(key, j);
+                if (!(s < list[k - 1])) continue;  // the threshold may have tightened meanwhile
+                // entries e = lane, lane+64 (k <= 128)
+                uint64_t cur0 = lane < k ? list[lane] : 0, cur1 = lane + 64 < k ? list[lane + 64] : 0;
+                uint64_t prev0 = (lane >= 1 && lane - 1 < k) ? list[lane - 1] : 0;
+                uint64_t prev1 = (lane + 63 < k) ? list[lane + 63] : 0;
+                wave_sync();
+                if (lane < k) {
+                    uint64_t nv = cur0;
+                    if (s < cur0) nv = (lane >= 1 && s < prev0) ? prev0 : s;
+                    list[lane] = nv;
+                }
+                if (lane + 64 < k) {
+                    uint64_t nv = cur1;
+                    if (s < cur1) nv = (s < prev1) ? prev1 : s;
+                    list[lane + 64] = nv;
+                }
+                wave_sync();
+            }
+        }
+        __syncthreads();
+    }
+    for (int i = tid; i < BF_TQ * k; i += 256) {
+        int row = i / k, e = i % k;
+        if (q0 + row < a.nq) a.partial[((size_t)(q0 + row) * a.nsplit + blockIdx.y) * k + e] = topk[i];
+    }
+}
+
+// One wavefront per query: k rounds of "take the smallest remaining key".
+template <int DT>
+__global__ void __launch_bounds__(64) bruteforce_merge_kernel(BfArgs a) {
+    extern __shared__ __align__(16) unsigned char dyn[];
+    uint64_t* keys = reinterpret_cast<uint64_t*>(dyn);
+    const long long qi = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int m = a.nsplit * a.k;
+    const uint64_t* src = a.partial + (size_t)qi * m;
+    for (int i = lane; i < m; i += 64) keys[i] = src[i];
+    wave_sync();
+    for (int r = 0; r < a.k; r++) {
+        uint64_t best = JX_EMPTY_KEY;
+        int bi = -1;
+        for (int i = lane; i < m; i += 64) {
+            uint64_t v = keys[i];
+            if (v < best) {
+                best = v;
+                bi = i;
+            }
+        }
+        uint64_t wbest = best;
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            uint64_t o = shfl_xor(wbest, s);
+            wbest = o < wbest ? o : wbest;
+        }
+        if (wbest != JX_EMPTY_KEY && best == wbest && bi >= 0) keys[bi] = JX_EMPTY_KEY;  // ids are unique
+        wave_sync();
+        if (lane == 0) {
+            bool valid = wbest != JX_EMPTY_KEY;
+            uint32_t code = (uint32_t)(wbest >> 32);
+            float dist = (DT == JX_U8) ? (float)code : ordered_to_f32(code);
+            a.out_ids[qi * a.k + r] = valid ? (uint32_t)wbest : JX_NONE_ID;
+            a.out_dist[qi * a.k + r] = valid ? dist : __builtin_inff();
+        }
+    }
+}
+
+hipError_t launch_bruteforce(const BfArgs& a, hipStream_t st) {
+    if (a.nq <= 0) return hipSuccess;
+    dim3 grid((unsigned)((a.nq + BF_TQ - 1) / BF_TQ), (unsigned)a.nsplit);
+    size_t sh = (size_t)BF_TQ * a.k * 8;
+    size_t shm = (size_t)a.nsplit * a.k * 8;
+    if (a.dtype == JX_U8) {
+        auto kt = bruteforce_tile_kernel<JX_U8>;
+        (void)hipFuncSetAttribute((const void*)kt, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipLaunchKernelGGL(kt, grid, dim3(256), sh, st, a);
+        auto km = bruteforce_merge_kernel<JX_U8>;
+        (void)hipFuncSetAttribute((const void*)km, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipLaunchKernelGGL(km, dim3((unsigned)a.nq), dim3(64), shm, st, a);
+    } else {
+        auto kt = bruteforce_tile_kernel<JX_F32>;
+        (void)hipFuncSetAttribute((const void*)kt, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipLaunchKernelGGL(kt, grid, dim3(256), sh, st, a);
+        auto km = bruteforce_merge_kernel<JX_F32>;
+        (void)hipFuncSetAttribute((const void*)km, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipLaunchKernelGGL(km, dim3((unsigned)a.nq), dim3(64), shm, st, a);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ utilities
+
+__global__ void fill_u32_kernel(uint32_t* p, long long n, uint32_t v) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+hipError_t launch_fill_u32(uint32_t* p, long long n, uint32_t v, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    long long blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, n, v);
+    return hipGetLastError();
+}
+
+__global__ void row_degrees_kernel(const uint32_t* adj, long long n, int R, uint32_t* deg) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t* row = adj + (size_t)i * R;
+    int g = 0;
+    while (g < R && row[g] != JX_NONE_ID) g++;
+    deg[i] = (uint32_t)g;
+}
+
+hipError_t launch_row_degrees(const uint32_t* adj, long long n, int R, uint32_t* deg, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(row_degrees_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, adj, n, R, deg);
+    return hipGetLastError();
+}
+
+}  // namespace jx

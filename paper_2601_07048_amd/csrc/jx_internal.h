@@ -1,0 +1,77 @@
+// Host-side internals of libjx: index object, arena layout, kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/jx.h"
+
+#define JX_BEAM_WPB 4  // wavefronts (= queries) per workgroup of the beamSearch kernel
+
+namespace jx {
+
+// ---- beamSearch -----------------------------------------------------------
+struct BeamArgs {
+    const uint32_t* adj;   // [N][R]
+    int R;
+    const uint8_t* recs;   // records the distances are taken on
+    long long rec_stride;  // bytes between records (multiple of 16)
+    int nch;               // 16-byte chunks read per record
+    int meta_chunk;        // RaBitQ: chunk that holds data_add, data_rescale
+    const uint8_t* qrecs;  // per-query records
+    long long qrec_stride;
+    int qplane_stride;     // RaBitQ: bytes between the query's planes
+    long long nq;
+    int L;
+    uint32_t entry;
+    int hash_log2;         // log2 of the visited-table size
+    uint32_t* out_ids;     // [nq][out_k]
+    float* out_dist;       // [nq][out_k]
+    int out_k;
+    unsigned long long* stats;  // {hops, dist_evals} or NULL
+};
+hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st);
+
+// ---- brute force ------------------------------------------------------------
+struct BfArgs {
+    const void* base;
+    const void* queries;
+    int dtype, d;
+    long long n, nq;
+    int k;
+    int nsplit;
+    uint32_t* norms;        // u8: [n] squared norms of the base vectors
+    uint64_t* partial;      // [nq][nsplit][k]
+    uint32_t* out_ids;
+    float* out_dist;
+};
+hipError_t launch_bruteforce(const BfArgs& a, hipStream_t st);
+
+// ---- small utilities ----------------------------------------------------------
+hipError_t launch_fill_u32(uint32_t* p, long long n, uint32_t v, hipStream_t st);
+hipError_t launch_row_degrees(const uint32_t* adj, long long n, int R, uint32_t* deg, hipStream_t st);
+
+}  // namespace jx
+
+// ---- the index object --------------------------------------------------------
+struct jx_index {
+    jx_params p;
+    int64_t n;        // points stored and linked
+    uint32_t entry;
+    int vec_bytes;    // dim * element size
+    // arena sub-buffers
+    uint8_t* d_arena;
+    int64_t arena_bytes;
+    uint8_t* d_vecs;     // [capacity][vec_bytes]
+    uint32_t* d_adj;     // [capacity][R]
+    uint8_t* d_codes;    // [capacity][code_stride] RaBitQ records
+    float* d_P;          // [dim][dim]
+    float* d_centroid;   // [dim]
+    uint8_t* d_work;     // workspace shared by the phases
+    int64_t work_bytes;
+    unsigned long long* d_stats;  // [8] counters
+    // RaBitQ state
+    int quantized;    // 0 or bits
+    int qbits, rule;
+    int code_bytes;   // dim*bits/8
+    int meta_chunk;   // = ceil(code_bytes/16)
+    int code_stride;  // (meta_chunk+1)*16
+};

@@ -1,0 +1,218 @@
+"""Thin ctypes binding of libjx's C ABI (include/jx.h).
+
+Argument marshalling only: every function here forwards torch tensors' device
+pointers and the current HIP stream to the entry point of the same name.  There
+is no CPU path; importing this module without a built ``libjx.so`` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libjx.so")
+
+NONE = 0xFFFFFFFF
+U8, F32 = 0, 1
+EXACT, RABITQ = 0, 1
+CAND_FRONTIER = 0
+RULE_MAXABS = 1
+MAX_L, MAX_R, MAX_BF_K = 512, 256, 128
+
+EXPORTS = [
+    "jx_arena_bytes", "jx_create", "jx_destroy", "jx_insert", "jx_quantize", "jx_search", "jx_beam_frontier",
+    "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_rotate",
+    "jx_encode_rotated", "jx_strerror", "jx_last_error",
+]
+
+
+class Params(C.Structure):
+    _fields_ = [
+        ("dim", C.c_int32), ("dtype", C.c_int32), ("R", C.c_int32), ("L_build", C.c_int32), ("alpha", C.c_float),
+        ("cand_mode", C.c_int32), ("capacity", C.c_int64), ("max_batch", C.c_int64), ("quant_bits", C.c_int32),
+        ("reserved", C.c_int32),
+    ]
+
+
+class Stats(C.Structure):
+    _fields_ = [("hops", C.c_uint64), ("dist_evals", C.c_uint64), ("adj_bytes", C.c_uint64),
+                ("vec_bytes", C.c_uint64), ("rerank_bytes", C.c_uint64)]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k, _ in self._fields_}
+
+
+class JxError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"libjx error {code}: {text}")
+        self.code = code
+
+
+def load_library(path: str = LIB_PATH) -> C.CDLL:
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2601_07048_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(path)
+    lib.jx_arena_bytes.restype = C.c_int64
+    lib.jx_strerror.restype = C.c_char_p
+    lib.jx_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        getattr(lib, name)  # fail loudly on a missing symbol
+    return lib
+
+
+_lib = load_library()
+
+
+def _check(rc):
+    if rc != 0:
+        raise JxError(rc, (_lib.jx_last_error() or b"").decode() or _lib.jx_strerror(rc).decode())
+
+
+def _ptr(t):
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _torch_dtype(dtype):
+    return torch.uint8 if dtype == U8 else torch.float32
+
+
+def jx_arena_bytes(params: Params) -> int:
+    n = _lib.jx_arena_bytes(C.byref(params))
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+class Index:
+    """Owns the arena tensor and the opaque handle; methods mirror the C ABI."""
+
+    def __init__(self, dim, dtype, R, L_build, alpha=1.2, capacity=0, max_batch=0, quant_bits=0, device="cuda:0"):
+        self.params = Params(dim=dim, dtype=dtype, R=R, L_build=L_build, alpha=alpha, cand_mode=CAND_FRONTIER,
+                             capacity=capacity, max_batch=max_batch or capacity, quant_bits=quant_bits, reserved=0)
+        self.device = torch.device(device)
+        self.dim, self.dtype, self.R = dim, dtype, R
+        nbytes = jx_arena_bytes(self.params)
+        with torch.cuda.device(self.device):
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            h = C.c_void_p()
+            _check(_lib.jx_create(C.byref(self.params), _ptr(self.arena), C.c_int64(nbytes), _stream(), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.jx_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    # -- jx_size
+    def size(self):
+        n = C.c_int64()
+        e = C.c_uint32()
+        _check(_lib.jx_size(self._h, C.byref(n), C.byref(e)))
+        return n.value, e.value
+
+    # -- jx_insert
+    def insert(self, vecs: torch.Tensor):
+        assert vecs.dtype == _torch_dtype(self.dtype) and vecs.shape[1] == self.dim
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_insert(self._h, _ptr(vecs), C.c_int64(vecs.shape[0]), _stream()))
+
+    # -- jx_import_graph / jx_export_graph
+    def import_graph(self, vecs, adj, entry):
+        assert vecs.dtype == _torch_dtype(self.dtype)
+        assert adj.dtype in (torch.int32, torch.uint32)
+        assert adj.shape == (vecs.shape[0], self.R)
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_import_graph(self._h, _ptr(vecs), C.c_int64(vecs.shape[0]), _ptr(adj), C.c_uint32(entry),
+                                        _stream()))
+
+    def export_graph(self):
+        n, _ = self.size()
+        adj = torch.empty((n, self.R), dtype=torch.int32, device=self.device)
+        deg = torch.empty(n, dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_export_graph(self._h, _ptr(adj), _ptr(deg), _stream()))
+        return adj, deg
+
+    # -- jx_quantize / jx_export_codes / stage entry points
+    def quantize(self, bits, rotation, centroid=None, query_bits=8, rule=RULE_MAXABS):
+        assert rotation.dtype == torch.float32 and rotation.shape == (self.dim, self.dim)
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_quantize(self._h, C.c_int32(bits), _ptr(rotation), _ptr(centroid), C.c_int32(query_bits),
+                                    C.c_int32(rule), _stream()))
+        self.bits = bits
+
+    def export_codes(self):
+        n, _ = self.size()
+        codes = torch.empty((n, self.dim * self.bits // 8), dtype=torch.uint8, device=self.device)
+        meta = torch.empty((n, 2), dtype=torch.float32, device=self.device)
+        cen = torch.empty(self.dim, dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_export_codes(self._h, _ptr(codes), _ptr(meta), _ptr(cen), _stream()))
+        return codes, meta, cen
+
+    def rotate(self, x):
+        out = torch.empty_like(x)
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_rotate(self._h, _ptr(x), C.c_int64(x.shape[0]), _ptr(out), _stream()))
+        return out
+
+    def encode_rotated(self, r):
+        n = r.shape[0]
+        codes = torch.empty((n, self.dim * self.bits // 8), dtype=torch.uint8, device=self.device)
+        meta = torch.empty((n, 2), dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_encode_rotated(self._h, _ptr(r), C.c_int64(n), _ptr(codes), _ptr(meta), _stream()))
+        return codes, meta
+
+    # -- jx_search / jx_beam_frontier / jx_bruteforce
+    def search(self, queries, k, L, mode=EXACT, rerank=0, stats=False, out=None):
+        nq = queries.shape[0]
+        if out is None:
+            ids = torch.empty((nq, k), dtype=torch.int32, device=self.device)
+            dist = torch.empty((nq, k), dtype=torch.float32, device=self.device)
+        else:
+            ids, dist = out
+        st = Stats() if stats else None
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_search(self._h, _ptr(queries), C.c_int64(nq), C.c_int32(k), C.c_int32(L), C.c_int32(mode),
+                                  C.c_int32(rerank), _ptr(ids), _ptr(dist), C.byref(st) if stats else None, _stream()))
+        return (ids, dist, st.as_dict()) if stats else (ids, dist)
+
+    def beam_frontier(self, queries, L, mode=EXACT, stats=False):
+        nq = queries.shape[0]
+        ids = torch.empty((nq, L), dtype=torch.int32, device=self.device)
+        dist = torch.empty((nq, L), dtype=torch.float32, device=self.device)
+        st = Stats() if stats else None
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_beam_frontier(self._h, _ptr(queries), C.c_int64(nq), C.c_int32(L), C.c_int32(mode),
+                                         _ptr(ids), _ptr(dist), C.byref(st) if stats else None, _stream()))
+        return (ids, dist, st.as_dict()) if stats else (ids, dist)
+
+    def bruteforce(self, queries, k):
+        nq = queries.shape[0]
+        ids = torch.empty((nq, k), dtype=torch.int32, device=self.device)
+        dist = torch.empty((nq, k), dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_bruteforce(self._h, _ptr(queries), C.c_int64(nq), C.c_int32(k), _ptr(ids), _ptr(dist),
+                                      _stream()))
+        return ids, dist
+
+
+def ids_to_numpy(t: torch.Tensor):
+    """int32 device tensor of ids -> uint32 numpy array."""
+    import numpy as np
+
+    return t.cpu().numpy().view(np.uint32)

@@ -1,0 +1,192 @@
+"""GPU parity: beamSearch and brute force through the C ABI vs the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_07048_amd import datagen
+from gpu_common import dev, u32, random_data, oracle_index, gpu_index_from_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def jx():
+    from paper_2601_07048_amd import jx as m
+    return m
+
+
+@pytest.fixture(scope="module")
+def u8_case(jx):
+    n = 20000
+    x = datagen.base(2, n)
+    q = datagen.queries(2, 203)  # not a multiple of the queries per workgroup
+    ix = oracle_index(x, 64, 64)
+    g = gpu_index_from_oracle(jx, x, ix, 64, 64)
+    return x, q, ix, g
+
+
+@pytest.fixture(scope="module")
+def f32_case(jx):
+    n = 10000
+    x = datagen.base(1, n)[datagen.insertion_order(1, n)]
+    q = datagen.queries(1, 200)
+    ix = oracle_index(x, 32, 64)
+    g = gpu_index_from_oracle(jx, x, ix, 32, 64)
+    return x, q, ix, g
+
+
+@pytest.mark.parametrize("L", [1, 10, 32, 64, 100, 128, 200, 256, 300, 512])
+def test_beam_u8_bit_exact(jx, u8_case, L):
+    """Integer distances: the whole frontier (ids and distances), the number of
+    expansions and the bounds on distance evaluations must match the oracle."""
+    x, q, ix, g = u8_case
+    ref = ix.search(q, 1, L, want_frontier=True)
+    ref_nofilter = ix.search(q, 1, L, filter=oracle.FILTER_NONE)
+    ids, dist, st = g.beam_frontier(dev(q), L, stats=True)
+    ids, dist = u32(ids), dist.cpu().numpy()
+    assert np.array_equal(ids, ref["F_ids"])
+    assert np.array_equal(dist.astype(np.float64), ref["F_dist"])
+    assert st["hops"] == ref["hops"]
+    assert ref["evals"] <= st["dist_evals"] <= ref_nofilter["evals"]
+    assert st["adj_bytes"] == st["hops"] * 4 * 64 and st["vec_bytes"] == st["dist_evals"] * 128
+
+
+def test_search_topk_is_frontier_prefix_and_deterministic(jx, u8_case):
+    x, q, ix, g = u8_case
+    dq = dev(q)
+    a_ids, a_dist = g.search(dq, 10, 64)
+    b_ids, b_dist = g.search(dq, 10, 64)
+    f_ids, f_dist = g.beam_frontier(dq, 64)
+    assert torch.equal(a_ids, b_ids) and torch.equal(a_dist, b_dist)
+    assert torch.equal(a_ids, f_ids[:, :10]) and torch.equal(a_dist, f_dist[:, :10])
+    ref = ix.search(q, 10, 64)
+    assert np.array_equal(u32(a_ids), ref["ids"])
+
+
+@pytest.mark.parametrize("L", [16, 64, 130])
+def test_beam_f32_tolerance(jx, f32_case, L):
+    """float32 distances: within 1e-4 relative of the oracle's double result;
+    ids compared where the oracle's gap to both neighbours exceeds that."""
+    x, q, ix, g = f32_case
+    ref = ix.search(q, 1, L, want_frontier=True)
+    ids, dist = g.beam_frontier(dev(q), L)
+    ids, dist = u32(ids), dist.cpu().numpy().astype(np.float64)
+    rd, ri = ref["F_dist"], ref["F_ids"]
+    assert np.allclose(dist, rd, rtol=1e-4, atol=0)
+    gap_prev = np.abs(np.diff(rd, axis=1, prepend=-np.inf))
+    gap_next = np.abs(np.diff(rd, axis=1, append=np.inf))
+    safe = (gap_prev > 2e-4 * rd) & (gap_next > 2e-4 * rd)
+    assert safe.mean() > 0.8
+    assert np.array_equal(ids[safe], ri[safe])
+    # recall against brute force within 0.002 of the oracle's
+    gt, _ = oracle.bruteforce(x, q, min(10, L))
+    k = min(10, L)
+    assert abs(oracle.recall_at_k(ids[:, :k], gt) - oracle.recall_at_k(ri[:, :k], gt)) <= 0.002
+
+
+def test_beam_f32_dyadic_grid_bit_exact(jx):
+    """Points on a coarse dyadic grid make every float32 partial sum exact in
+    any order, so the float path can be compared bit for bit."""
+    x = datagen.dyadic_grid(4000, 64, seed=5)
+    q = datagen.dyadic_grid(100, 64, seed=6)
+    ix = oracle_index(x, 24, 48)
+    g = gpu_index_from_oracle(jx, x, ix, 24, 48)
+    for L in (20, 70):
+        ref = ix.search(q, 1, L, want_frontier=True)
+        ids, dist, st = g.beam_frontier(dev(q), L, stats=True)
+        assert np.array_equal(u32(ids), ref["F_ids"])
+        assert np.array_equal(dist.cpu().numpy().astype(np.float64), ref["F_dist"])
+        assert st["hops"] == ref["hops"]
+
+
+@pytest.mark.parametrize("dtype,d", [(np.uint8, 16), (np.uint8, 64), (np.uint8, 256), (np.uint8, 1024),
+                                     (np.uint8, 2048), (np.uint8, 4096), (np.uint8, 6144),
+                                     (np.float32, 4), (np.float32, 96), (np.float32, 200), (np.float32, 960),
+                                     (np.float32, 1536)])
+def test_beam_shapes(jx, dtype, d):
+    """Every lanes-per-record / chunks-per-lane variant, ragged dimensions."""
+    n = 1500
+    x = random_data(n, d, dtype, seed=d)
+    q = random_data(37, d, dtype, seed=d + 1)
+    ix = oracle_index(x, 20, 40)
+    g = gpu_index_from_oracle(jx, x, ix, 20, 40)
+    ref = ix.search(q, 1, 50, want_frontier=True)
+    ids, dist = g.beam_frontier(dev(q), 50)
+    ids, dist = u32(ids), dist.cpu().numpy().astype(np.float64)
+    if dtype == np.uint8:
+        # the order is decided on exact integers; the returned float32 is the
+        # exact distance when it is below 2^24 (d <= 256), else its nearest float
+        assert np.array_equal(ids, ref["F_ids"])
+        assert np.array_equal(dist, ref["F_dist"].astype(np.float32).astype(np.float64))
+    else:
+        assert np.allclose(dist, ref["F_dist"], rtol=1e-4)
+        assert (ids == ref["F_ids"]).mean() > 0.98
+
+
+@pytest.mark.parametrize("R", [1, 7, 64, 100, 256])
+def test_beam_degrees(jx, R):
+    x = random_data(1200, 32, np.uint8, seed=R)
+    q = random_data(21, 32, np.uint8, seed=R + 1)
+    ix = oracle_index(x, R, 32)
+    g = gpu_index_from_oracle(jx, x, ix, R, 32)
+    ref = ix.search(q, 1, 40, want_frontier=True)
+    ids, dist, st = g.beam_frontier(dev(q), 40, stats=True)
+    assert np.array_equal(u32(ids), ref["F_ids"])
+    assert st["hops"] == ref["hops"]
+
+
+def test_beam_small_index_and_padding(jx):
+    """N < L: the frontier never fills; unused slots are NONE / +inf.  An entry
+    with no edges returns only itself."""
+    x = random_data(9, 16, np.uint8, seed=1)
+    ix = oracle_index(x, 4, 8)
+    g = gpu_index_from_oracle(jx, x, ix, 4, 8)
+    q = random_data(5, 16, np.uint8, seed=2)
+    ref = ix.search(q, 1, 32, want_frontier=True)
+    ids, dist = g.beam_frontier(dev(q), 32)
+    assert np.array_equal(u32(ids), ref["F_ids"])
+    d = dist.cpu().numpy()
+    assert np.isinf(d[u32(ids) == jx.NONE]).all() and (u32(ids) == jx.NONE).any()
+    adj = np.full((9, 4), jx.NONE, np.uint32)
+    g.import_graph(dev(x), dev(adj), 3)
+    ids, dist = g.search(dev(q), 2, 4)
+    assert (u32(ids)[:, 0] == 3).all() and (u32(ids)[:, 1] == jx.NONE).all()
+
+
+def test_search_argument_errors(jx, u8_case):
+    x, q, ix, g = u8_case
+    dq = dev(q)
+    with pytest.raises(jx.JxError):
+        g.search(dq, 11, 10)            # k > L
+    with pytest.raises(jx.JxError):
+        g.search(dq, 10, jx.MAX_L + 1)  # L too large
+    with pytest.raises(jx.JxError):
+        g.search(dq, 10, 64, mode=jx.RABITQ)  # not quantised
+    e = jx.Index(128, jx.U8, 8, 8, 1.2, capacity=16)
+    with pytest.raises(jx.JxError):
+        e.search(dq, 1, 8)              # empty index
+    ids, dist = g.search(dq[:0], 10, 64)  # empty batch is fine
+    assert ids.shape == (0, 10)
+    with pytest.raises(jx.JxError):
+        jx.Index(100, jx.U8, 8, 8, 1.2, capacity=16)  # bad dim
+
+
+@pytest.mark.parametrize("dtype,n,d,k", [(np.uint8, 5000, 128, 10), (np.uint8, 777, 32, 1), (np.float32, 3000, 96, 100),
+                                         (np.float32, 1000, 960, 10), (np.uint8, 100, 16, 128)])
+def test_bruteforce_parity(jx, dtype, n, d, k):
+    x = random_data(n, d, dtype, seed=n)
+    q = random_data(70, d, dtype, seed=n + 1)
+    g = jx.Index(d, jx.U8 if dtype == np.uint8 else jx.F32, 8, 8, 1.2, capacity=n)
+    adj = np.full((n, 8), jx.NONE, np.uint32)
+    g.import_graph(dev(x), dev(adj), 0)
+    ids, dist = g.bruteforce(dev(q), k)
+    ids, dist = u32(ids), dist.cpu().numpy().astype(np.float64)
+    rid, rd = oracle.bruteforce(x, q, k)
+    if dtype == np.uint8:
+        assert np.array_equal(ids, rid) and np.array_equal(dist, rd)
+    else:
+        fin = np.isfinite(rd)
+        assert np.allclose(dist[fin], rd[fin], rtol=1e-4)
+        assert np.array_equal(np.isfinite(dist), fin)
+        assert (ids == rid).mean() > 0.99
