@@ -1,0 +1,550 @@
+// Batch insertion (Alg. 4 with the changes of Sec. 4.3 / 4.5): everything that
+// follows the candidate search.
+//
+//   entry point   : column means (two-stage, fixed order, double) and the
+//                   point nearest to the mean
+//   forward prune : one wavefront per new point runs robustPrune (Alg. 3) on
+//                   its final frontier, writes adjacency row, emits reverse
+//                   edges (target, distance, source) to the kept neighbours only
+//   sort          : stable LSD radix sort (4-bit digits) of the unified edge
+//                   buffer on the 64-bit key (target << 32 | distance bits);
+//                   stability leaves equal keys in emission order = ascending
+//                   source id, so the order is (target, distance, source)
+//   reverse merge : one wavefront per touched target: append if the row still
+//                   fits, else robustPrune(row U new edges) with the existing
+//                   neighbours' distances recomputed.  A row is written by
+//                   exactly one wavefront: no locks (Sec. 3.3).
+//
+// robustPrune walks two sorted lists -- the target's existing neighbours (LDS)
+// and the new candidates (global memory, already sorted) -- as one merged
+// sequence.  Each time the closest live candidate p* is selected, all remaining
+// live candidates p' get d(p*,p') computed (T lanes per vector, as in
+// beamSearch) and are discarded when alpha * d(p*,p') <= d(p,p'), evaluated in
+// float32 as one multiply and one compare.
+#include "jx_distance.h"
+
+namespace jx {
+
+#define INS_WPB 4      // wavefronts per workgroup
+#define INS_RA JX_MAX_R
+
+// ------------------------------------------------------------------ entry point
+
+template <int DT>
+__global__ void __launch_bounds__(256) col_partial_kernel(const void* vecs, long long n, int d, int nblk, double* partial) {
+    const long long per = (n + nblk - 1) / nblk;
+    const long long r0 = (long long)blockIdx.x * per;
+    const long long r1 = r0 + per < n ? r0 + per : n;
+    for (int j = threadIdx.x; j < d; j += 256) {
+        double s = 0.0;
+        for (long long i = r0; i < r1; i++) {
+            if (DT == JX_U8)
+                s += (double)reinterpret_cast<const uint8_t*>(vecs)[(size_t)i * d + j];
+            else
+                s += (double)reinterpret_cast<const float*>(vecs)[(size_t)i * d + j];
+        }
+        partial[(size_t)blockIdx.x * d + j] = s;
+    }
+}
+
+__global__ void mean_finalize_kernel(const double* partial, int nblk, int d, long long n, float* mean) {
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= d) return;
+    double s = 0.0;
+    for (int b = 0; b < nblk; b++) s += partial[(size_t)b * d + j];
+    mean[j] = (float)(s / (double)n);
+}
+
+template <int DT>
+__global__ void __launch_bounds__(256) dist_to_mean_kernel(const void* vecs, long long n, int d, const float* mean, double* out) {
+    const long long i = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= n) return;
+    const int lane = lane_id();
+    double s = 0.0;
+    for (int j = lane; j < d; j += 64) {
+        double v = (DT == JX_U8) ? (double)reinterpret_cast<const uint8_t*>(vecs)[(size_t)i * d + j]
+                                 : (double)reinterpret_cast<const float*>(vecs)[(size_t)i * d + j];
+        double t = v - (double)mean[j];
+        s += t * t;
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) s += shfl_xor(s, m);
+    if (lane == 0) out[i] = s;
+}
+
+// single workgroup: smallest (distance, id)
+__global__ void __launch_bounds__(1024) argmin_kernel(const double* dist, long long n, uint32_t* out_id) {
+    __shared__ double sd[1024];
+    __shared__ long long si[1024];
+    double bd = __builtin_inf();
+    long long bi = 0x7FFFFFFFFFFFFFFFLL;
+    for (long long i = threadIdx.x; i < n; i += 1024) {
+        double v = dist[i];
+        if (v < bd || (v == bd && i < bi)) {
+            bd = v;
+            bi = i;
+        }
+    }
+    sd[threadIdx.x] = bd;
+    si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int s = 512; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) {
+            double od = sd[threadIdx.x + s];
+            long long oi = si[threadIdx.x + s];
+            if (od < sd[threadIdx.x] || (od == sd[threadIdx.x] && oi < si[threadIdx.x])) {
+                sd[threadIdx.x] = od;
+                si[threadIdx.x] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out_id = (uint32_t)si[0];
+}
+
+// ------------------------------------------------------------------ robustPrune
+
+struct PruneLds {
+    uint64_t a_key[INS_RA];   // existing neighbours sorted by (distance, id); key = distance bits << 32 | id
+    uint64_t a_tmp[INS_RA];
+    uint64_t cand_key[64];
+    uint32_t cand_id[64];
+    uint32_t cand_src[64];
+    uint32_t sel_id[INS_RA];
+    uint32_t sel_dist[INS_RA];
+    uint8_t a_dead[INS_RA];
+};
+
+template <int KIND>
+__device__ __forceinline__ float code_to_dist(uint32_t code) {
+    if constexpr (KIND == K_U8)
+        return (float)code;
+    else
+        return ordered_to_f32(code);
+}
+
+// Candidate list B in global memory: ids and non-negative float distance bits
+// with element strides, plus one discard byte per element.
+struct BList {
+    const uint32_t* ids;
+    const uint32_t* dbits;
+    int id_stride, d_stride;
+    int n;
+    uint8_t* dead;
+};
+
+// Evaluate d(pivot, c) for the live elements of one 64-wide chunk and discard
+// those with alpha * d(pivot,c) <= d(p,c).
+template <int KIND, int T, int CPL, bool IS_A>
+__device__ __forceinline__ void kill_chunk(const QueryRegs<KIND, CPL, 0>& q, const DistSrc& ds, PruneLds* L, const BList& B,
+                                           int c0, int n, float alpha, int g, int lig, int lane) {
+    constexpr int G = 64 / T;
+    constexpr int U0 = (8 / CPL) > 0 ? (8 / CPL) : 1;
+    constexpr int U = U0 < (64 / G) ? U0 : (64 / G);
+    const int i = c0 + lane;
+    bool alive = false;
+    uint32_t id = JX_NONE_ID;
+    if (i < n) {
+        if (IS_A) {
+            alive = L->a_dead[i] == 0;
+            id = (uint32_t)L->a_key[i];
+        } else {
+            alive = B.dead[i] == 0;
+            id = B.ids[(size_t)i * B.id_stride];
+        }
+    }
+    const uint64_t am = ballot(alive);
+    const int n_alive = __builtin_popcountll(am);
+    if (n_alive == 0) return;
+    if (alive) {
+        int slot = prefix_count(am);
+        L->cand_id[slot] = id;
+        L->cand_src[slot] = (uint32_t)i;
+    }
+    wave_sync();
+    for (int s0 = 0; s0 < n_alive; s0 += G * U)
+        eval_batch<KIND, T, CPL, 0, U>(q, ds, s0, n_alive, L->cand_id, L->cand_key, g, lig);
+    wave_sync();
+    if (lane < n_alive) {
+        const uint32_t src = L->cand_src[lane];
+        const float d1 = code_to_dist<KIND>(key_dist(L->cand_key[lane]));
+        float d2;
+        if (IS_A)
+            d2 = __uint_as_float((uint32_t)(L->a_key[src] >> 32));
+        else
+            d2 = __uint_as_float(B.dbits[(size_t)src * B.d_stride]);
+        if (__fmul_rn(alpha, d1) <= d2) {
+            if (IS_A)
+                L->a_dead[src] = 1;
+            else
+                B.dead[src] = 1;
+        }
+    }
+    __threadfence_block();
+    wave_sync();
+}
+
+// Alg. 3 over the merged sequence of A (LDS, nA entries) and B.  Returns the
+// number of selected ids (L->sel_id / L->sel_dist, selection order).
+template <int KIND, int T, int CPL>
+__device__ __forceinline__ int robust_prune_wave(const DistSrc& ds, PruneLds* L, int nA, const BList& B, int R, float alpha) {
+    const int lane = lane_id();
+    const int g = lane / T, lig = lane % T;
+    int iA = 0, iB = 0, nsel = 0;
+    QueryRegs<KIND, CPL, 0> q;
+    while (nsel < R) {
+        while (iA < nA && L->a_dead[iA]) iA++;
+        while (iB < B.n) {
+            const int i = iB + lane;
+            const bool alive = i < B.n && B.dead[i] == 0;
+            const uint64_t m = ballot(alive);
+            if (m) {
+                iB += __builtin_ctzll(m);
+                break;
+            }
+            iB += 64;
+        }
+        const bool hasA = iA < nA, hasB = iB < B.n;
+        if (!hasA && !hasB) break;
+        uint64_t kA = JX_EMPTY_KEY, kB = JX_EMPTY_KEY;
+        if (hasA) kA = L->a_key[iA];
+        if (hasB) kB = ((uint64_t)B.dbits[(size_t)iB * B.d_stride] << 32) | B.ids[(size_t)iB * B.id_stride];
+        const bool takeA = kA < kB;
+        const uint64_t kp = takeA ? kA : kB;
+        if (takeA) iA++; else iB++;
+        const uint32_t pid = (uint32_t)kp;
+        if (lane == 0) {
+            L->sel_id[nsel] = pid;
+            L->sel_dist[nsel] = (uint32_t)(kp >> 32);
+        }
+        nsel++;
+        if (nsel >= R) break;
+        load_query<KIND, T, CPL, 0>(q, ds, (int64_t)pid, lig);
+        for (int c0 = iA; c0 < nA; c0 += 64) kill_chunk<KIND, T, CPL, true>(q, ds, L, B, c0, nA, alpha, g, lig, lane);
+        for (int c0 = iB; c0 < B.n; c0 += 64) kill_chunk<KIND, T, CPL, false>(q, ds, L, B, c0, B.n, alpha, g, lig, lane);
+    }
+    wave_sync();
+    return nsel;
+}
+
+template <int KIND, int T, int CPL>
+__global__ void __launch_bounds__(INS_WPB * 64) forward_prune_kernel(InsertArgs a) {
+    __shared__ PruneLds lds[INS_WPB];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const long long i = (long long)blockIdx.x * INS_WPB + wave;
+    if (i >= a.B) return;
+    PruneLds* L = &lds[wave];
+    long long xid = a.id_base + i;
+    if (xid >= a.id_skip) xid++;
+    BList B;
+    B.ids = a.cand_ids + (size_t)i * a.L;
+    B.dbits = a.cand_dist + (size_t)i * a.L;
+    B.id_stride = 1;
+    B.d_stride = 1;
+    B.dead = a.dead + (size_t)i * a.L;
+    // the frontier is filled from the left: count its valid entries
+    int nB = 0;
+    for (int c0 = 0; c0 < a.L; c0 += 64) {
+        const int j = c0 + lane;
+        const bool valid = j < a.L && B.ids[j] != JX_NONE_ID;
+        if (j < a.L) B.dead[j] = 0;
+        nB += __builtin_popcountll(ballot(valid));
+    }
+    B.n = nB;
+    __threadfence_block();
+    wave_sync();
+    const int nsel = robust_prune_wave<KIND, T, CPL>(a.ds, L, 0, B, a.R, a.alpha);
+    uint32_t* row = a.adj + (size_t)xid * a.R;
+    for (int j = lane; j < a.R; j += 64) {
+        const bool on = j < nsel;
+        const uint32_t v = on ? L->sel_id[j] : JX_NONE_ID;
+        row[j] = v;
+        a.keys[(size_t)i * a.R + j] = on ? (((uint64_t)v << 32) | L->sel_dist[j]) : JX_EMPTY_KEY;
+        a.vals[(size_t)i * a.R + j] = on ? (uint32_t)xid : JX_NONE_ID;
+    }
+}
+
+template <int KIND, int T, int CPL>
+__global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs a) {
+    __shared__ PruneLds lds[INS_WPB];
+    constexpr int G = 64 / T;
+    constexpr int U0 = (8 / CPL) > 0 ? (8 / CPL) : 1;
+    constexpr int U = U0 < (64 / G) ? U0 : (64 / G);
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const int g = lane / T, lig = lane % T;
+    PruneLds* L = &lds[wave];
+    const long long nseg = *a.nseg;
+    const long long total = a.B * a.R;
+    for (long long s = (long long)blockIdx.x * INS_WPB + wave; s < nseg; s += (long long)gridDim.x * INS_WPB) {
+        const long long lo = a.heads[s];
+        const uint32_t v = (uint32_t)(a.keys[lo] >> 32);
+        // segment length
+        int m = 0;
+        for (long long c0 = lo; c0 < total; c0 += 64) {
+            const long long j = c0 + lane;
+            const bool same = j < total && (uint32_t)(a.keys[j] >> 32) == v;
+            const uint64_t sm = ballot(same);
+            m += __builtin_popcountll(sm);
+            if (sm != ~0ull) break;
+        }
+        uint32_t* row = a.adj + (size_t)v * a.R;
+        int deg = 0;
+        for (int rb = 0; rb < a.R; rb += 64) {
+            const bool on = rb + lane < a.R && row[rb + lane] != JX_NONE_ID;
+            deg += __builtin_popcountll(ballot(on));
+        }
+        if (deg + m <= a.R) {
+            for (int j = lane; j < m; j += 64) row[deg + j] = a.vals[lo + j];
+            continue;
+        }
+        // distances from v to its existing neighbours, then sort them
+        QueryRegs<KIND, CPL, 0> q;
+        load_query<KIND, T, CPL, 0>(q, a.ds, (int64_t)v, lig);
+        for (int c0 = 0; c0 < deg; c0 += 64) {
+            const int nn = deg - c0 < 64 ? deg - c0 : 64;
+            if (lane < nn) L->cand_id[lane] = row[c0 + lane];
+            wave_sync();
+            for (int s0 = 0; s0 < nn; s0 += G * U)
+                eval_batch<KIND, T, CPL, 0, U>(q, a.ds, s0, nn, L->cand_id, L->cand_key, g, lig);
+            wave_sync();
+            if (lane < nn) {
+                const uint64_t k = L->cand_key[lane];
+                const float dd = code_to_dist<KIND>(key_dist(k));
+                L->a_tmp[c0 + lane] = ((uint64_t)__float_as_uint(dd) << 32) | (uint64_t)key_id(k);
+            }
+            wave_sync();
+        }
+        for (int j = lane; j < deg; j += 64) {
+            const uint64_t k = L->a_tmp[j];
+            int rank = 0;
+            for (int t = 0; t < deg; t++) rank += (L->a_tmp[t] < k) ? 1 : 0;
+            L->a_key[rank] = k;
+            L->a_dead[j] = 0;
+        }
+        BList B;
+        B.ids = a.vals + lo;
+        B.dbits = reinterpret_cast<const uint32_t*>(a.keys + lo);
+        B.id_stride = 1;
+        B.d_stride = 2;
+        B.n = m;
+        B.dead = a.dead + lo;
+        for (int j = lane; j < m; j += 64) B.dead[j] = 0;
+        __threadfence_block();
+        wave_sync();
+        const int nsel = robust_prune_wave<KIND, T, CPL>(a.ds, L, deg, B, a.R, a.alpha);
+        for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? L->sel_id[j] : JX_NONE_ID;
+        wave_sync();
+    }
+}
+
+// ------------------------------------------------------------------ radix sort
+
+#define RS_ITEMS 16
+#define RS_TILE (256 * RS_ITEMS)
+
+__global__ void __launch_bounds__(256) radix_hist_kernel(const uint64_t* keys, long long n, int shift, uint32_t* table, int ntiles) {
+    __shared__ uint32_t cnt[16];
+    if (threadIdx.x < 16) cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const long long base = (long long)blockIdx.x * RS_TILE;
+#pragma unroll
+    for (int e = 0; e < RS_ITEMS; e++) {
+        const long long i = base + e * 256 + threadIdx.x;
+        if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & 15], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < 16) table[(size_t)threadIdx.x * ntiles + blockIdx.x] = cnt[threadIdx.x];
+}
+
+// exclusive prefix sum of `total` counters, single workgroup
+__global__ void __launch_bounds__(1024) radix_scan_kernel(uint32_t* table, long long total) {
+    __shared__ uint32_t ws[16];
+    __shared__ uint32_t carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (long long c0 = 0; c0 < total; c0 += 1024) {
+        const long long i = c0 + threadIdx.x;
+        const uint32_t v = i < total ? table[i] : 0u;
+        uint32_t x = v;
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            uint32_t o = __shfl_up(x, s, 64);
+            if (lane >= s) x += o;
+        }
+        if (lane == 63) ws[wave] = x;
+        __syncthreads();
+        uint32_t woff = 0;
+        for (int w = 0; w < wave; w++) woff += ws[w];
+        const uint32_t carry = carry_s;
+        if (i < total) table[i] = carry + woff + x - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry_s = carry + woff + x;
+        __syncthreads();
+    }
+}
+
+__global__ void __launch_bounds__(256) radix_scatter_kernel(const uint64_t* keys, const uint32_t* vals, uint64_t* keys_out,
+                                                           uint32_t* vals_out, long long n, int shift,
+                                                           const uint32_t* table, int ntiles) {
+    __shared__ uint16_t hist[16 * 256];  // [digit][thread]
+    __shared__ uint32_t psum[256];
+    __shared__ uint32_t gbase[16];
+    __shared__ uint16_t bstart[16];
+    const int t = threadIdx.x;
+    const long long base = (long long)blockIdx.x * RS_TILE + (long long)t * RS_ITEMS;
+    uint64_t k[RS_ITEMS];
+    uint32_t v[RS_ITEMS];
+#pragma unroll
+    for (int e = 0; e < RS_ITEMS; e++) {
+        const long long i = base + e;
+        k[e] = i < n ? keys[i] : JX_EMPTY_KEY;
+        v[e] = i < n ? vals[i] : 0u;
+    }
+#pragma unroll
+    for (int d = 0; d < 16; d++) hist[d * 256 + t] = 0;
+#pragma unroll
+    for (int e = 0; e < RS_ITEMS; e++)
+        if (base + e < n) hist[((k[e] >> shift) & 15) * 256 + t]++;
+    if (t < 16) gbase[t] = table[(size_t)t * ntiles + blockIdx.x];
+    __syncthreads();
+    // exclusive scan over the digit-major linear order li = digit*256 + thread
+    uint32_t loc[16];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+        loc[e] = sum;
+        sum += hist[t * 16 + e];
+    }
+    psum[t] = sum;
+    __syncthreads();
+    // 256-entry scan by the first wavefront, 4 entries per lane
+    if (t < 64) {
+        uint32_t a0 = psum[4 * t], a1 = psum[4 * t + 1], a2 = psum[4 * t + 2], a3 = psum[4 * t + 3];
+        uint32_t tot = a0 + a1 + a2 + a3, x = tot;
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            uint32_t o = __shfl_up(x, s, 64);
+            if (t >= s) x += o;
+        }
+        uint32_t ex = x - tot;
+        psum[4 * t] = ex;
+        psum[4 * t + 1] = ex + a0;
+        psum[4 * t + 2] = ex + a0 + a1;
+        psum[4 * t + 3] = ex + a0 + a1 + a2;
+    }
+    __syncthreads();
+    const uint32_t off = psum[t];
+#pragma unroll
+    for (int e = 0; e < 16; e++) hist[t * 16 + e] = (uint16_t)(off + loc[e]);
+    __syncthreads();
+    if (t < 16) bstart[t] = hist[t * 256];
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < RS_ITEMS; e++) {
+        if (base + e < n) {
+            const int d = (int)((k[e] >> shift) & 15);
+            const uint32_t r = hist[d * 256 + t];
+            hist[d * 256 + t] = (uint16_t)(r + 1);
+            const size_t pos = (size_t)gbase[d] + (r - bstart[d]);
+            keys_out[pos] = k[e];
+            vals_out[pos] = v[e];
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) segment_heads_kernel(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t t = (uint32_t)(keys[i] >> 32);
+    if (t == JX_NONE_ID) return;
+    if (i == 0 || (uint32_t)(keys[i - 1] >> 32) != t) heads[atomicAdd(nseg, 1u)] = (uint32_t)i;
+}
+
+// ------------------------------------------------------------------ launchers
+
+hipError_t launch_entry_point(const void* vecs, int dtype, long long n, int d, double* partial, float* mean, double* dist,
+                              uint32_t* out_id, hipStream_t st) {
+    int nblk = (int)((n + 255) / 256);
+    if (nblk > 512) nblk = 512;
+    if (nblk < 1) nblk = 1;
+    if (dtype == JX_U8)
+        hipLaunchKernelGGL(col_partial_kernel<JX_U8>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
+    else
+        hipLaunchKernelGGL(col_partial_kernel<JX_F32>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
+    hipLaunchKernelGGL(mean_finalize_kernel, dim3((d + 255) / 256), dim3(256), 0, st, partial, nblk, d, n, mean);
+    if (dtype == JX_U8)
+        hipLaunchKernelGGL(dist_to_mean_kernel<JX_U8>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, vecs, n, d, mean, dist);
+    else
+        hipLaunchKernelGGL(dist_to_mean_kernel<JX_F32>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, vecs, n, d, mean, dist);
+    hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, st, dist, n, out_id);
+    return hipGetLastError();
+}
+
+int entry_point_partial_blocks(long long n) {
+    long long nblk = (n + 255) / 256;
+    return (int)(nblk > 512 ? 512 : (nblk < 1 ? 1 : nblk));
+}
+
+template <int KIND, int T, int CPL>
+static hipError_t launch_prune_pair(bool forward, const InsertArgs& a, hipStream_t st) {
+    if (forward) {
+        dim3 grid((unsigned)((a.B + INS_WPB - 1) / INS_WPB));
+        hipLaunchKernelGGL((forward_prune_kernel<KIND, T, CPL>), grid, dim3(INS_WPB * 64), 0, st, a);
+    } else {
+        long long want = (a.B * a.R + INS_WPB - 1) / INS_WPB;
+        unsigned grid = (unsigned)(want < 4096 ? (want < 1 ? 1 : want) : 4096);
+        hipLaunchKernelGGL((reverse_merge_kernel<KIND, T, CPL>), dim3(grid), dim3(INS_WPB * 64), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+template <int KIND>
+static hipError_t launch_prune_shape(bool forward, const InsertArgs& a, hipStream_t st) {
+    const int nch = a.ds.nch;
+    if (nch <= 8) return launch_prune_pair<KIND, 8, 1>(forward, a, st);
+    if (nch <= 16) return launch_prune_pair<KIND, 16, 1>(forward, a, st);
+    if (nch <= 32) return launch_prune_pair<KIND, 32, 1>(forward, a, st);
+    if (nch <= 64) return launch_prune_pair<KIND, 64, 1>(forward, a, st);
+    if (nch <= 128) return launch_prune_pair<KIND, 64, 2>(forward, a, st);
+    if (nch <= 256) return launch_prune_pair<KIND, 64, 4>(forward, a, st);
+    if (nch <= 384) return launch_prune_pair<KIND, 64, 6>(forward, a, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st) {
+    return dtype == JX_U8 ? launch_prune_shape<K_U8>(true, a, st) : launch_prune_shape<K_F32>(true, a, st);
+}
+
+hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st) {
+    return dtype == JX_U8 ? launch_prune_shape<K_U8>(false, a, st) : launch_prune_shape<K_F32>(false, a, st);
+}
+
+// Sorts n (key, value) pairs on key bits [0, nbits), stable.  The result is in
+// keys_a/vals_a again (an even number of passes is always run).
+hipError_t launch_radix_sort(uint64_t* keys_a, uint32_t* vals_a, uint64_t* keys_b, uint32_t* vals_b, long long n, int nbits,
+                             uint32_t* table, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    const int ntiles = (int)((n + RS_TILE - 1) / RS_TILE);
+    int passes = (nbits + 3) / 4;
+    if (passes & 1) passes++;
+    uint64_t *ki = keys_a, *ko = keys_b;
+    uint32_t *vi = vals_a, *vo = vals_b;
+    for (int p = 0; p < passes; p++) {
+        const int shift = 4 * p;
+        hipLaunchKernelGGL(radix_hist_kernel, dim3(ntiles), dim3(256), 0, st, ki, n, shift, table, ntiles);
+        hipLaunchKernelGGL(radix_scan_kernel, dim3(1), dim3(1024), 0, st, table, (long long)16 * ntiles);
+        hipLaunchKernelGGL(radix_scatter_kernel, dim3(ntiles), dim3(256), 0, st, ki, vi, ko, vo, n, shift, table, ntiles);
+        uint64_t* tk = ki; ki = ko; ko = tk;
+        uint32_t* tv = vi; vi = vo; vo = tv;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_segment_heads(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(segment_heads_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, keys, n, heads, nseg);
+    return hipGetLastError();
+}
+
+}  // namespace jx

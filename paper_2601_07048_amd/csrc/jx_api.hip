@@ -54,6 +54,32 @@ int check_params(const jx_params* p) {
     return JX_OK;
 }
 
+// Workspace of the insert phase for internal batches of at most B points.
+struct InsertWork {
+    int64_t cand_ids, cand_dist, keys0, keys1, vals0, vals1, heads, dead, table, counters, partial, mean, dist, total;
+};
+
+int64_t insert_work(const jx_params* p, int64_t B, InsertWork* w) {
+    int64_t off = 0;
+    const int64_t E = B * p->R;
+    auto take = [&](int64_t bytes) { int64_t o = off; off += align256(bytes); return o; };
+    w->cand_ids = take(B * p->L_build * 4);
+    w->cand_dist = take(B * p->L_build * 4);
+    w->keys0 = take(E * 8);
+    w->keys1 = take(E * 8);
+    w->vals0 = take(E * 4);
+    w->vals1 = take(E * 4);
+    w->heads = take(E * 4);
+    w->dead = take(B * (p->R > p->L_build ? p->R : p->L_build));
+    w->table = take(16 * (E / 4096 + 2) * 4);
+    w->counters = take(256);
+    w->partial = take((int64_t)512 * p->dim * 8);
+    w->mean = take((int64_t)p->dim * 4);
+    w->dist = take(p->capacity * 8);
+    w->total = off;
+    return off;
+}
+
 void layout(const jx_params* p, Layout* L) {
     L->vec_bytes = p->dim * (p->dtype == JX_U8 ? 1 : 4);
     L->code_bytes = p->quant_bits ? p->dim * p->quant_bits / 8 : 0;
@@ -74,13 +100,8 @@ void layout(const jx_params* p, Layout* L) {
     off += 256;
     // workspace: the larger of the insert phase and the query phase, at least 64 MiB
     const int64_t B = p->max_batch;
-    int64_t ins = align256(B * p->L_build * 4) * 2       // candidate ids, distances
-                  + align256(B * p->R * 8) * 2           // sort keys (ping-pong)
-                  + align256(B * p->R * 4) * 2           // sort payload (ping-pong)
-                  + align256(B * p->R * 4)               // segment heads
-                  + align256(B * p->R)                   // discard flags
-                  + align256((int64_t)p->dim * 8 + 64)   // mean / entry scratch
-                  + (1 << 20);                           // histograms, counters
+    InsertWork iw;
+    int64_t ins = insert_work(p, B, &iw);
     int64_t qry = align256(B * p->dim * 4)                              // rotated queries
                   + align256(B * ((int64_t)p->dim + 64) * 2)            // integer query records
                   + align256(B * JX_MAX_L * 4) * 2;                     // frontier ids / distances for re-rank
@@ -92,6 +113,8 @@ void layout(const jx_params* p, Layout* L) {
     L->total = off;
 }
 
+}  // namespace
+namespace {
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 int hash_log2_for(int L) {
@@ -214,13 +237,14 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     memset(&a, 0, sizeof a);
     a.adj = idx->d_adj;
     a.R = idx->p.R;
-    a.recs = idx->d_vecs;
-    a.rec_stride = idx->vec_bytes;
-    a.nch = idx->vec_bytes / 16;
-    a.meta_chunk = 0;
-    a.qrecs = (const uint8_t*)d_queries;
-    a.qrec_stride = idx->vec_bytes;
+    a.ds.recs = idx->d_vecs;
+    a.ds.rec_stride = idx->vec_bytes;
+    a.ds.nch = idx->vec_bytes / 16;
+    a.ds.meta_chunk = 0;
+    a.ds.qrecs = (const uint8_t*)d_queries;
+    a.ds.qrec_stride = idx->vec_bytes;
     a.nq = nq;
+    a.q_skip = 0x7FFFFFFFFFFFFFFFLL;
     a.L = L;
     a.entry = idx->entry;
     a.hash_log2 = hash_log2_for(L);
@@ -293,9 +317,118 @@ int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, u
     return JX_OK;
 }
 
+static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_t B, int64_t first, int64_t id_skip,
+                        int64_t n_after, hipStream_t st) {
+    uint8_t* W = idx->d_work;
+    const jx_params& p = idx->p;
+    jx::DistSrc ds;
+    memset(&ds, 0, sizeof ds);
+    ds.recs = idx->d_vecs;
+    ds.rec_stride = idx->vec_bytes;
+    ds.nch = idx->vec_bytes / 16;
+    ds.qrecs = idx->d_vecs;
+    ds.qrec_stride = idx->vec_bytes;
+    const int64_t id_base = first + pos0;
+    // 1. candidate generation: beamSearch from the entry point on the graph as it stands
+    jx::BeamArgs b;
+    memset(&b, 0, sizeof b);
+    b.adj = idx->d_adj;
+    b.R = p.R;
+    b.ds = ds;
+    b.ds.qrecs = idx->d_vecs + (size_t)id_base * idx->vec_bytes;
+    b.nq = B;
+    b.q_skip = id_skip >= id_base ? id_skip - id_base : 0;
+    b.L = p.L_build;
+    b.entry = idx->entry;
+    b.hash_log2 = hash_log2_for(p.L_build);
+    b.out_ids = (uint32_t*)(W + w.cand_ids);
+    b.out_dist = (float*)(W + w.cand_dist);
+    b.out_k = p.L_build;
+    b.stats = nullptr;
+    JX_HIP(jx::launch_beam_search(p.dtype == JX_U8 ? 0 : 1, 0, b, st));
+    // 2. robustPrune of the frontier, new rows, reverse edges
+    jx::InsertArgs a;
+    memset(&a, 0, sizeof a);
+    a.ds = ds;
+    a.adj = idx->d_adj;
+    a.R = p.R;
+    a.L = p.L_build;
+    a.alpha = p.alpha;
+    a.B = B;
+    a.id_base = id_base;
+    a.id_skip = id_skip;
+    a.cand_ids = (const uint32_t*)(W + w.cand_ids);
+    a.cand_dist = (const uint32_t*)(W + w.cand_dist);
+    a.dead = W + w.dead;
+    a.keys = (uint64_t*)(W + w.keys0);
+    a.vals = (uint32_t*)(W + w.vals0);
+    a.heads = (const uint32_t*)(W + w.heads);
+    a.nseg = (const uint32_t*)(W + w.counters);
+    JX_HIP(jx::launch_forward_prune(p.dtype, a, st));
+    // 3. one global sort by (target, distance, source)
+    int tbits = 1;
+    while (((int64_t)1 << tbits) <= n_after) tbits++;
+    const int64_t E = B * p.R;
+    JX_HIP(jx::launch_radix_sort((uint64_t*)(W + w.keys0), (uint32_t*)(W + w.vals0), (uint64_t*)(W + w.keys1),
+                                 (uint32_t*)(W + w.vals1), E, 32 + tbits, (uint32_t*)(W + w.table), st));
+    // 4. per target: append or robustPrune
+    JX_HIP(jx::launch_fill_u32((uint32_t*)(W + w.counters), 16, 0u, st));
+    JX_HIP(jx::launch_segment_heads((const uint64_t*)(W + w.keys0), E, (uint32_t*)(W + w.heads), (uint32_t*)(W + w.counters), st));
+    JX_HIP(jx::launch_reverse_merge(p.dtype, a, st));
+    return JX_OK;
+}
+
 int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream) {
-    (void)idx; (void)d_vecs; (void)n; (void)stream;
-    return fail(JX_ESTATE, "jx_insert: not available in this build");
+    if (!idx) return fail(JX_EINVAL, "index is NULL");
+    if (n < 0) return fail(JX_EINVAL, "n < 0");
+    if (n == 0) return JX_OK;
+    if (!d_vecs) return fail(JX_EINVAL, "d_vecs is NULL");
+    const jx_params& p = idx->p;
+    const int64_t first = idx->n;
+    if (first + n > p.capacity) return fail(JX_ECAPACITY, "%lld + %lld points exceed the capacity %lld", (long long)first, (long long)n, (long long)p.capacity);
+    if (idx->quantized) return fail(JX_ESTATE, "insert into a quantised index is not available in this build");
+    // the internal batch schedule: min(remaining, points already linked)
+    {
+        int64_t linked = first == 0 ? 1 : first, rem = first == 0 ? n - 1 : n, maxB = 0;
+        while (rem > 0) {
+            int64_t B = rem < linked ? rem : linked;
+            if (B > maxB) maxB = B;
+            linked += B;
+            rem -= B;
+        }
+        if (maxB > p.max_batch) return fail(JX_ECAPACITY, "an internal batch of %lld points exceeds max_batch = %lld", (long long)maxB, (long long)p.max_batch);
+    }
+    hipStream_t st = as_stream(stream);
+    InsertWork w;
+    insert_work(&p, p.max_batch, &w);
+    if (w.total > idx->work_bytes) return fail(JX_ECAPACITY, "workspace too small");
+    uint8_t* W = idx->d_work;
+    JX_HIP(hipMemcpyAsync(idx->d_vecs + (size_t)first * idx->vec_bytes, d_vecs, (size_t)n * idx->vec_bytes, hipMemcpyDeviceToDevice, st));
+    int64_t id_skip = 0x7FFFFFFFFFFFFFFFLL;
+    int64_t m = n, linked = first;
+    if (first == 0) {
+        // entry point: the point nearest to the mean of this first call; it joins alone
+        JX_HIP(jx::launch_entry_point(idx->d_vecs, p.dtype, n, p.dim, (double*)(W + w.partial), (float*)(W + w.mean),
+                                      (double*)(W + w.dist), (uint32_t*)(W + w.counters) + 32, st));
+        uint32_t e = 0;
+        JX_HIP(hipMemcpyAsync(&e, (uint32_t*)(W + w.counters) + 32, 4, hipMemcpyDeviceToHost, st));
+        JX_HIP(hipStreamSynchronize(st));
+        if (e >= (uint64_t)n) return fail(JX_EHIP, "entry point selection returned %u", e);
+        idx->entry = e;
+        id_skip = e;
+        m = n - 1;
+        linked = 1;
+    }
+    int64_t pos = 0;
+    while (pos < m) {
+        int64_t B = m - pos < linked ? m - pos : linked;
+        int rc = run_subbatch(idx, w, pos, B, first, id_skip, first + n, st);
+        if (rc) return rc;
+        pos += B;
+        linked += B;
+    }
+    idx->n = first + n;
+    return JX_OK;
 }
 
 int jx_quantize(jx_index* idx, int32_t bits, const float* d_rotation, const float* d_centroid, int32_t query_bits,

@@ -1,0 +1,197 @@
+// Distance providers shared by the beamSearch and robustPrune kernels:
+// a query (or pivot) vector held in registers, T lanes per stored record,
+// 16-byte gathers, partial sums reduced inside each T-lane group.
+//   K_U8  : uint8 vectors, exact int32 squared L2 via packed dot products
+//   K_F32 : float32 vectors, float32 squared L2
+//   K_RQ4 : 4-bit RaBitQ codes, packed 4-bit dot products against the two
+//           nibble planes of an 8-bit integer query
+//   K_RQ1 : 1-bit RaBitQ codes, AND + popcount against the query's bit planes
+#pragma once
+#include "jx_device.h"
+#include "jx_internal.h"
+
+namespace jx {
+
+enum { K_U8 = 0, K_F32 = 1, K_RQ4 = 2, K_RQ1 = 3 };
+
+template <int KIND, int CPL, int QB>
+struct QueryRegs {
+    static constexpr int PLANES = (KIND == K_RQ4) ? 2 : (KIND == K_RQ1 ? QB : 1);
+    static constexpr int N = 4 * CPL * PLANES;
+    uint32_t w[N];
+    uint32_t cmask[CPL];  // RaBitQ: all-ones for code chunks, 0 for the meta chunk and beyond
+    // per-query scalars
+    int32_t qq;           // U8: sum q^2
+    float lo, delta, qadd, qsumq;
+};
+
+template <int KIND, int T, int CPL, int QB>
+__device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const DistSrc& a, int64_t qi, int lig) {
+    const uint8_t* base = a.qrecs + qi * a.qrec_stride;
+    if constexpr (KIND == K_U8 || KIND == K_F32) {
+#pragma unroll
+        for (int j = 0; j < CPL; j++) {
+            int ch = lig + T * j;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (ch < a.nch) v = load16(base + (size_t)ch * 16);
+            q.w[4 * j + 0] = v.x;
+            q.w[4 * j + 1] = v.y;
+            q.w[4 * j + 2] = v.z;
+            q.w[4 * j + 3] = v.w;
+        }
+        if constexpr (KIND == K_U8) {
+            int32_t s = 0;
+#pragma unroll
+            for (int i = 0; i < 4 * CPL; i++) s = (int32_t)__builtin_amdgcn_udot4(q.w[i], q.w[i], (uint32_t)s, false);
+            q.qq = group_sum<T>(s);
+        }
+    } else {
+        constexpr int PL = QueryRegs<KIND, CPL, QB>::PLANES;
+        const float* hdr = reinterpret_cast<const float*>(base);
+        q.lo = hdr[0];
+        q.delta = hdr[1];
+        q.qadd = hdr[2];
+        q.qsumq = hdr[3];
+#pragma unroll
+        for (int p = 0; p < PL; p++) {
+#pragma unroll
+            for (int j = 0; j < CPL; j++) {
+                int ch = lig + T * j;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (ch < a.meta_chunk) v = load16(base + 16 + (size_t)p * a.qplane_stride + (size_t)ch * 16);
+                q.w[(p * CPL + j) * 4 + 0] = v.x;
+                q.w[(p * CPL + j) * 4 + 1] = v.y;
+                q.w[(p * CPL + j) * 4 + 2] = v.z;
+                q.w[(p * CPL + j) * 4 + 3] = v.w;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < CPL; j++) q.cmask[j] = (lig + T * j) < a.meta_chunk ? 0xFFFFFFFFu : 0u;
+    }
+}
+
+// Distance of the query to up to G*U records; result keys go to cand_key[].
+template <int KIND, int T, int CPL, int QB, int U>
+__device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, const DistSrc& a, int s0, int n_new,
+                                           const uint32_t* cand_id, uint64_t* cand_key, int g, int lig) {
+    constexpr int G = 64 / T;
+    uint4 data[U][CPL];
+    uint32_t ids[U];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        int c = s0 + u * G + g;
+        ids[u] = (c < n_new) ? cand_id[c] : JX_NONE_ID;
+    }
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+#pragma unroll
+        for (int j = 0; j < CPL; j++) {
+            int ch = lig + T * j;
+            data[u][j] = make_uint4(0, 0, 0, 0);
+            if (ids[u] != JX_NONE_ID && ch < a.nch)
+                data[u][j] = load16(a.recs + (size_t)ids[u] * (size_t)a.rec_stride + (size_t)ch * 16);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        int c = s0 + u * G + g;
+        // wave-uniform skip of batches that hold no candidate at all
+        if (s0 + u * G >= n_new) break;
+        uint32_t dist_code = 0;
+        bool writer = (lig == 0);
+        if constexpr (KIND == K_U8) {
+            uint32_t aa = 0, aq = 0;
+#pragma unroll
+            for (int j = 0; j < CPL; j++) {
+                const uint4 v = data[u][j];
+                aa = __builtin_amdgcn_udot4(v.x, v.x, aa, false);
+                aa = __builtin_amdgcn_udot4(v.y, v.y, aa, false);
+                aa = __builtin_amdgcn_udot4(v.z, v.z, aa, false);
+                aa = __builtin_amdgcn_udot4(v.w, v.w, aa, false);
+                aq = __builtin_amdgcn_udot4(v.x, q.w[4 * j + 0], aq, false);
+                aq = __builtin_amdgcn_udot4(v.y, q.w[4 * j + 1], aq, false);
+                aq = __builtin_amdgcn_udot4(v.z, q.w[4 * j + 2], aq, false);
+                aq = __builtin_amdgcn_udot4(v.w, q.w[4 * j + 3], aq, false);
+            }
+            int32_t part = (int32_t)aa - 2 * (int32_t)aq;
+            part = group_sum<T>(part);
+            dist_code = (uint32_t)(part + q.qq);
+        } else if constexpr (KIND == K_F32) {
+            float acc = 0.f;
+#pragma unroll
+            for (int j = 0; j < CPL; j++) {
+                const uint4 v = data[u][j];
+                float d0 = __uint_as_float(v.x) - __uint_as_float(q.w[4 * j + 0]);
+                float d1 = __uint_as_float(v.y) - __uint_as_float(q.w[4 * j + 1]);
+                float d2 = __uint_as_float(v.z) - __uint_as_float(q.w[4 * j + 2]);
+                float d3 = __uint_as_float(v.w) - __uint_as_float(q.w[4 * j + 3]);
+                acc = fmaf(d0, d0, acc);
+                acc = fmaf(d1, d1, acc);
+                acc = fmaf(d2, d2, acc);
+                acc = fmaf(d3, d3, acc);
+            }
+            acc = group_sum<T>(acc);
+            dist_code = f32_to_ordered(acc);
+        } else {
+            // RaBitQ estimator, integer-query form (Sec. 5.1): exact integer
+            // <u,q_int> and sum(u), then five float32 operations in a fixed order.
+            uint32_t I = 0, S = 0;
+            float m_add = 0.f, m_rescale = 0.f;
+            const int mj = a.meta_chunk / T, ml = a.meta_chunk % T;
+            writer = (lig == ml);
+#pragma unroll
+            for (int j = 0; j < CPL; j++) {
+                uint4 v = data[u][j];
+                if (j == mj) {
+                    m_add = __uint_as_float(v.x);
+                    m_rescale = __uint_as_float(v.y);
+                }
+                v.x &= q.cmask[j];
+                v.y &= q.cmask[j];
+                v.z &= q.cmask[j];
+                v.w &= q.cmask[j];
+                if constexpr (KIND == K_RQ4) {
+                    uint32_t ih = 0, il = 0;
+                    const uint32_t* qh = &q.w[(0 * CPL + j) * 4];
+                    const uint32_t* ql = &q.w[(1 * CPL + j) * 4];
+                    ih = __builtin_amdgcn_udot8(v.x, qh[0], ih, false);
+                    ih = __builtin_amdgcn_udot8(v.y, qh[1], ih, false);
+                    ih = __builtin_amdgcn_udot8(v.z, qh[2], ih, false);
+                    ih = __builtin_amdgcn_udot8(v.w, qh[3], ih, false);
+                    il = __builtin_amdgcn_udot8(v.x, ql[0], il, false);
+                    il = __builtin_amdgcn_udot8(v.y, ql[1], il, false);
+                    il = __builtin_amdgcn_udot8(v.z, ql[2], il, false);
+                    il = __builtin_amdgcn_udot8(v.w, ql[3], il, false);
+                    I += (QB == 8) ? (16u * ih + il) : il;
+                    S = __builtin_amdgcn_udot8(v.x, 0x11111111u, S, false);
+                    S = __builtin_amdgcn_udot8(v.y, 0x11111111u, S, false);
+                    S = __builtin_amdgcn_udot8(v.z, 0x11111111u, S, false);
+                    S = __builtin_amdgcn_udot8(v.w, 0x11111111u, S, false);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < QB; b++) {
+                        const uint32_t* qp = &q.w[(b * CPL + j) * 4];
+                        uint32_t cnt = __builtin_popcount(v.x & qp[0]) + __builtin_popcount(v.y & qp[1]) +
+                                       __builtin_popcount(v.z & qp[2]) + __builtin_popcount(v.w & qp[3]);
+                        I += cnt << b;
+                    }
+                    S += __builtin_popcount(v.x) + __builtin_popcount(v.y) + __builtin_popcount(v.z) +
+                         __builtin_popcount(v.w);
+                }
+            }
+            I = group_sum<T>(I);
+            S = group_sum<T>(S);
+            float t = __fmul_rn((float)I, q.delta);
+            float t2 = __fmul_rn(q.lo, (float)S);
+            t = __fadd_rn(t, t2);
+            t = __fsub_rn(t, q.qsumq);
+            float e = __fadd_rn(m_add, q.qadd);
+            float p = __fmul_rn(m_rescale, t);
+            e = __fadd_rn(e, p);
+            dist_code = f32_to_ordered(e);
+        }
+        if (writer && c < n_new) cand_key[c] = make_key(dist_code, ids[u]);
+    }
+}
+
+}  // namespace jx

@@ -9,9 +9,8 @@
 namespace jx {
 
 // ---- beamSearch -----------------------------------------------------------
-struct BeamArgs {
-    const uint32_t* adj;   // [N][R]
-    int R;
+// Where distances are taken: stored records and the records of the queries.
+struct DistSrc {
     const uint8_t* recs;   // records the distances are taken on
     long long rec_stride;  // bytes between records (multiple of 16)
     int nch;               // 16-byte chunks read per record
@@ -19,7 +18,14 @@ struct BeamArgs {
     const uint8_t* qrecs;  // per-query records
     long long qrec_stride;
     int qplane_stride;     // RaBitQ: bytes between the query's planes
+};
+
+struct BeamArgs {
+    const uint32_t* adj;   // [N][R]
+    int R;
+    DistSrc ds;
     long long nq;
+    long long q_skip;      // query i reads record i + (i >= q_skip); used by insertion to skip the entry point
     int L;
     uint32_t entry;
     int hash_log2;         // log2 of the visited-table size
@@ -29,6 +35,32 @@ struct BeamArgs {
     unsigned long long* stats;  // {hops, dist_evals} or NULL
 };
 hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st);
+
+// ---- batch insertion -------------------------------------------------------
+struct InsertArgs {
+    DistSrc ds;            // recs = qrecs = the vector store
+    uint32_t* adj;
+    int R, L;
+    float alpha;
+    long long B;           // points in this batch
+    long long id_base;     // id of batch element i = id_base + i (+1 if >= id_skip)
+    long long id_skip;
+    const uint32_t* cand_ids;   // [B][L]
+    const uint32_t* cand_dist;  // [B][L] float bits
+    uint8_t* dead;              // max(B*L, B*R) bytes
+    uint64_t* keys;             // [B*R] edge keys
+    uint32_t* vals;             // [B*R] edge sources
+    const uint32_t* heads;      // segment starts (reverse merge)
+    const uint32_t* nseg;       // number of segments (device)
+};
+
+hipError_t launch_entry_point(const void* vecs, int dtype, long long n, int d, double* partial, float* mean, double* dist,
+                              uint32_t* out_id, hipStream_t st);
+hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st);
+hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st);
+hipError_t launch_radix_sort(uint64_t* keys_a, uint32_t* vals_a, uint64_t* keys_b, uint32_t* vals_b, long long n, int nbits,
+                             uint32_t* table, hipStream_t st);
+hipError_t launch_segment_heads(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg, hipStream_t st);
 
 // ---- brute force ------------------------------------------------------------
 struct BfArgs {

@@ -1,0 +1,138 @@
+"""GPU parity: batch insertion (beamSearch candidates, robustPrune, reverse-edge
+merge) through the C ABI vs the CPU oracle.  Integer data must give the same
+adjacency bit for bit, rows in the same order."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_07048_amd import datagen
+from gpu_common import dev, u32, random_data
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def jx():
+    from paper_2601_07048_amd import jx as m
+    return m
+
+
+def _build_both(jx, x, R, L, calls=None, alpha=1.2):
+    n, d = x.shape
+    dt = jx.U8 if x.dtype == np.uint8 else jx.F32
+    calls = calls or [n]
+    ref = oracle.Index(d, x.dtype, R, L, alpha, n)
+    g = jx.Index(d, dt, R, L, alpha, capacity=n, max_batch=n)
+    pos = 0
+    for c in calls:
+        ref.insert(x[pos:pos + c])
+        g.insert(dev(x[pos:pos + c]))
+        pos += c
+    torch.cuda.synchronize()
+    return ref, g
+
+
+def _graphs(ref, g):
+    oadj, odeg = ref.graph()
+    adj, deg = g.export_graph()
+    return oadj, odeg, u32(adj), u32(deg)
+
+
+@pytest.mark.parametrize("n,d,R,L,calls", [
+    (5, 16, 2, 4, None),
+    (700, 32, 8, 16, None),
+    (3000, 128, 32, 64, None),
+    (3000, 128, 32, 64, [1, 1, 2, 996, 2000]),
+    (4000, 64, 16, 100, [1500, 2500]),
+    (2500, 128, 70, 130, None),      # R > 64: rows span two lane blocks
+])
+def test_insert_u8_graph_bit_exact(jx, n, d, R, L, calls):
+    x = random_data(n, d, np.uint8, seed=n + R)
+    ref, g = _build_both(jx, x, R, L, calls)
+    oadj, odeg, adj, deg = _graphs(ref, g)
+    assert g.size() == (n, ref.entry)
+    assert np.array_equal(deg, odeg)
+    bad = np.nonzero((adj != oadj).any(axis=1))[0]
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+
+
+def test_insert_u8_workload2_20k(jx):
+    """Workload-2 generator and parameters (R=64, L_build=128, alpha=1.2) at
+    N = 20,000, inserted in two calls."""
+    n = 20000
+    x = datagen.base(2, n)
+    ref, g = _build_both(jx, x, 64, 128, [12000, 8000])
+    oadj, odeg, adj, deg = _graphs(ref, g)
+    assert g.size() == (n, ref.entry)
+    assert np.array_equal(adj, oadj)
+    q = datagen.queries(2, 500)
+    ids, dist = g.search(dev(q), 10, 64)
+    want = ref.search(q, 10, 64)
+    assert np.array_equal(u32(ids), want["ids"])
+    gt, _ = g.bruteforce(dev(q), 10)
+    assert oracle.recall_at_k(u32(ids), u32(gt)) > 0.95
+
+
+def test_insert_duplicate_points_and_hub(jx):
+    """Many identical vectors: zero distances, ties broken by id, one hub that
+    receives far more reverse edges than R."""
+    rng = np.random.default_rng(3)
+    x = rng.integers(0, 256, (1200, 16), dtype=np.uint8)
+    x[200:700] = x[7]
+    ref, g = _build_both(jx, x, 6, 24)
+    oadj, odeg, adj, deg = _graphs(ref, g)
+    assert np.array_equal(adj, oadj)
+
+
+def test_insert_f32_dyadic_grid_bit_exact(jx):
+    """On a dyadic grid every float32 distance is exact, so the float path must
+    also reproduce the oracle's graph bit for bit."""
+    x = datagen.dyadic_grid(3000, 64, seed=11)
+    ref, g = _build_both(jx, x, 24, 48, [1000, 2000])
+    oadj, odeg, adj, deg = _graphs(ref, g)
+    assert g.size() == (3000, ref.entry)
+    assert np.array_equal(adj, oadj)
+
+
+def _invariants(adj, deg, n, R):
+    for i in range(n):
+        row = adj[i, :deg[i]]
+        assert (adj[i, deg[i]:] == 0xFFFFFFFF).all()
+        assert (row < n).all() and i not in row and len(set(row.tolist())) == len(row)
+
+
+def test_insert_f32_workload1(jx):
+    """Workload 1 (float32, N=10,000, R=32, L_build=64, seeded random order):
+    float distances differ from the oracle's double in the last bits, so the
+    graph is compared through its invariants and through recall, which must be
+    within 0.002 of the oracle-built graph's and at least 0.95 at L=64."""
+    n = 10000
+    x = datagen.base(1, n)[datagen.insertion_order(1, n)]
+    q = datagen.queries(1, 1000)
+    ref, g = _build_both(jx, x, 32, 64)
+    oadj, odeg, adj, deg = _graphs(ref, g)
+    _invariants(adj, deg, n, 32)
+    assert g.size() == (n, ref.entry)
+    assert (adj == oadj).all(axis=1).mean() > 0.95  # most rows are identical
+    gt, _ = oracle.bruteforce(x, q, 10)
+    ids, dist = g.search(dev(q), 10, 64)
+    r_gpu = oracle.recall_at_k(u32(ids), gt)
+    r_ref = oracle.recall_at_k(ref.search(q, 10, 64)["ids"], gt)
+    assert r_gpu >= 0.95 and abs(r_gpu - r_ref) <= 0.002, (r_gpu, r_ref)
+
+
+def test_insert_errors(jx):
+    x = random_data(100, 16, np.uint8, seed=1)
+    g = jx.Index(16, jx.U8, 4, 8, 1.2, capacity=64, max_batch=64)
+    with pytest.raises(jx.JxError) as e:
+        g.insert(dev(x))
+    assert e.value.code == -2  # capacity
+    g2 = jx.Index(16, jx.U8, 4, 8, 1.2, capacity=100, max_batch=8)
+    with pytest.raises(jx.JxError) as e:
+        g2.insert(dev(x))      # an internal batch would exceed max_batch
+    assert e.value.code == -2
+    g2.insert(dev(x[:9]))      # batches of 1,1,2,4 fit
+    assert g2.size()[0] == 9
+    g2.insert(dev(x[:0]))      # empty insert is a no-op
+    assert g2.size()[0] == 9
