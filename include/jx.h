@@ -77,7 +77,8 @@ typedef struct {
                           and largest number of queries processed at once
                           (larger query batches are processed in slices) */
     int32_t quant_bits; /* 0: never quantised; 1 or 4: reserve room for RaBitQ codes */
-    int32_t reserved;
+    float batch_growth; /* an internal insert batch holds at most max(1, floor(batch_growth * #linked))
+                           points; 0 selects the default 0.25 */
 } jx_params;
 
 /* Counters of one jx_search call, summed over its queries. */
@@ -109,8 +110,9 @@ int jx_destroy(jx_index* idx);
  * the first call picks the entry point = the point of that call nearest to the
  * call's coordinate-wise mean (the paper's "medoid"), which joins the graph
  * first with an empty row, (3) links the remaining points in id order in
- * internal batches of size min(remaining, number of points already linked), so
- * the linked set at most doubles per batch; each batch runs beamSearch
+ * internal batches of size min(remaining, max(1, floor(batch_growth * number of
+ * points already linked))) (Sec. 6.3 reports batches of 0.5 % to 32 % of the
+ * index as working); each batch runs beamSearch
  * (L_build, from the entry point, exact distances) for all its points against
  * the graph as it stood before the batch, robustPrune of the final frontier
  * (Alg. 3), emission of reverse edges to the kept neighbours only, one global

@@ -208,12 +208,13 @@ def rabitq_int_dot(code, bits, d, qint):
 class Index:
     """Vector store + Vamana graph built by batch insertion (Alg. 4)."""
 
-    def __init__(self, d, dtype, R, L_build, alpha, capacity, cand_mode=CAND_FRONTIER):
+    def __init__(self, d, dtype, R, L_build, alpha, capacity, cand_mode=CAND_FRONTIER, batch_growth=0.25):
         self.d, self.R, self.L_build, self.alpha, self.capacity = d, R, L_build, alpha, capacity
         self.np_dtype = np.dtype(dtype)
         self.dtype = U8 if self.np_dtype == np.uint8 else F32
         self._h = C.c_void_p(lib().orc_index_create(C.c_int(d), C.c_int(self.dtype), C.c_int(R), C.c_int(L_build),
-                                                    C.c_float(alpha), C.c_int64(capacity), C.c_int(cand_mode)))
+                                                    C.c_float(alpha), C.c_int64(capacity), C.c_int(cand_mode),
+                                                    C.c_float(batch_growth)))
         self.bits = 0
 
     def __del__(self):

@@ -390,6 +390,7 @@ int orc_robust_prune(uint32_t p_id, const uint32_t *cand_ids, const double *cand
 typedef struct orc_index {
     int d, dtype, R, L_build, cand_mode;
     float alpha;
+    float batch_growth; /* an internal batch holds at most max(1, floor(batch_growth * #linked)) points */
     int64_t capacity, n;
     uint32_t entry;
     void *base;    /* [capacity][d] */
@@ -402,7 +403,8 @@ typedef struct orc_index {
     float *meta;    /* [capacity][2] */
 } orc_index;
 
-orc_index *orc_index_create(int d, int dtype, int R, int L_build, float alpha, int64_t capacity, int cand_mode) {
+orc_index *orc_index_create(int d, int dtype, int R, int L_build, float alpha, int64_t capacity, int cand_mode,
+                            float batch_growth) {
     orc_index *x = (orc_index *)calloc(1, sizeof(orc_index));
     x->d = d;
     x->dtype = dtype;
@@ -411,6 +413,7 @@ orc_index *orc_index_create(int d, int dtype, int R, int L_build, float alpha, i
     x->alpha = alpha;
     x->capacity = capacity;
     x->cand_mode = cand_mode;
+    x->batch_growth = batch_growth;
     x->n = 0;
     x->entry = ORC_NONE;
     x->base = malloc((size_t)capacity * d * esize(dtype) + 16);
@@ -612,10 +615,15 @@ static void insert_subbatch(orc_index *x, const uint32_t *ids, int64_t B, int nt
  * against the float mean).  It joins the graph first, alone, with an empty row.
  *
  * Sub-batch schedule (the paper is silent on how a stream that starts empty is
- * bootstrapped): the remaining ids of the call, in increasing order, are cut
- * into sub-batches of size min(remaining, max(1, #points already linked)), so
- * the linked set at most doubles per sub-batch.
+ * bootstrapped; Sec. 6.3 reports batches of 0.5 % to 32 % of the index as
+ * working): the remaining ids of the call, in increasing order, are cut into
+ * sub-batches of size min(remaining, max(1, floor(batch_growth * #linked))).
  */
+static int64_t batch_cap(const orc_index *x, int64_t linked) {
+    int64_t c = (int64_t)floor((double)x->batch_growth * (double)linked);
+    return c < 1 ? 1 : c;
+}
+
 int orc_index_insert(orc_index *x, const void *vecs, int64_t n, int nthreads) {
     if (x->n + n > x->capacity) return -1;
     const int d = x->d;
@@ -657,7 +665,7 @@ int orc_index_insert(orc_index *x, const void *vecs, int64_t n, int nthreads) {
         int64_t linked = 1, pos = 0;
         while (pos < m) {
             int64_t B = m - pos;
-            if (B > linked) B = linked;
+            if (B > batch_cap(x, linked)) B = batch_cap(x, linked);
             insert_subbatch(x, ids + pos, B, nthreads);
             pos += B;
             linked += B;
@@ -671,8 +679,7 @@ int orc_index_insert(orc_index *x, const void *vecs, int64_t n, int nthreads) {
     while (pos < m) {
         int64_t linked = x->n;
         int64_t B = m - pos;
-        if (B > linked) B = linked;
-        if (B < 1) B = 1;
+        if (B > batch_cap(x, linked)) B = batch_cap(x, linked);
         insert_subbatch(x, ids + pos, B, nthreads); /* advances x->n by B */
         pos += B;
     }

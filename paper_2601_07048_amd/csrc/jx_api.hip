@@ -1,6 +1,7 @@
 // C ABI of libjx (see include/jx.h): argument checks, arena layout, phase
 // orchestration.  Every step of the path runs in the HIP kernels; nothing here
 // computes on the host except the tiny amount of control that needs a count.
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -51,6 +52,7 @@ int check_params(const jx_params* p) {
         return fail(JX_EINVAL, "quant_bits must be 0, 1 or 4");
     if (p->quant_bits && p->dtype != JX_F32) return fail(JX_EINVAL, "RaBitQ needs float32 data");
     if (p->quant_bits && p->dim % 32) return fail(JX_EINVAL, "RaBitQ needs dim to be a multiple of 32");
+    if (!(p->batch_growth >= 0.0f) || p->batch_growth > 1.0f) return fail(JX_EINVAL, "batch_growth must be in [0, 1]");
     return JX_OK;
 }
 
@@ -115,6 +117,12 @@ void layout(const jx_params* p, Layout* L) {
 
 }  // namespace
 namespace {
+int64_t batch_cap(const jx_params& p, int64_t linked) {
+    const float gr = p.batch_growth > 0.0f ? p.batch_growth : 0.25f;
+    int64_t c = (int64_t)floor((double)gr * (double)linked);
+    return c < 1 ? 1 : c;
+}
+
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 int hash_log2_for(int L) {
@@ -387,11 +395,11 @@ int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream) {
     const int64_t first = idx->n;
     if (first + n > p.capacity) return fail(JX_ECAPACITY, "%lld + %lld points exceed the capacity %lld", (long long)first, (long long)n, (long long)p.capacity);
     if (idx->quantized) return fail(JX_ESTATE, "insert into a quantised index is not available in this build");
-    // the internal batch schedule: min(remaining, points already linked)
+    // the internal batch schedule: min(remaining, max(1, floor(batch_growth * linked)))
     {
         int64_t linked = first == 0 ? 1 : first, rem = first == 0 ? n - 1 : n, maxB = 0;
         while (rem > 0) {
-            int64_t B = rem < linked ? rem : linked;
+            int64_t B = rem < batch_cap(p, linked) ? rem : batch_cap(p, linked);
             if (B > maxB) maxB = B;
             linked += B;
             rem -= B;
@@ -421,7 +429,7 @@ int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream) {
     }
     int64_t pos = 0;
     while (pos < m) {
-        int64_t B = m - pos < linked ? m - pos : linked;
+        int64_t B = m - pos < batch_cap(p, linked) ? m - pos : batch_cap(p, linked);
         int rc = run_subbatch(idx, w, pos, B, first, id_skip, first + n, st);
         if (rc) return rc;
         pos += B;

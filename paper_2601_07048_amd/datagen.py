@@ -30,7 +30,7 @@ SEED0 = 20260107
 
 _SPEC = {
     1: dict(d=128, dtype=np.float32, comps=64, kind="iso", centre_std=1.0, sigma=0.3),
-    2: dict(d=128, dtype=np.uint8, comps=256, kind="u8", centre_mean=64.0, centre_std=24.0, sigma=18.0),
+    2: dict(d=128, dtype=np.uint8, comps=256, kind="u8", centre_mean=64.0, centre_std=24.0, sigma=18.0, decay=1.25),
     3: dict(d=960, dtype=np.float32, comps=128, kind="aniso", centre_std=0.25, sigma=0.3, decay=0.5, normalise=False),
     4: dict(d=1536, dtype=np.float32, comps=512, kind="aniso", centre_std=0.25, sigma=0.3, decay=1.0, normalise=True),
 }
@@ -74,7 +74,7 @@ def _params(workload: int) -> dict:
         p["centres"] = sp["centre_mean"] + sp["centre_std"] * rng.standard_normal((c, d))
     else:
         p["centres"] = sp["centre_std"] * rng.standard_normal((c, d))
-    if sp["kind"] == "aniso":
+    if sp["kind"] == "aniso" or sp.get("decay", 0.0) > 0.0:
         lam = np.arange(1, d + 1, dtype=np.float64) ** (-sp["decay"])
         lam *= (sp["sigma"] ** 2) / lam.mean()
         u = random_orthogonal(d, _seed(key) + 4242)
@@ -99,7 +99,7 @@ def _chunk(workload: int, stream: str, chunk_idx: int) -> np.ndarray:
         x = mu + sp["sigma"] * z
         return x.astype(np.float32)
     if sp["kind"] == "u8":
-        x = mu + sp["sigma"] * z
+        x = mu + (z @ p["mix"] if "mix" in p else sp["sigma"] * z)
         return np.clip(np.rint(x), 0, 255).astype(np.uint8)
     x = mu.astype(np.float32) + z @ p["mix"]
     if sp["normalise"]:

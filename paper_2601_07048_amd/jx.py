@@ -32,7 +32,7 @@ class Params(C.Structure):
     _fields_ = [
         ("dim", C.c_int32), ("dtype", C.c_int32), ("R", C.c_int32), ("L_build", C.c_int32), ("alpha", C.c_float),
         ("cand_mode", C.c_int32), ("capacity", C.c_int64), ("max_batch", C.c_int64), ("quant_bits", C.c_int32),
-        ("reserved", C.c_int32),
+        ("batch_growth", C.c_float),
     ]
 
 
@@ -96,9 +96,10 @@ def jx_arena_bytes(params: Params) -> int:
 class Index:
     """Owns the arena tensor and the opaque handle; methods mirror the C ABI."""
 
-    def __init__(self, dim, dtype, R, L_build, alpha=1.2, capacity=0, max_batch=0, quant_bits=0, device="cuda:0"):
+    def __init__(self, dim, dtype, R, L_build, alpha=1.2, capacity=0, max_batch=0, quant_bits=0, batch_growth=0.25,
+                 device="cuda:0"):
         self.params = Params(dim=dim, dtype=dtype, R=R, L_build=L_build, alpha=alpha, cand_mode=CAND_FRONTIER,
-                             capacity=capacity, max_batch=max_batch or capacity, quant_bits=quant_bits, reserved=0)
+                             capacity=capacity, max_batch=max_batch or capacity, quant_bits=quant_bits, batch_growth=batch_growth)
         self.device = torch.device(device)
         self.dim, self.dtype, self.R = dim, dtype, R
         nbytes = jx_arena_bytes(self.params)

@@ -18,12 +18,12 @@ def jx():
     return m
 
 
-def _build_both(jx, x, R, L, calls=None, alpha=1.2):
+def _build_both(jx, x, R, L, calls=None, alpha=1.2, growth=0.25):
     n, d = x.shape
     dt = jx.U8 if x.dtype == np.uint8 else jx.F32
     calls = calls or [n]
-    ref = oracle.Index(d, x.dtype, R, L, alpha, n)
-    g = jx.Index(d, dt, R, L, alpha, capacity=n, max_batch=n)
+    ref = oracle.Index(d, x.dtype, R, L, alpha, n, batch_growth=growth)
+    g = jx.Index(d, dt, R, L, alpha, capacity=n, max_batch=n, batch_growth=growth)
     pos = 0
     for c in calls:
         ref.insert(x[pos:pos + c])
@@ -39,17 +39,18 @@ def _graphs(ref, g):
     return oadj, odeg, u32(adj), u32(deg)
 
 
-@pytest.mark.parametrize("n,d,R,L,calls", [
-    (5, 16, 2, 4, None),
-    (700, 32, 8, 16, None),
-    (3000, 128, 32, 64, None),
-    (3000, 128, 32, 64, [1, 1, 2, 996, 2000]),
-    (4000, 64, 16, 100, [1500, 2500]),
-    (2500, 128, 70, 130, None),      # R > 64: rows span two lane blocks
+@pytest.mark.parametrize("n,d,R,L,calls,growth", [
+    (5, 16, 2, 4, None, 1.0),
+    (700, 32, 8, 16, None, 0.25),
+    (3000, 128, 32, 64, None, 0.25),
+    (3000, 128, 32, 64, None, 1.0),
+    (3000, 128, 32, 64, [1, 1, 2, 996, 2000], 0.5),
+    (4000, 64, 16, 100, [1500, 2500], 0.25),
+    (2500, 128, 70, 130, None, 0.3),      # R > 64: rows span two lane blocks
 ])
-def test_insert_u8_graph_bit_exact(jx, n, d, R, L, calls):
+def test_insert_u8_graph_bit_exact(jx, n, d, R, L, calls, growth):
     x = random_data(n, d, np.uint8, seed=n + R)
-    ref, g = _build_both(jx, x, R, L, calls)
+    ref, g = _build_both(jx, x, R, L, calls, growth=growth)
     oadj, odeg, adj, deg = _graphs(ref, g)
     assert g.size() == (n, ref.entry)
     assert np.array_equal(deg, odeg)
@@ -128,7 +129,7 @@ def test_insert_errors(jx):
     with pytest.raises(jx.JxError) as e:
         g.insert(dev(x))
     assert e.value.code == -2  # capacity
-    g2 = jx.Index(16, jx.U8, 4, 8, 1.2, capacity=100, max_batch=8)
+    g2 = jx.Index(16, jx.U8, 4, 8, 1.2, capacity=100, max_batch=4, batch_growth=1.0)
     with pytest.raises(jx.JxError) as e:
         g2.insert(dev(x))      # an internal batch would exceed max_batch
     assert e.value.code == -2

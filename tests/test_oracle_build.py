@@ -101,7 +101,7 @@ def test_insert_1d_golden(golden_dir):
     base = np.zeros((5, 4), np.float32)
     base[:, 0] = [0, 10, 4, 5, 20]
     for nt in (1, 3):
-        ix = oracle.Index(4, np.float32, 2, 4, 1.2, 8)
+        ix = oracle.Index(4, np.float32, 2, 4, 1.2, 8, batch_growth=1.0)
         ix.insert(base, nthreads=nt)
         adj, deg = ix.graph()
         assert ix.entry == entry and ix.n == 5
