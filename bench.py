@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--recall", type=float, default=0.95)
     ap.add_argument("--L", type=int, default=0, help="force the beam width (0 = smallest with recall >= target)")
     ap.add_argument("--cpu-queries", type=int, default=2000, help="sample size of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; every figure is single-GPU throughput (use --gpus 1)")
@@ -112,6 +114,13 @@ def main():
     avg_ms = sum(kern_ms) / len(kern_ms)
     ms_per_step = wall * 1e3 / args.steps
     qps = nq * args.steps / wall
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # algorithmic bytes of one launch: adjacency rows + gathered vectors + queries in + results out
     alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * d + nq * k * 8
