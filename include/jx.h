@@ -187,6 +187,12 @@ int jx_import_graph(jx_index* idx, const void* d_vecs, int64_t n, const uint32_t
  * vector (d_meta [N][2]) and the centroid (d_centroid [dim], may be NULL). */
 int jx_export_codes(jx_index* idx, uint8_t* d_codes, float* d_meta, float* d_centroid, void* stream);
 
+/* Install codes produced elsewhere (d_codes [N][dim*bits/8] unpadded, d_meta
+ * [N][2]) together with the rotation and centroid they were made with; the
+ * counterpart of jx_export_codes.  Lets a test search on injected codes. */
+int jx_import_codes(jx_index* idx, int32_t bits, const float* d_rotation, const float* d_centroid, int32_t query_bits,
+                    const uint8_t* d_codes, const float* d_meta, void* stream);
+
 /* Stage entry points of the RaBitQ pipeline (Sec. 5.1), used to test each
  * stage against injected inputs.
  *   jx_rotate: d_out[n][dim] = (d_in[n][dim] - c) P^T with the index's frozen

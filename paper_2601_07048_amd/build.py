@@ -22,6 +22,9 @@ LIB = os.path.join(HERE, "libjx.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
+    # no implicit fused multiply-add: the estimator, the alpha test and the code
+    # decisions are specified as separate float32 operations (explicit fmaf stays fused)
+    "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
 ]

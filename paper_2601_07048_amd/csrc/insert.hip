@@ -481,6 +481,19 @@ hipError_t launch_entry_point(const void* vecs, int dtype, long long n, int d, d
     return hipGetLastError();
 }
 
+// column means only (two-stage, fixed order): the RaBitQ centroid
+hipError_t launch_column_mean(const void* vecs, int dtype, long long n, int d, double* partial, float* mean, hipStream_t st) {
+    int nblk = (int)((n + 255) / 256);
+    if (nblk > 512) nblk = 512;
+    if (nblk < 1) nblk = 1;
+    if (dtype == JX_U8)
+        hipLaunchKernelGGL(col_partial_kernel<JX_U8>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
+    else
+        hipLaunchKernelGGL(col_partial_kernel<JX_F32>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
+    hipLaunchKernelGGL(mean_finalize_kernel, dim3((d + 255) / 256), dim3(256), 0, st, partial, nblk, d, n, mean);
+    return hipGetLastError();
+}
+
 int entry_point_partial_blocks(long long n) {
     long long nblk = (n + 255) / 256;
     return (int)(nblk > 512 ? 512 : (nblk < 1 ? 1 : nblk));

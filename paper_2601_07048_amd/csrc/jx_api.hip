@@ -82,6 +82,30 @@ int64_t insert_work(const jx_params* p, int64_t B, InsertWork* w) {
     return off;
 }
 
+// Workspace of the query phase (RaBitQ mode) for slices of at most B queries.
+struct QueryWork {
+    int64_t rot, qrecs, fr_ids, fr_dist, total;
+    int plane_stride, qrec_stride_max;
+};
+
+int64_t query_work(const jx_params* p, int64_t B, int meta_chunk, QueryWork* w) {
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) { int64_t o = off; off += align256(bytes); return o; };
+    w->plane_stride = meta_chunk * 16;
+    w->qrec_stride_max = 16 + (p->quant_bits == 4 ? 2 : 8) * w->plane_stride;
+    if (!p->quant_bits) {
+        w->rot = w->qrecs = w->fr_ids = w->fr_dist = 0;
+        w->total = 0;
+        return 0;
+    }
+    w->rot = take(B * p->dim * 4);
+    w->qrecs = take(B * (int64_t)w->qrec_stride_max);
+    w->fr_ids = take(B * JX_MAX_L * 4);
+    w->fr_dist = take(B * JX_MAX_L * 4);
+    w->total = off;
+    return off;
+}
+
 void layout(const jx_params* p, Layout* L) {
     L->vec_bytes = p->dim * (p->dtype == JX_U8 ? 1 : 4);
     L->code_bytes = p->quant_bits ? p->dim * p->quant_bits / 8 : 0;
@@ -104,9 +128,10 @@ void layout(const jx_params* p, Layout* L) {
     const int64_t B = p->max_batch;
     InsertWork iw;
     int64_t ins = insert_work(p, B, &iw);
-    int64_t qry = align256(B * p->dim * 4)                              // rotated queries
-                  + align256(B * ((int64_t)p->dim + 64) * 2)            // integer query records
-                  + align256(B * JX_MAX_L * 4) * 2;                     // frontier ids / distances for re-rank
+    QueryWork qw;
+    int64_t qry = query_work(p, B, L->meta_chunk, &qw);
+    int64_t qnt = align256((int64_t)512 * p->dim * 8) + align256((int64_t)p->dim * 4 * 1024);  // centroid + >= 1024 rotated rows
+    if (p->quant_bits && qnt > qry) qry = qnt;
     int64_t w = ins > qry ? ins : qry;
     if (w < (64 << 20)) w = 64 << 20;
     L->work = off;
@@ -229,60 +254,124 @@ int jx_export_graph(jx_index* idx, uint32_t* d_adj, uint32_t* d_deg, void* strea
     return JX_OK;
 }
 
+static void fill_exact_src(const jx_index* idx, jx::DistSrc* ds, const void* queries) {
+    memset(ds, 0, sizeof *ds);
+    ds->recs = idx->d_vecs;
+    ds->rec_stride = idx->vec_bytes;
+    ds->nch = idx->vec_bytes / 16;
+    ds->qrecs = (const uint8_t*)queries;
+    ds->qrec_stride = idx->vec_bytes;
+}
+
 static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32_t out_k, int32_t L, int32_t mode,
-                         uint32_t* d_out_ids, float* d_out_dist, jx_stats* h_stats, hipStream_t st) {
+                         int32_t rerank, uint32_t* d_out_ids, float* d_out_dist, jx_stats* h_stats, hipStream_t st) {
     if (!idx) return fail(JX_EINVAL, "index is NULL");
     if (nq < 0) return fail(JX_EINVAL, "nq < 0");
     if (nq > 0 && (!d_queries || !d_out_ids || !d_out_dist)) return fail(JX_EINVAL, "NULL argument");
     if (L < 1 || L > JX_MAX_L) return fail(JX_EINVAL, "L must be in [1, %d]", JX_MAX_L);
     if (out_k < 1 || out_k > L) return fail(JX_EINVAL, "k must be in [1, L]");
+    if (rerank != 0 && (rerank < out_k || rerank > L)) return fail(JX_EINVAL, "rerank must be 0 or in [k, L]");
     if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
     if (mode != JX_EXACT && mode != JX_RABITQ) return fail(JX_EINVAL, "unknown mode");
-    if (mode == JX_RABITQ) return fail(JX_ESTATE, "index is not quantised");
+    if (mode == JX_RABITQ && !idx->quantized) return fail(JX_ESTATE, "index is not quantised");
     if (nq == 0) return JX_OK;
+    const jx_params& p = idx->p;
     if (h_stats) JX_HIP(jx::launch_fill_u32((uint32_t*)idx->d_stats, 16, 0u, st));
     jx::BeamArgs a;
     memset(&a, 0, sizeof a);
     a.adj = idx->d_adj;
-    a.R = idx->p.R;
-    a.ds.recs = idx->d_vecs;
-    a.ds.rec_stride = idx->vec_bytes;
-    a.ds.nch = idx->vec_bytes / 16;
-    a.ds.meta_chunk = 0;
-    a.ds.qrecs = (const uint8_t*)d_queries;
-    a.ds.qrec_stride = idx->vec_bytes;
-    a.nq = nq;
+    a.R = p.R;
     a.q_skip = 0x7FFFFFFFFFFFFFFFLL;
     a.L = L;
     a.entry = idx->entry;
     a.hash_log2 = hash_log2_for(L);
-    a.out_ids = d_out_ids;
-    a.out_dist = d_out_dist;
-    a.out_k = out_k;
     a.stats = h_stats ? idx->d_stats : nullptr;
-    JX_HIP(jx::launch_beam_search(idx->p.dtype == JX_U8 ? 0 : 1, 0, a, st));
+    if (mode == JX_EXACT) {
+        // distances are already exact: a re-rank would change nothing
+        fill_exact_src(idx, &a.ds, d_queries);
+        a.nq = nq;
+        a.out_ids = d_out_ids;
+        a.out_dist = d_out_dist;
+        a.out_k = out_k;
+        JX_HIP(jx::launch_beam_search(p.dtype == JX_U8 ? 0 : 1, 0, a, st));
+    } else {
+        QueryWork qw;
+        query_work(&p, p.max_batch, idx->meta_chunk, &qw);
+        uint8_t* W = idx->d_work;
+        const int nplanes = idx->quantized == 4 ? 2 : idx->qbits;
+        const int qrec_stride = 16 + nplanes * qw.plane_stride;
+        for (int64_t q0 = 0; q0 < nq; q0 += p.max_batch) {
+            const int64_t m = nq - q0 < p.max_batch ? nq - q0 : p.max_batch;
+            const float* qs = (const float*)d_queries + (size_t)q0 * p.dim;
+            JX_HIP(jx::launch_rotate(qs, m, p.dim, idx->d_P, idx->d_centroid, (float*)(W + qw.rot), st));
+            jx::QueryPrepArgs qp;
+            memset(&qp, 0, sizeof qp);
+            qp.rot = (const float*)(W + qw.rot);
+            qp.nq = m;
+            qp.d = p.dim;
+            qp.bits = idx->quantized;
+            qp.qbits = idx->qbits;
+            qp.qrecs = W + qw.qrecs;
+            qp.qrec_stride = qrec_stride;
+            qp.plane_stride = qw.plane_stride;
+            JX_HIP(jx::launch_query_prep(qp, st));
+            memset(&a.ds, 0, sizeof a.ds);
+            a.ds.recs = idx->d_codes;
+            a.ds.rec_stride = idx->code_stride;
+            a.ds.nch = idx->meta_chunk + 1;
+            a.ds.meta_chunk = idx->meta_chunk;
+            a.ds.qrecs = W + qw.qrecs;
+            a.ds.qrec_stride = qrec_stride;
+            a.ds.qplane_stride = qw.plane_stride;
+            a.nq = m;
+            if (rerank) {
+                a.out_ids = (uint32_t*)(W + qw.fr_ids);
+                a.out_dist = (float*)(W + qw.fr_dist);
+                a.out_k = rerank;
+            } else {
+                a.out_ids = d_out_ids + (size_t)q0 * out_k;
+                a.out_dist = d_out_dist + (size_t)q0 * out_k;
+                a.out_k = out_k;
+            }
+            JX_HIP(jx::launch_beam_search(idx->quantized == 4 ? 2 : 3, idx->qbits, a, st));
+            if (rerank) {
+                jx::RerankArgs r;
+                memset(&r, 0, sizeof r);
+                fill_exact_src(idx, &r.ds, qs);
+                r.nq = m;
+                r.cand = (const uint32_t*)(W + qw.fr_ids);
+                r.cand_stride = rerank;
+                r.rr = rerank;
+                r.k = out_k;
+                r.out_ids = d_out_ids + (size_t)q0 * out_k;
+                r.out_dist = d_out_dist + (size_t)q0 * out_k;
+                r.stats = h_stats ? idx->d_stats : nullptr;
+                JX_HIP(jx::launch_rerank(p.dtype, r, st));
+            }
+        }
+    }
     if (h_stats) {
-        unsigned long long hs[2];
+        unsigned long long hs[3];
         JX_HIP(hipMemcpyAsync(hs, idx->d_stats, sizeof hs, hipMemcpyDeviceToHost, st));
         JX_HIP(hipStreamSynchronize(st));
         memset(h_stats, 0, sizeof *h_stats);
         h_stats->hops = hs[0];
         h_stats->dist_evals = hs[1];
-        h_stats->adj_bytes = hs[0] * 4ull * idx->p.R;
-        h_stats->vec_bytes = hs[1] * (unsigned long long)idx->vec_bytes;
+        h_stats->adj_bytes = hs[0] * 4ull * p.R;
+        h_stats->vec_bytes = hs[1] * (unsigned long long)(mode == JX_EXACT ? idx->vec_bytes : idx->code_stride);
+        h_stats->rerank_bytes = hs[2] * (unsigned long long)idx->vec_bytes;
     }
     return JX_OK;
 }
 
 int jx_search(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, int32_t L, int32_t mode, int32_t rerank,
               uint32_t* d_out_ids, float* d_out_dist, jx_stats* h_stats, void* stream) {
-    if (rerank != 0 && (rerank < k || rerank > L)) return fail(JX_EINVAL, "rerank must be 0 or in [k, L]");
-    return search_common(idx, d_queries, nq, k, L, mode, d_out_ids, d_out_dist, h_stats, as_stream(stream));
+    return search_common(idx, d_queries, nq, k, L, mode, rerank, d_out_ids, d_out_dist, h_stats, as_stream(stream));
 }
 
 int jx_beam_frontier(jx_index* idx, const void* d_queries, int64_t nq, int32_t L, int32_t mode, uint32_t* d_out_ids,
                      float* d_out_dist, jx_stats* h_stats, void* stream) {
-    return search_common(idx, d_queries, nq, L, L, mode, d_out_ids, d_out_dist, h_stats, as_stream(stream));
+    return search_common(idx, d_queries, nq, L, L, mode, 0, d_out_ids, d_out_dist, h_stats, as_stream(stream));
 }
 
 int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, uint32_t* d_out_ids, float* d_out_dist,
@@ -324,6 +413,8 @@ int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, u
     }
     return JX_OK;
 }
+
+static int encode_range(jx_index* idx, int64_t first, int64_t count, hipStream_t st);
 
 static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_t B, int64_t first, int64_t id_skip,
                         int64_t n_after, hipStream_t st) {
@@ -394,7 +485,6 @@ int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream) {
     const jx_params& p = idx->p;
     const int64_t first = idx->n;
     if (first + n > p.capacity) return fail(JX_ECAPACITY, "%lld + %lld points exceed the capacity %lld", (long long)first, (long long)n, (long long)p.capacity);
-    if (idx->quantized) return fail(JX_ESTATE, "insert into a quantised index is not available in this build");
     // the internal batch schedule: min(remaining, max(1, floor(batch_growth * linked)))
     {
         int64_t linked = first == 0 ? 1 : first, rem = first == 0 ? n - 1 : n, maxB = 0;
@@ -436,28 +526,124 @@ int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream) {
         linked += B;
     }
     idx->n = first + n;
+    if (idx->quantized) return encode_range(idx, first, n, st);  // new points get codes with the frozen P and c
+    return JX_OK;
+}
+
+// rotate + encode vectors [first, first+count) of the store into their records
+static int encode_range(jx_index* idx, int64_t first, int64_t count, hipStream_t st) {
+    const jx_params& p = idx->p;
+    uint8_t* W = idx->d_work;
+    const int64_t part = align256((int64_t)512 * p.dim * 8);
+    int64_t slice = (idx->work_bytes - part) / ((int64_t)p.dim * 4);
+    if (slice < 1) return fail(JX_ECAPACITY, "workspace too small to encode");
+    float* rot = (float*)(W + part);
+    for (int64_t s0 = 0; s0 < count; s0 += slice) {
+        const int64_t m = count - s0 < slice ? count - s0 : slice;
+        const float* src = (const float*)(idx->d_vecs + (size_t)(first + s0) * idx->vec_bytes);
+        JX_HIP(jx::launch_rotate(src, m, p.dim, idx->d_P, idx->d_centroid, rot, st));
+        jx::EncodeArgs e;
+        memset(&e, 0, sizeof e);
+        e.rot = rot;
+        e.n = m;
+        e.d = p.dim;
+        e.bits = idx->quantized;
+        e.codes = idx->d_codes + (size_t)(first + s0) * idx->code_stride;
+        e.code_stride = idx->code_stride;
+        e.code_bytes = idx->code_bytes;
+        e.pad_to = idx->meta_chunk * 16;
+        e.meta = e.codes + (size_t)idx->meta_chunk * 16;
+        e.meta_stride = idx->code_stride;
+        e.meta_pad = 8;
+        JX_HIP(jx::launch_encode(e, st));
+    }
     return JX_OK;
 }
 
 int jx_quantize(jx_index* idx, int32_t bits, const float* d_rotation, const float* d_centroid, int32_t query_bits,
                 int32_t rule, void* stream) {
-    (void)idx; (void)bits; (void)d_rotation; (void)d_centroid; (void)query_bits; (void)rule; (void)stream;
-    return fail(JX_ESTATE, "jx_quantize: not available in this build");
+    if (!idx || !d_rotation) return fail(JX_EINVAL, "NULL argument");
+    const jx_params& p = idx->p;
+    if (!p.quant_bits) return fail(JX_ESTATE, "the index was created with quant_bits = 0");
+    if (bits != p.quant_bits) return fail(JX_EINVAL, "bits must equal params.quant_bits (%d)", p.quant_bits);
+    if (query_bits != 4 && query_bits != 8) return fail(JX_EINVAL, "query_bits must be 4 or 8");
+    if (rule != JX_RULE_MAXABS) return fail(JX_EINVAL, "only JX_RULE_MAXABS is supported");
+    if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
+    hipStream_t st = as_stream(stream);
+    JX_HIP(hipMemcpyAsync(idx->d_P, d_rotation, (size_t)p.dim * p.dim * 4, hipMemcpyDeviceToDevice, st));
+    if (d_centroid) {
+        JX_HIP(hipMemcpyAsync(idx->d_centroid, d_centroid, (size_t)p.dim * 4, hipMemcpyDeviceToDevice, st));
+    } else {
+        JX_HIP(jx::launch_column_mean(idx->d_vecs, p.dtype, idx->n, p.dim, (double*)idx->d_work, idx->d_centroid, st));
+    }
+    idx->quantized = bits;
+    idx->qbits = query_bits;
+    idx->rule = rule;
+    int rc = encode_range(idx, 0, idx->n, st);
+    if (rc) idx->quantized = 0;
+    return rc;
 }
 
 int jx_export_codes(jx_index* idx, uint8_t* d_codes, float* d_meta, float* d_centroid, void* stream) {
-    (void)idx; (void)d_codes; (void)d_meta; (void)d_centroid; (void)stream;
-    return fail(JX_ESTATE, "index is not quantised");
+    if (!idx || !d_codes || !d_meta) return fail(JX_EINVAL, "NULL argument");
+    if (!idx->quantized) return fail(JX_ESTATE, "index is not quantised");
+    hipStream_t st = as_stream(stream);
+    JX_HIP(jx::launch_unpack_records(idx->d_codes, idx->n, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, d_codes,
+                                     d_meta, st));
+    if (d_centroid)
+        JX_HIP(hipMemcpyAsync(d_centroid, idx->d_centroid, (size_t)idx->p.dim * 4, hipMemcpyDeviceToDevice, st));
+    return JX_OK;
+}
+
+int jx_import_codes(jx_index* idx, int32_t bits, const float* d_rotation, const float* d_centroid, int32_t query_bits,
+                    const uint8_t* d_codes, const float* d_meta, void* stream) {
+    if (!idx || !d_rotation || !d_centroid || !d_codes || !d_meta) return fail(JX_EINVAL, "NULL argument");
+    const jx_params& p = idx->p;
+    if (!p.quant_bits) return fail(JX_ESTATE, "the index was created with quant_bits = 0");
+    if (bits != p.quant_bits) return fail(JX_EINVAL, "bits must equal params.quant_bits (%d)", p.quant_bits);
+    if (query_bits != 4 && query_bits != 8) return fail(JX_EINVAL, "query_bits must be 4 or 8");
+    if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
+    hipStream_t st = as_stream(stream);
+    JX_HIP(hipMemcpyAsync(idx->d_P, d_rotation, (size_t)p.dim * p.dim * 4, hipMemcpyDeviceToDevice, st));
+    JX_HIP(hipMemcpyAsync(idx->d_centroid, d_centroid, (size_t)p.dim * 4, hipMemcpyDeviceToDevice, st));
+    JX_HIP(jx::launch_pack_records(idx->d_codes, idx->n, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, d_codes, d_meta, st));
+    idx->quantized = bits;
+    idx->qbits = query_bits;
+    idx->rule = JX_RULE_MAXABS;
+    return JX_OK;
 }
 
 int jx_rotate(jx_index* idx, const float* d_in, int64_t n, float* d_out, void* stream) {
-    (void)idx; (void)d_in; (void)n; (void)d_out; (void)stream;
-    return fail(JX_ESTATE, "index is not quantised");
+    if (!idx) return fail(JX_EINVAL, "index is NULL");
+    if (!idx->quantized) return fail(JX_ESTATE, "index is not quantised");
+    if (n < 0) return fail(JX_EINVAL, "n < 0");
+    if (n == 0) return JX_OK;
+    if (!d_in || !d_out) return fail(JX_EINVAL, "NULL argument");
+    JX_HIP(jx::launch_rotate(d_in, n, idx->p.dim, idx->d_P, idx->d_centroid, d_out, as_stream(stream)));
+    return JX_OK;
 }
 
 int jx_encode_rotated(jx_index* idx, const float* d_rot, int64_t n, uint8_t* d_codes, float* d_meta, void* stream) {
-    (void)idx; (void)d_rot; (void)n; (void)d_codes; (void)d_meta; (void)stream;
-    return fail(JX_ESTATE, "index is not quantised");
+    if (!idx) return fail(JX_EINVAL, "index is NULL");
+    if (!idx->quantized) return fail(JX_ESTATE, "index is not quantised");
+    if (n < 0) return fail(JX_EINVAL, "n < 0");
+    if (n == 0) return JX_OK;
+    if (!d_rot || !d_codes || !d_meta) return fail(JX_EINVAL, "NULL argument");
+    jx::EncodeArgs e;
+    memset(&e, 0, sizeof e);
+    e.rot = d_rot;
+    e.n = n;
+    e.d = idx->p.dim;
+    e.bits = idx->quantized;
+    e.codes = d_codes;
+    e.code_stride = idx->code_bytes;
+    e.code_bytes = idx->code_bytes;
+    e.pad_to = idx->code_bytes;
+    e.meta = (uint8_t*)d_meta;
+    e.meta_stride = 8;
+    e.meta_pad = 0;
+    JX_HIP(jx::launch_encode(e, as_stream(stream)));
+    return JX_OK;
 }
 
 }  // extern "C"

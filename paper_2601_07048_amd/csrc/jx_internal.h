@@ -62,6 +62,49 @@ hipError_t launch_radix_sort(uint64_t* keys_a, uint32_t* vals_a, uint64_t* keys_
                              uint32_t* table, hipStream_t st);
 hipError_t launch_segment_heads(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg, hipStream_t st);
 
+// ---- RaBitQ -----------------------------------------------------------------
+struct EncodeArgs {
+    const float* rot;   // [n][d]
+    long long n;
+    int d, bits;
+    uint8_t* codes;     // record i at codes + i*code_stride
+    long long code_stride;
+    int code_bytes;     // d*bits/8
+    int pad_to;         // bytes of the code area to zero-fill (>= code_bytes)
+    uint8_t* meta;      // two floats of vector i at meta + i*meta_stride
+    long long meta_stride;
+    int meta_pad;       // bytes after the two floats to zero-fill
+};
+
+struct QueryPrepArgs {
+    const float* rot;  // [nq][d] rotated, centred queries
+    long long nq;
+    int d, bits, qbits;
+    uint8_t* qrecs;    // [nq][qrec_stride]: 16-byte header {lo, delta, query_add, query_sumq}, then planes
+    long long qrec_stride;
+    int plane_stride;  // bytes per plane (multiple of 16)
+};
+
+struct RerankArgs {
+    DistSrc ds;              // recs = the float32 store, qrecs = the original queries
+    long long nq;
+    const uint32_t* cand;    // [nq][cand_stride] frontier ids (JX_NONE padded)
+    int cand_stride, rr, k;
+    uint32_t* out_ids;       // [nq][k]
+    float* out_dist;
+    unsigned long long* stats;  // [2] += number of vectors read
+};
+
+hipError_t launch_rotate(const float* in, long long n, int d, const float* P, const float* c, float* out, hipStream_t st);
+hipError_t launch_encode(const EncodeArgs& a, hipStream_t st);
+hipError_t launch_unpack_records(const uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,
+                                 uint8_t* codes, float* meta, hipStream_t st);
+hipError_t launch_pack_records(uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,
+                               const uint8_t* codes, const float* meta, hipStream_t st);
+hipError_t launch_query_prep(const QueryPrepArgs& a, hipStream_t st);
+hipError_t launch_rerank(int dtype, const RerankArgs& a, hipStream_t st);
+hipError_t launch_column_mean(const void* vecs, int dtype, long long n, int d, double* partial, float* mean, hipStream_t st);
+
 // ---- brute force ------------------------------------------------------------
 struct BfArgs {
     const void* base;

@@ -1,0 +1,387 @@
+// RaBitQ pipeline (Sec. 5.1): rotation GEMM on the matrix cores, encoder,
+// integer query records, exact re-rank.
+//
+//   rotate      out = (in - c) P^T   float32 MFMA (32x32x2), 128x128 tile per
+//               workgroup, 64x64 per wavefront, K staged through LDS in slabs
+//               of 32; the centroid is subtracted while staging.
+//   encode      one wavefront per vector: 1-bit codes via ballot, 4-bit codes
+//               with the max-abs grid scale; data_add, data_rescale in double.
+//   query prep  one wavefront per query: min/max, B_q-bit integer query,
+//               nibble planes (4-bit codes) or bit planes (1-bit codes).
+//   rerank      one wavefront per query: exact float32 squared L2 of the first
+//               `rerank` frontier entries against the original query, sorted by
+//               (distance, id).
+#include "jx_distance.h"
+
+namespace jx {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define GT 128
+#define GK 32
+#define GLD 36  // padded LDS row (floats)
+
+__global__ void __launch_bounds__(256) rotate_gemm_kernel(const float* __restrict__ in, long long n, int d,
+                                                          const float* __restrict__ P, const float* __restrict__ c,
+                                                          float* __restrict__ out) {
+    __shared__ __align__(16) float As[GT][GLD];
+    __shared__ __align__(16) float Bs[GT][GLD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const long long m0 = (long long)blockIdx.y * GT;
+    const int n0 = blockIdx.x * GT;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+    for (int k0 = 0; k0 < d; k0 += GK) {
+#pragma unroll
+        for (int t = 0; t < 4; t++) {
+            const int idx = tid + t * 256;
+            const int row = idx >> 3, c4 = (idx & 7) * 4;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            if (k0 + c4 < d) {
+                if (m0 + row < n) {
+                    const float4 v = *reinterpret_cast<const float4*>(in + (size_t)(m0 + row) * d + k0 + c4);
+                    const float4 cc = *reinterpret_cast<const float4*>(c + k0 + c4);
+                    a = make_float4(v.x - cc.x, v.y - cc.y, v.z - cc.z, v.w - cc.w);
+                }
+                if (n0 + row < d) b = *reinterpret_cast<const float4*>(P + (size_t)(n0 + row) * d + k0 + c4);
+            }
+            *reinterpret_cast<float4*>(&As[row][c4]) = a;
+            *reinterpret_cast<float4*>(&Bs[row][c4]) = b;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s8 = 0; s8 < GK / 8; s8++) {
+            float4 af[2], bf[2];
+#pragma unroll
+            for (int s = 0; s < 2; s++) {
+                af[s] = *reinterpret_cast<const float4*>(&As[wm * 64 + s * 32 + (lane & 31)][8 * s8 + 4 * (lane >> 5)]);
+                bf[s] = *reinterpret_cast<const float4*>(&Bs[wn * 64 + s * 32 + (lane & 31)][8 * s8 + 4 * (lane >> 5)]);
+            }
+#pragma unroll
+            for (int mi = 0; mi < 2; mi++)
+#pragma unroll
+                for (int ni = 0; ni < 2; ni++) {
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi].x, bf[ni].x, acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi].y, bf[ni].y, acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi].z, bf[ni].z, acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi].w, bf[ni].w, acc[mi][ni], 0, 0, 0);
+                }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int mi = 0; mi < 2; mi++)
+#pragma unroll
+        for (int ni = 0; ni < 2; ni++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const long long row = m0 + wm * 64 + mi * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const int col = n0 + wn * 64 + ni * 32 + (lane & 31);
+                if (row < n && col < d) out[(size_t)row * d + col] = acc[mi][ni][e];
+            }
+}
+
+hipError_t launch_rotate(const float* in, long long n, int d, const float* P, const float* c, float* out, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    dim3 grid((unsigned)((d + GT - 1) / GT), (unsigned)((n + GT - 1) / GT));
+    hipLaunchKernelGGL(rotate_gemm_kernel, grid, dim3(256), 0, st, in, n, d, P, c, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ encoder
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v += shfl_xor(v, m);
+    return v;
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, shfl_xor(v, m));
+    return v;
+}
+__device__ __forceinline__ float wave_min_f32(float v) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v = fminf(v, shfl_xor(v, m));
+    return v;
+}
+
+// Code layout: 1-bit: coordinate i is bit i%32 of dword i/32.  4-bit: coordinate i
+// is nibble i%8 of dword i/8 (so even coordinates sit in low nibbles of a byte).
+__global__ void __launch_bounds__(256) encode_kernel(EncodeArgs a) {
+    const long long v = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= a.n) return;
+    const int lane = lane_id();
+    const float* r = a.rot + (size_t)v * a.d;
+    uint8_t* code = a.codes + (size_t)v * a.code_stride;
+    double l2 = 0.0, ip = 0.0;
+    if (a.bits == 1) {
+        for (int c0 = 0; c0 < a.d; c0 += 64) {
+            const int i = c0 + lane;
+            const float x = i < a.d ? r[i] : -1.0f;
+            const bool pos = i < a.d && x >= 0.0f;
+            const uint64_t m = ballot(pos);
+            if (i < a.d) {
+                l2 += (double)x * (double)x;
+                ip += 0.5 * fabs((double)x);
+            }
+            if (lane == 0) *reinterpret_cast<uint32_t*>(code + c0 / 8) = (uint32_t)m;
+            if (lane == 1 && c0 + 32 < a.d) *reinterpret_cast<uint32_t*>(code + c0 / 8 + 4) = (uint32_t)(m >> 32);
+        }
+    } else {
+        const int half = 1 << (a.bits - 1);
+        float amax = 0.f;
+        for (int i = lane; i < a.d; i += 64) amax = fmaxf(amax, fabsf(r[i]));
+        amax = wave_max_f32(amax);
+        const float t = amax > 0.f ? __fdiv_rn((float)half - 0.5f, amax) : 0.f;
+        const double cb = ((double)(1 << a.bits) - 1.0) * 0.5;
+        // 8 consecutive coordinates per lane -> one dword of nibbles (bits == 4)
+        for (int c0 = 0; c0 < a.d; c0 += 512) {
+            const int i0 = c0 + lane * 8;
+            if (i0 < a.d) {
+                uint32_t w = 0;
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    const float x = r[i0 + j];
+                    float lvf = floorf(__fmul_rn(t, fabsf(x)));
+                    int lv = (int)lvf;
+                    lv = lv > half - 1 ? half - 1 : (lv < 0 ? 0 : lv);
+                    const int u = x >= 0.0f ? half + lv : half - 1 - lv;
+                    w |= (uint32_t)u << (4 * j);
+                    l2 += (double)x * (double)x;
+                    ip += ((double)u - cb) * (double)x;
+                }
+                *reinterpret_cast<uint32_t*>(code + i0 / 2) = w;
+            }
+        }
+    }
+    l2 = wave_sum_f64(l2);
+    ip = wave_sum_f64(ip);
+    for (int b = a.code_bytes + lane * 4; b < a.pad_to; b += 256) *reinterpret_cast<uint32_t*>(code + b) = 0u;
+    if (lane == 0) {
+        float* m = reinterpret_cast<float*>(a.meta + (size_t)v * a.meta_stride);
+        m[0] = l2 > 0.0 ? (float)l2 : 0.f;
+        m[1] = l2 > 0.0 ? (float)(-2.0 * l2 / ip) : 0.f;
+        for (int b = 0; b < a.meta_pad; b += 4) m[2 + b / 4] = 0.f;
+    }
+}
+
+hipError_t launch_encode(const EncodeArgs& a, hipStream_t st) {
+    if (a.n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(encode_kernel, dim3((unsigned)((a.n + 3) / 4)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// records -> unpadded codes + meta
+__global__ void __launch_bounds__(256) unpack_records_kernel(const uint8_t* recs, long long n, int code_stride, int code_bytes,
+                                                            int meta_off, uint8_t* codes, float* meta) {
+    const long long v = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const int lane = lane_id();
+    const uint8_t* rec = recs + (size_t)v * code_stride;
+    for (int b = lane * 4; b < code_bytes; b += 256)
+        *reinterpret_cast<uint32_t*>(codes + (size_t)v * code_bytes + b) = *reinterpret_cast<const uint32_t*>(rec + b);
+    if (lane < 2) meta[2 * v + lane] = reinterpret_cast<const float*>(rec + meta_off)[lane];
+}
+
+hipError_t launch_unpack_records(const uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,
+                                 uint8_t* codes, float* meta, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(unpack_records_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, recs, n, code_stride, code_bytes,
+                       meta_off, codes, meta);
+    return hipGetLastError();
+}
+
+// unpadded codes + meta -> records (padding zeroed)
+__global__ void __launch_bounds__(256) pack_records_kernel(uint8_t* recs, long long n, int code_stride, int code_bytes,
+                                                          int meta_off, const uint8_t* codes, const float* meta) {
+    const long long v = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const int lane = lane_id();
+    uint8_t* rec = recs + (size_t)v * code_stride;
+    for (int b = lane * 4; b < code_stride; b += 256) {
+        uint32_t w = 0;
+        if (b < code_bytes) w = *reinterpret_cast<const uint32_t*>(codes + (size_t)v * code_bytes + b);
+        else if (b == meta_off) w = __float_as_uint(meta[2 * v]);
+        else if (b == meta_off + 4) w = __float_as_uint(meta[2 * v + 1]);
+        *reinterpret_cast<uint32_t*>(rec + b) = w;
+    }
+}
+
+hipError_t launch_pack_records(uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,
+                               const uint8_t* codes, const float* meta, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(pack_records_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, recs, n, code_stride, code_bytes,
+                       meta_off, codes, meta);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ query records
+
+__global__ void __launch_bounds__(256) query_prep_kernel(QueryPrepArgs a) {
+    const long long qi = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (qi >= a.nq) return;
+    const int lane = lane_id();
+    const float* q = a.rot + (size_t)qi * a.d;
+    uint8_t* rec = a.qrecs + (size_t)qi * a.qrec_stride;
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+    double s = 0.0, s2 = 0.0;
+    for (int i = lane; i < a.d; i += 64) {
+        const float x = q[i];
+        lo = fminf(lo, x);
+        hi = fmaxf(hi, x);
+        s += (double)x;
+        s2 += (double)x * (double)x;
+    }
+    lo = wave_min_f32(lo);
+    hi = wave_max_f32(hi);
+    s = wave_sum_f64(s);
+    s2 = wave_sum_f64(s2);
+    const float levels = (float)((1 << a.qbits) - 1);
+    const float delta = __fdiv_rn(__fsub_rn(hi, lo), levels);
+    const double cb = ((double)(1 << a.bits) - 1.0) * 0.5;
+    if (lane == 0) {
+        float* hdr = reinterpret_cast<float*>(rec);
+        hdr[0] = lo;
+        hdr[1] = delta;
+        hdr[2] = (float)s2;
+        hdr[3] = (float)(cb * s);
+    }
+    const int nplanes = a.bits == 4 ? 2 : a.qbits;
+    // zero the padding of each plane (planes are whole 16-byte chunks)
+    const int written = a.bits == 4 ? a.d / 2 : a.d / 8;
+    for (int p = 0; p < nplanes; p++)
+        for (int b = written + lane * 4; b < a.plane_stride; b += 256)
+            *reinterpret_cast<uint32_t*>(rec + 16 + (size_t)p * a.plane_stride + b) = 0u;
+    auto quant = [&](float x) -> uint32_t {
+        if (!(delta > 0.f)) return 0u;
+        float t = __fdiv_rn(__fsub_rn(x, lo), delta);
+        t = floorf(__fadd_rn(t, 0.5f));
+        t = t < 0.f ? 0.f : (t > levels ? levels : t);
+        return (uint32_t)t;
+    };
+    if (a.bits == 4) {
+        // nibble planes: dword k holds coordinates 8k..8k+7; plane 0 = high nibbles, plane 1 = low nibbles
+        for (int c0 = 0; c0 < a.d; c0 += 512) {
+            const int i0 = c0 + lane * 8;
+            if (i0 < a.d) {
+                uint32_t wh = 0, wl = 0;
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    const uint32_t v = quant(q[i0 + j]);
+                    wh |= (v >> 4) << (4 * j);
+                    wl |= (v & 15u) << (4 * j);
+                }
+                *reinterpret_cast<uint32_t*>(rec + 16 + i0 / 2) = wh;
+                *reinterpret_cast<uint32_t*>(rec + 16 + a.plane_stride + i0 / 2) = wl;
+            }
+        }
+    } else {
+        // bit planes: plane b, dword k, bit j = bit b of q_int[32k + j]
+        for (int c0 = 0; c0 < a.d; c0 += 64) {
+            const int i = c0 + lane;
+            const uint32_t v = i < a.d ? quant(q[i]) : 0u;
+            for (int b = 0; b < a.qbits; b++) {
+                const uint64_t m = ballot(((v >> b) & 1u) != 0u);
+                if (lane == 0) *reinterpret_cast<uint32_t*>(rec + 16 + (size_t)b * a.plane_stride + c0 / 8) = (uint32_t)m;
+                if (lane == 1 && c0 + 32 < a.d)
+                    *reinterpret_cast<uint32_t*>(rec + 16 + (size_t)b * a.plane_stride + c0 / 8 + 4) = (uint32_t)(m >> 32);
+            }
+        }
+    }
+}
+
+hipError_t launch_query_prep(const QueryPrepArgs& a, hipStream_t st) {
+    if (a.nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(query_prep_kernel, dim3((unsigned)((a.nq + 3) / 4)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ exact re-rank
+
+struct RerankLds {
+    uint64_t key[JX_MAX_L];
+    uint64_t cand_key[64];
+    uint32_t cand_id[64];
+};
+
+template <int KIND, int T, int CPL>
+__global__ void __launch_bounds__(256) rerank_kernel(RerankArgs a) {
+    __shared__ RerankLds lds[4];
+    constexpr int G = 64 / T;
+    constexpr int U0 = (8 / CPL) > 0 ? (8 / CPL) : 1;
+    constexpr int U = U0 < (64 / G) ? U0 : (64 / G);
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const int g = lane / T, lig = lane % T;
+    const long long qi = (long long)blockIdx.x * 4 + wave;
+    if (qi >= a.nq) return;
+    RerankLds* L = &lds[wave];
+    QueryRegs<KIND, CPL, 0> q;
+    load_query<KIND, T, CPL, 0>(q, a.ds, qi, lig);
+    const uint32_t* cand = a.cand + (size_t)qi * a.cand_stride;
+    int m = 0;
+    for (int c0 = 0; c0 < a.rr; c0 += 64) {
+        const int j = c0 + lane;
+        const uint32_t id = j < a.rr ? cand[j] : JX_NONE_ID;
+        const uint64_t vm = ballot(id != JX_NONE_ID);
+        const int nn = __builtin_popcountll(vm);
+        if (nn == 0) break;  // the frontier is filled from the left
+        if (id != JX_NONE_ID) L->cand_id[prefix_count(vm)] = id;
+        wave_sync();
+        for (int s0 = 0; s0 < nn; s0 += G * U) eval_batch<KIND, T, CPL, 0, U>(q, a.ds, s0, nn, L->cand_id, L->cand_key, g, lig);
+        wave_sync();
+        if (lane < nn) L->key[m + lane] = L->cand_key[lane] | 1ull;
+        m += nn;
+        wave_sync();
+    }
+    // rank sort by (distance, id); write the first k, pad what is left
+    for (int j = m + lane; j < a.k; j += 64) {
+        a.out_ids[qi * a.k + j] = JX_NONE_ID;
+        a.out_dist[qi * a.k + j] = __builtin_inff();
+    }
+    for (int j = lane; j < m; j += 64) {
+        const uint64_t kj = L->key[j];
+        int rank = 0;
+        for (int t = 0; t < m; t++) rank += (L->key[t] < kj) ? 1 : 0;
+        if (rank < a.k) {
+            a.out_ids[qi * a.k + rank] = key_id(kj);
+            const uint32_t dc = key_dist(kj);
+            a.out_dist[qi * a.k + rank] = (KIND == K_U8) ? (float)dc : ordered_to_f32(dc);
+        }
+    }
+    if (a.stats && lane == 0) atomicAdd(&a.stats[2], (unsigned long long)m);
+}
+
+template <int KIND>
+static hipError_t launch_rerank_shape(const RerankArgs& a, hipStream_t st) {
+    dim3 grid((unsigned)((a.nq + 3) / 4)), block(256);
+    const int nch = a.ds.nch;
+#define JX_RR(T, C)                                                             \
+    {                                                                           \
+        hipLaunchKernelGGL((rerank_kernel<KIND, T, C>), grid, block, 0, st, a); \
+        return hipGetLastError();                                               \
+    }
+    if (nch <= 8) JX_RR(8, 1)
+    if (nch <= 16) JX_RR(16, 1)
+    if (nch <= 32) JX_RR(32, 1)
+    if (nch <= 64) JX_RR(64, 1)
+    if (nch <= 128) JX_RR(64, 2)
+    if (nch <= 256) JX_RR(64, 4)
+    if (nch <= 384) JX_RR(64, 6)
+#undef JX_RR
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_rerank(int dtype, const RerankArgs& a, hipStream_t st) {
+    if (a.nq <= 0) return hipSuccess;
+    return dtype == JX_U8 ? launch_rerank_shape<K_U8>(a, st) : launch_rerank_shape<K_F32>(a, st);
+}
+
+}  // namespace jx

@@ -23,7 +23,7 @@ MAX_L, MAX_R, MAX_BF_K = 512, 256, 128
 
 EXPORTS = [
     "jx_arena_bytes", "jx_create", "jx_destroy", "jx_insert", "jx_quantize", "jx_search", "jx_beam_frontier",
-    "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_rotate",
+    "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_import_codes", "jx_rotate",
     "jx_encode_rotated", "jx_strerror", "jx_last_error",
 ]
 
@@ -153,6 +153,13 @@ class Index:
         with torch.cuda.device(self.device):
             _check(_lib.jx_quantize(self._h, C.c_int32(bits), _ptr(rotation), _ptr(centroid), C.c_int32(query_bits),
                                     C.c_int32(rule), _stream()))
+        self.bits = bits
+
+    def import_codes(self, bits, rotation, centroid, codes, meta, query_bits=8):
+        assert codes.dtype == torch.uint8 and meta.dtype == torch.float32
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_import_codes(self._h, C.c_int32(bits), _ptr(rotation), _ptr(centroid), C.c_int32(query_bits),
+                                        _ptr(codes), _ptr(meta), _stream()))
         self.bits = bits
 
     def export_codes(self):

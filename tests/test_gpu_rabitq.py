@@ -1,0 +1,215 @@
+"""GPU parity of the RaBitQ pipeline (rotation GEMM, encoder, query records,
+estimated-distance beamSearch, exact re-rank) vs the CPU oracle, stage by stage
+with injected inputs and end to end."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_07048_amd import datagen
+from gpu_common import dev, u32, oracle_index, gpu_index_from_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def jx():
+    from paper_2601_07048_amd import jx as m
+    return m
+
+
+def _clustered(n, d, seed, comps=8):
+    rng = np.random.default_rng(seed)
+    cent = rng.standard_normal((comps, d)) * 0.5
+    lam = np.sqrt(np.arange(1, d + 1, dtype=np.float64) ** -0.5)
+    x = cent[rng.integers(0, comps, n)] + 0.3 * rng.standard_normal((n, d)) * lam
+    return x.astype(np.float32)
+
+
+def _signed_permutation(d, seed):
+    rng = np.random.default_rng(seed)
+    P = np.zeros((d, d), np.float32)
+    P[np.arange(d), rng.permutation(d)] = rng.choice([-1.0, 1.0], d)
+    return P
+
+
+@pytest.mark.parametrize("d,n", [(96, 300), (960, 257), (1536, 130)])
+def test_rotation_gemm(jx, d, n):
+    """(in - c) P^T on the matrix cores vs the double-precision rotation."""
+    rng = np.random.default_rng(d)
+    x = _clustered(n, d, d)
+    P = datagen.random_orthogonal(d, d + 1).astype(np.float32)
+    c = x.astype(np.float64).mean(0).astype(np.float32)
+    g = jx.Index(d, jx.F32, 8, 8, 1.2, capacity=n, quant_bits=1)
+    g.import_graph(dev(x), dev(np.full((n, 8), jx.NONE, np.uint32)), 0)
+    g.quantize(1, dev(P), dev(c))
+    got = g.rotate(dev(x)).cpu().numpy().astype(np.float64)
+    _, want = oracle.rabitq_rotate(x, P, c)
+    scale = np.abs(want).max()
+    assert np.abs(got - want).max() <= 2e-6 * scale * np.sqrt(d)
+    # a signed permutation with c = 0 must be reproduced exactly
+    Q = _signed_permutation(d, 3)
+    g.quantize(1, dev(Q), dev(np.zeros(d, np.float32)))
+    got = g.rotate(dev(x)).cpu().numpy()
+    assert np.array_equal(got, x @ Q.T)
+
+
+@pytest.mark.parametrize("bits,d", [(1, 1536), (4, 960), (1, 96), (4, 32), (4, 1536), (1, 960)])
+def test_encoder_on_injected_rotated_vectors(jx, bits, d):
+    """Encoder stage alone: fed with the oracle's float32 rotated vectors it must
+    emit the oracle's codes bit for bit (the decisions are float32 on both
+    sides) and the two floats to float rounding."""
+    n = 400
+    r32 = (_clustered(n, d, bits * 1000 + d) * np.float32(1.7)).astype(np.float32)
+    r32[3] = 0.0  # degenerate vector
+    r32[5, :7] = [0.0, -0.0, 1e-30, -1e-30, 5.0, -5.0, 0.25]
+    g = jx.Index(d, jx.F32, 8, 8, 1.2, capacity=n, quant_bits=bits)
+    g.import_graph(dev(r32), dev(np.full((n, 8), jx.NONE, np.uint32)), 0)
+    g.quantize(bits, dev(np.eye(d, dtype=np.float32)), dev(np.zeros(d, np.float32)))
+    codes, meta = g.encode_rotated(dev(r32))
+    wc, wm, _ = oracle.rabitq_encode(r32, bits, oracle.RULE_MAXABS)
+    assert np.array_equal(codes.cpu().numpy(), wc)
+    assert np.allclose(meta.cpu().numpy(), wm, rtol=2e-7, atol=0)
+    # with P = I and c = 0 the whole quantise call is the same computation
+    ec, em, cen = g.export_codes()
+    assert np.array_equal(ec.cpu().numpy(), wc) and np.allclose(em.cpu().numpy(), wm, rtol=2e-7, atol=0)
+    assert (cen.cpu().numpy() == 0).all()
+
+
+def _quantized_pair(jx, x, P, bits, qbits, R=24, L=48, centroid=None, inject=False):
+    ix = oracle_index(x, R, L)
+    ix.quantize(bits, P, centroid=centroid, qbits=qbits, rule=oracle.RULE_MAXABS)
+    g = gpu_index_from_oracle(jx, x, ix, R, L, quant_bits=bits)
+    if inject:
+        codes, meta, cen = ix.codes()
+        g.import_codes(bits, dev(P), dev(cen), dev(codes), dev(meta), query_bits=qbits)
+    else:
+        g.quantize(bits, dev(P), None if centroid is None else dev(centroid), query_bits=qbits)
+    return ix, g
+
+
+@pytest.mark.parametrize("bits,qbits,d", [(4, 8, 960), (1, 8, 1536), (4, 4, 128), (1, 4, 256), (1, 8, 96), (4, 8, 1536)])
+def test_estimated_beam_bit_exact_on_injected_codes(jx, bits, qbits, d):
+    """beamSearch + estimator stage: oracle codes injected, rotation a signed
+    permutation and c = 0 (so both sides see identical rotated queries).  The
+    integer inner products are exact and the five float operations are ordered
+    identically, so frontier ids AND estimated distances must be identical."""
+    n = 1500
+    x = _clustered(n, d, d + bits)
+    q = _clustered(60, d, d + bits + 1)
+    P = _signed_permutation(d, 5)
+    ix, g = _quantized_pair(jx, x, P, bits, qbits, centroid=np.zeros(d, np.float32), inject=True)
+    for L in (10, 50, 130):
+        ref = ix.search(q, 1, L, mode=1, want_frontier=True)
+        ids, dist, st = g.beam_frontier(dev(q), L, mode=jx.RABITQ, stats=True)
+        assert np.array_equal(u32(ids), ref["F_ids"])
+        assert np.array_equal(dist.cpu().numpy().astype(np.float64), ref["F_dist"])
+        assert st["hops"] == ref["hops"]
+
+
+@pytest.mark.parametrize("bits,d,n", [(4, 960, 3000), (1, 1536, 2000)])
+def test_quantize_end_to_end(jx, bits, d, n):
+    """Whole path with a random orthogonal P and the mean as centroid.  The GPU
+    rotates in float32 on the matrix cores, the oracle in double, so a code may
+    differ where a coordinate sits on a rounding boundary."""
+    wl = 3 if bits == 4 else 4
+    x = datagen.base(wl, n)
+    q = datagen.queries(wl, 300)
+    P = datagen.rotation(wl)
+    ix, g = _quantized_pair(jx, x, P, bits, 8, R=32, L=64)
+    wc, wm, wcen = ix.codes()
+    gc, gm, gcen = [t.cpu().numpy() for t in g.export_codes()]
+    assert np.allclose(gcen, wcen, rtol=0, atol=1e-6)
+    r32, r64 = oracle.rabitq_rotate(x, P, wcen)
+    U = np.stack([oracle.rabitq_unpack(wc[i], bits, d) for i in range(0, n, 7)])
+    G = np.stack([oracle.rabitq_unpack(gc[i], bits, d) for i in range(0, n, 7)])
+    diff = U != G
+    if bits == 1:
+        # codes agree except where the rotated value is within 1e-6 of zero
+        assert (np.abs(r64[::7][diff]) < 1e-6).all()
+    else:
+        # at most one level apart, and rare
+        assert diff.mean() < 2e-3
+        assert (np.abs(U.astype(int) - G.astype(int))[diff] == 1).all()
+    same = ~diff.any(axis=1)
+    assert np.allclose(gm[::7][same], wm[::7][same], rtol=1e-4)
+    # search: estimates within 1e-4 relative where the same vertex sits at the same rank
+    ref = ix.search(q, 10, 64, mode=1, want_frontier=True)
+    ids, dist = g.beam_frontier(dev(q), 64, mode=jx.RABITQ)
+    ids, dist = u32(ids), dist.cpu().numpy().astype(np.float64)
+    m = ids == ref["F_ids"]
+    assert m.mean() > 0.9
+    assert np.allclose(dist[m], ref["F_dist"][m], rtol=1e-3, atol=1e-3 * np.abs(ref["F_dist"]).mean())
+    # re-ranked results: exact distances, recall close to the oracle's
+    gt, gd = oracle.bruteforce(x, q, 10)
+    rr = ix.search(q, 10, 64, mode=1, rerank=40)
+    gi, gdist, st = g.search(dev(q), 10, 64, mode=jx.RABITQ, rerank=40, stats=True)
+    gi, gdist = u32(gi), gdist.cpu().numpy().astype(np.float64)
+    r_gpu, r_ref = oracle.recall_at_k(gi, gt), oracle.recall_at_k(rr["ids"], gt)
+    assert abs(r_gpu - r_ref) <= 0.004, (r_gpu, r_ref)
+    assert st["rerank_bytes"] == 40 * len(q) * d * 4
+    for i in range(0, len(q), 13):
+        for j in range(10):
+            assert abs(gdist[i, j] - oracle.l2sq(q[i], x[gi[i, j]])) <= 1e-4 * gdist[i, j]
+        keys = list(zip(gdist[i].tolist(), gi[i].tolist()))
+        assert keys == sorted(keys)
+
+
+def test_rerank_stage_exact_on_injected_codes(jx):
+    """Re-rank stage: with injected codes and an exact rotation the candidate
+    lists are identical, so the re-ranked ids must equal the oracle's wherever
+    the exact distances are not within float rounding of each other."""
+    d, n = 128, 2000
+    x = _clustered(n, d, 1)
+    q = _clustered(80, d, 2)
+    P = _signed_permutation(d, 9)
+    ix, g = _quantized_pair(jx, x, P, 4, 8, centroid=np.zeros(d, np.float32), inject=True)
+    for rr_n, k in ((40, 10), (64, 64), (10, 1)):
+        want = ix.search(q, k, 64, mode=1, rerank=rr_n)
+        ids, dist = g.search(dev(q), k, 64, mode=jx.RABITQ, rerank=rr_n)
+        ids, dist = u32(ids), dist.cpu().numpy().astype(np.float64)
+        assert np.allclose(dist, want["dist"], rtol=1e-5)
+        gaps = np.abs(np.diff(want["dist"], axis=1))
+        safe = np.ones_like(ids, bool)
+        tight = gaps < 1e-5 * want["dist"][:, 1:]
+        safe[:, 1:] &= ~tight
+        safe[:, :-1] &= ~tight
+        assert np.array_equal(ids[safe], want["ids"][safe])
+
+
+def test_insert_after_quantize_encodes_new_points(jx):
+    d, n = 96, 1200
+    x = _clustered(n, d, 4)
+    P = datagen.random_orthogonal(d, 8).astype(np.float32)
+    c = x[:800].astype(np.float64).mean(0).astype(np.float32)
+    g = jx.Index(d, jx.F32, 16, 32, 1.2, capacity=n, max_batch=n, quant_bits=4)
+    g.insert(dev(x[:800]))
+    g.quantize(4, dev(P), dev(c))
+    g.insert(dev(x[800:]))
+    codes, meta, _ = [t.cpu().numpy() for t in g.export_codes()]
+    h = jx.Index(d, jx.F32, 16, 32, 1.2, capacity=n, max_batch=n, quant_bits=4)
+    h.insert(dev(x))
+    h.quantize(4, dev(P), dev(c))
+    c2, m2, _ = [t.cpu().numpy() for t in h.export_codes()]
+    assert codes.shape == (n, d // 2) and np.array_equal(codes, c2) and np.array_equal(meta, m2)
+
+
+def test_rabitq_argument_errors(jx):
+    d, n = 64, 50
+    x = _clustered(n, d, 1)
+    g = jx.Index(d, jx.F32, 8, 16, 1.2, capacity=n, quant_bits=4)
+    P = dev(np.eye(d, dtype=np.float32))
+    with pytest.raises(jx.JxError):
+        g.quantize(4, P)                      # empty index
+    g.insert(dev(x))
+    with pytest.raises(jx.JxError):
+        g.quantize(1, P)                      # bits differ from quant_bits
+    with pytest.raises(jx.JxError):
+        g.quantize(4, P, query_bits=5)
+    with pytest.raises(jx.JxError):
+        g.search(dev(x[:4]), 1, 8, mode=jx.RABITQ)  # not quantised yet
+    g.quantize(4, P)
+    with pytest.raises(jx.JxError):
+        g.search(dev(x[:4]), 5, 8, mode=jx.RABITQ, rerank=3)  # rerank < k
+    with pytest.raises(jx.JxError):
+        jx.Index(d, jx.U8, 8, 16, 1.2, capacity=n, quant_bits=4)  # RaBitQ needs float32 data
