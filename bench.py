@@ -23,6 +23,9 @@ sys.path.insert(0, ROOT)
 
 L_SWEEP = [16, 24, 32, 48, 64, 96, 128, 256]
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes of one timed launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command
+# (profiles/beam_search_u8_N1M_L96.md); reported only when the run has the same shape.
+MEASURED_TRAFFIC = {(1_000_000, 10_000, 96): 4.485e9 + 1.29e6}
 
 
 def log(*a):
@@ -126,7 +129,8 @@ def main():
     alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * d + nq * k * 8
     achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "beam_search_kernel<u8,T=8>", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC.get((n, nq, L_star)),
                 "bytes_per_launch": int(alg_bytes), "kernel_ms": round(avg_ms, 4),
                 "hops_per_query": round(st["hops"] / nq, 1), "dist_evals_per_query": round(st["dist_evals"] / nq, 1)}
 
