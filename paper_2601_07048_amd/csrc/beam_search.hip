@@ -43,6 +43,7 @@ __global__ void __launch_bounds__(JX_BEAM_WPB * 64) beam_search_kernel(BeamArgs 
     uint32_t* tab = cand_id + 64;
 
     for (int i = lane; i < H; i += 64) tab[i] = JX_NONE_ID;
+    for (int i = lane; i < FCAP; i += 64) fr[i] = JX_EMPTY_KEY;
 
     QueryRegs<KIND, CPL, QB> q;
     load_query<KIND, T, CPL, QB>(q, a.ds, qi + (qi >= a.q_skip ? 1 : 0), lig);
@@ -62,7 +63,11 @@ __global__ void __launch_bounds__(JX_BEAM_WPB * 64) beam_search_kernel(BeamArgs 
     wave_sync();
     eval_batch<KIND, T, CPL, QB, 1>(q, a.ds, 0, 1, cand_id, cand_key, g, lig);
     wave_sync();
-    if (lane == 0) fk[0] = cand_key[0];
+    if (lane == 0) {
+        fk[0] = cand_key[0];
+        fr[0] = cand_key[0];
+    }
+    wave_sync();
     count = 1;
     evals = 1;
 
@@ -113,59 +118,51 @@ __global__ void __launch_bounds__(JX_BEAM_WPB * 64) beam_search_kernel(BeamArgs 
             uint64_t ck = lane < n_new ? cand_key[lane] : JX_EMPTY_KEY;
             wave_sync();
             // ---- 6. merge into the sorted frontier
+            // fr[] mirrors the frontier (flags aside) and is sorted, unused slots
+            // hold the largest key: every candidate finds its rank among the
+            // frontier entries by binary search, all candidates at once.
+            const uint64_t ckm = ck | 1ull;
             bool beats = lane < n_new;
-            if (count >= L) {
-                uint64_t worst = 0;
+            if (count >= L) beats = beats && (ckm < (fr[L - 1] | 1ull));
+            uint32_t pos = 0;
 #pragma unroll
-                for (int r = 0; r < NREG; r++)
-                    if (r == (L - 1) / 64) worst = readlane64(fk[r], (L - 1) % 64);
-                beats = beats && ((ck | 1ull) < (worst | 1ull));
-            }
+            for (int step = FCAP / 2; step >= 1; step >>= 1)
+                if ((fr[pos + step - 1] | 1ull) < ckm) pos += step;
+            // an id that is already in the frontier (the table forgot it) is dropped
+            beats = beats && ((fr[pos] | 1ull) != ckm);
             uint64_t sm = ballot(beats);
             if (sm == 0ull) continue;
+            const int n_ins = __builtin_popcountll(sm);
             uint32_t shift[NREG];
 #pragma unroll
             for (int r = 0; r < NREG; r++) shift[r] = 0;
-            uint32_t crank = 0, my_rank = 0;
-            bool my_dup = false;
-            int n_ins = 0;
+            uint32_t crank = 0;
             while (sm) {
                 const int j = __builtin_ctzll(sm);
                 sm &= sm - 1;
-                const uint64_t s = readlane64(ck, j) | 1ull;
-                uint32_t below = 0;
-                bool dup = false;
-#pragma unroll
-                for (int r = 0; r < NREG; r++) {
-                    const uint64_t f = fk[r] | 1ull;
-                    below += (uint32_t)__builtin_popcountll(ballot(f < s));
-                    dup = dup || (ballot(f == s) != 0ull);
-                }
-                if (dup) {  // id already in the frontier (the table forgot it)
-                    if (lane == j) my_dup = true;
-                    continue;
-                }
+                const uint64_t s = readlane64(ckm, j);
 #pragma unroll
                 for (int r = 0; r < NREG; r++) shift[r] += (s < (fk[r] | 1ull)) ? 1u : 0u;
-                crank += (s < (ck | 1ull)) ? 1u : 0u;
-                if (lane == j) my_rank = below;
-                n_ins++;
+                crank += (s < ckm) ? 1u : 0u;
             }
-            if (n_ins == 0) continue;
+            wave_sync();  // all binary-search reads of fr[] are done
 #pragma unroll
             for (int r = 0; r < NREG; r++) {
                 uint32_t np = (uint32_t)(r * 64 + lane) + shift[r];
                 if (np < (uint32_t)FCAP) fr[np] = fk[r];
             }
-            if (beats && !my_dup) {
-                uint32_t np = my_rank + crank;
+            if (beats) {
+                uint32_t np = pos + crank;
                 if (np < (uint32_t)FCAP) fr[np] = ck;
             }
             wave_sync();
 #pragma unroll
             for (int r = 0; r < NREG; r++) {
                 fk[r] = fr[r * 64 + lane];
-                if (r * 64 + lane >= L) fk[r] = JX_EMPTY_KEY;  // truncate to the beam width
+                if (r * 64 + lane >= L) {  // truncate to the beam width
+                    fk[r] = JX_EMPTY_KEY;
+                    fr[r * 64 + lane] = JX_EMPTY_KEY;
+                }
             }
             wave_sync();
             count = count + n_ins < L ? count + n_ins : L;

@@ -40,12 +40,46 @@ __device__ __forceinline__ T shfl_xor(T v, int m) {
     return __shfl_xor(v, m, 64);
 }
 
-// sum over aligned groups of W lanes (W power of two <= 64); every lane of the
-// group ends up with the total
+// One 32-bit value from another lane through the data-parallel-primitive path
+// (no LDS traffic).  CTRL: 0xB1 = quad_perm [1,0,3,2] (lane ^ 1), 0x4E =
+// quad_perm [2,3,0,1] (lane ^ 2), 0x141 = row_half_mirror (lane -> 7 - lane in
+// each group of 8), 0x140 = row_mirror (lane -> 15 - lane in each row of 16).
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+
+template <typename T>
+__device__ __forceinline__ T bits_add(T a, uint32_t b_bits);
+template <>
+__device__ __forceinline__ uint32_t bits_add<uint32_t>(uint32_t a, uint32_t b) { return a + b; }
+template <>
+__device__ __forceinline__ int32_t bits_add<int32_t>(int32_t a, uint32_t b) { return a + (int32_t)b; }
+template <>
+__device__ __forceinline__ float bits_add<float>(float a, uint32_t b) { return a + __uint_as_float(b); }
+
+template <typename T>
+__device__ __forceinline__ uint32_t to_bits(T v);
+template <>
+__device__ __forceinline__ uint32_t to_bits<uint32_t>(uint32_t v) { return v; }
+template <>
+__device__ __forceinline__ uint32_t to_bits<int32_t>(int32_t v) { return (uint32_t)v; }
+template <>
+__device__ __forceinline__ uint32_t to_bits<float>(float v) { return __float_as_uint(v); }
+
+// Sum over aligned groups of W lanes (W power of two <= 64); every lane of the
+// group ends up with the total.  The first four steps stay inside a row of 16
+// lanes and use DPP: after the lane^1 and lane^2 steps all four lanes of a
+// quad hold the same partial sum, so the mirror patterns (which pair each lane
+// with a lane of the other quad / the other half-row) complete the butterfly.
 template <int W, typename T>
 __device__ __forceinline__ T group_sum(T v) {
-#pragma unroll
-    for (int m = 1; m < W; m <<= 1) v += shfl_xor(v, m);
+    if (W >= 2) v = bits_add<T>(v, dpp_u32<0xB1>(to_bits<T>(v)));
+    if (W >= 4) v = bits_add<T>(v, dpp_u32<0x4E>(to_bits<T>(v)));
+    if (W >= 8) v = bits_add<T>(v, dpp_u32<0x141>(to_bits<T>(v)));
+    if (W >= 16) v = bits_add<T>(v, dpp_u32<0x140>(to_bits<T>(v)));
+    if (W >= 32) v += shfl_xor(v, 16);
+    if (W >= 64) v += shfl_xor(v, 32);
     return v;
 }
 

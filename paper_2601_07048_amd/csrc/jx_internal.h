@@ -4,7 +4,9 @@
 #include <stdint.h>
 #include "../../include/jx.h"
 
+#ifndef JX_BEAM_WPB
 #define JX_BEAM_WPB 4  // wavefronts (= queries) per workgroup of the beamSearch kernel
+#endif
 
 namespace jx {
 

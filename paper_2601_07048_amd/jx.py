@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libjx.so")
+LIB_PATH = os.environ.get("JX_LIB", os.path.join(_HERE, "libjx.so"))
 
 NONE = 0xFFFFFFFF
 U8, F32 = 0, 1
