@@ -17,12 +17,18 @@
 //      many candidates precede its entries, and one LDS scatter/gather applies
 //      the permutation.  Keys are 64-bit (ordered distance, id, expanded flag),
 //      so the order is the strict total order (distance, id).
+#include <stdlib.h>
 #include "jx_distance.h"
 
 namespace jx {
 
+#ifndef JX_BEAM_PREFETCH
+#define JX_BEAM_PREFETCH 0
+#endif
+
 template <int KIND, int T, int CPL, int NREG, int QB>
-__global__ void __launch_bounds__(JX_BEAM_WPB * 64) beam_search_kernel(BeamArgs a) {
+__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu(NREG <= 2 ? 6 : 4, 8)))
+beam_search_kernel(BeamArgs a) {
     constexpr int G = 64 / T;
     constexpr int U0 = (8 / CPL) > 0 ? (8 / CPL) : 1;
     constexpr int U = U0 < (64 / G) ? U0 : (64 / G);  // records in flight per lane group
@@ -53,7 +59,11 @@ __global__ void __launch_bounds__(JX_BEAM_WPB * 64) beam_search_kernel(BeamArgs 
     for (int r = 0; r < NREG; r++) fk[r] = JX_EMPTY_KEY;
     int count = 0;
     const int L = a.L;
+    const bool full = a.ds.nch == T * CPL;  // wave-uniform: no chunk slot is idle
     uint32_t hops = 0, evals = 0;
+#if JX_BEAM_PREFETCH
+    uint32_t pf_u = JX_NONE_ID, pf_v = JX_NONE_ID;  // prefetched adjacency row: vertex, entry of this lane
+#endif
 
     // seed: the entry vertex
     if (lane == 0) {
@@ -93,10 +103,44 @@ __global__ void __launch_bounds__(JX_BEAM_WPB * 64) beam_search_kernel(BeamArgs 
         }
         hops++;
         const uint32_t* row = a.adj + (size_t)u * (size_t)a.R;
+#if JX_BEAM_PREFETCH
+        // the first 64 entries of the row may have been fetched during the previous expansion
+        uint32_t v0 = JX_NONE_ID;
+        if (u == pf_u)
+            v0 = lane < a.R ? pf_v : JX_NONE_ID;
+        else if (lane < a.R)
+            v0 = row[lane];
+        // speculative fetch of the row of the next closest unexpanded entry: it is
+        // the next vertex to expand unless a closer candidate turns up in this round
+        {
+            int r2 = -1, l2 = 0;
+#pragma unroll
+            for (int r = 0; r < NREG; r++) {
+                uint64_t m = ballot((fk[r] & 1ull) == 0ull);
+                if (r2 < 0 && m != 0ull) {
+                    r2 = r;
+                    l2 = __builtin_ctzll(m);
+                }
+            }
+            pf_u = JX_NONE_ID;
+#pragma unroll
+            for (int r = 0; r < NREG; r++)
+                if (r == r2) pf_u = key_id(readlane64(fk[r], l2));
+            if (pf_u != JX_NONE_ID && lane < a.R) pf_v = a.adj[(size_t)pf_u * (size_t)a.R + lane];
+        }
+#endif
         for (int rb = 0; rb < a.R; rb += 64) {
             // ---- 2. adjacency row (coalesced)
+#if JX_BEAM_PREFETCH
+            uint32_t v = v0;
+            if (rb > 0) {
+                v = JX_NONE_ID;
+                if (rb + lane < a.R) v = row[rb + lane];
+            }
+#else
             uint32_t v = JX_NONE_ID;
             if (rb + lane < a.R) v = row[rb + lane];
+#endif
             bool is_new = false;
             // ---- 3. visited filter
             if (v != JX_NONE_ID) {
@@ -111,8 +155,13 @@ __global__ void __launch_bounds__(JX_BEAM_WPB * 64) beam_search_kernel(BeamArgs 
             if (is_new) cand_id[prefix_count(nm)] = v;
             wave_sync();
             // ---- 4./5. gather + distances
-            for (int s0 = 0; s0 < n_new; s0 += G * U)
-                eval_batch<KIND, T, CPL, QB, U>(q, a.ds, s0, n_new, cand_id, cand_key, g, lig);
+            if (full) {
+                for (int s0 = 0; s0 < n_new; s0 += G * U)
+                    eval_batch<KIND, T, CPL, QB, U, true>(q, a.ds, s0, n_new, cand_id, cand_key, g, lig);
+            } else {
+                for (int s0 = 0; s0 < n_new; s0 += G * U)
+                    eval_batch<KIND, T, CPL, QB, U, false>(q, a.ds, s0, n_new, cand_id, cand_key, g, lig);
+            }
             evals += n_new;
             wave_sync();
             uint64_t ck = lane < n_new ? cand_key[lane] : JX_EMPTY_KEY;
@@ -124,6 +173,7 @@ __global__ void __launch_bounds__(JX_BEAM_WPB * 64) beam_search_kernel(BeamArgs 
             const uint64_t ckm = ck | 1ull;
             bool beats = lane < n_new;
             if (count >= L) beats = beats && (ckm < (fr[L - 1] | 1ull));
+            if (ballot(beats) == 0ull) continue;  // nothing enters the frontier (the common case late in a search)
             uint32_t pos = 0;
 #pragma unroll
             for (int step = FCAP / 2; step >= 1; step >>= 1)
@@ -217,9 +267,31 @@ static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st) {
 #undef JX_LAUNCH
 }
 
+// Chunks per lane for records of at most 64 chunks: with 2 chunks per lane a
+// record is covered by half as many lanes, so twice as many candidates share
+// one instruction and the in-group reduction is one step shorter.
+static int chunks_per_lane_pref(int kind) {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("JX_CHUNKS_PER_LANE");
+        v = e ? atoi(e) : 0;
+        if (v != 1 && v != 2) v = 0;
+    }
+    if (v) return v;
+    return (kind == K_U8 || kind == K_F32) ? 2 : 1;
+}
+
 template <int KIND, int QB>
 static hipError_t launch_shape(const BeamArgs& a, hipStream_t st) {
     const int nch = a.ds.nch;
+    if constexpr (KIND != K_RQ1) {
+        if (nch <= 64 && chunks_per_lane_pref(KIND) == 2) {
+            if (nch <= 8) return launch_nreg<KIND, 4, 2, QB>(a, st);
+            if (nch <= 16) return launch_nreg<KIND, 8, 2, QB>(a, st);
+            if (nch <= 32) return launch_nreg<KIND, 16, 2, QB>(a, st);
+            return launch_nreg<KIND, 32, 2, QB>(a, st);
+        }
+    }
     if (nch <= 8) return launch_nreg<KIND, 8, 1, QB>(a, st);
     if (nch <= 16) return launch_nreg<KIND, 16, 1, QB>(a, st);
     if (nch <= 32) return launch_nreg<KIND, 32, 1, QB>(a, st);

@@ -151,7 +151,9 @@ int64_t batch_cap(const jx_params& p, int64_t linked) {
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 int hash_log2_for(int L) {
-    int h = 9;
+    // 1,024 slots at least: measured optimum of fewer repeated distance
+    // evaluations against LDS footprint for L <= 256
+    int h = 10;
     while ((1 << h) < 4 * L && h < 12) h++;
     return h;
 }

@@ -71,7 +71,11 @@ __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const Di
 }
 
 // Distance of the query to up to G*U records; result keys go to cand_key[].
-template <int KIND, int T, int CPL, int QB, int U>
+// FULL: every one of the T*CPL chunk slots maps to a chunk of the record, so no
+// lane has to be masked.  Lane groups beyond the last candidate of a batch read
+// the last candidate's record again (same cache lines, no extra traffic) and
+// drop the result; this keeps the gathers free of per-lane predication.
+template <int KIND, int T, int CPL, int QB, int U, bool FULL = false>
 __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, const DistSrc& a, int s0, int n_new,
                                            const uint32_t* cand_id, uint64_t* cand_key, int g, int lig) {
     constexpr int G = 64 / T;
@@ -80,16 +84,21 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
 #pragma unroll
     for (int u = 0; u < U; u++) {
         int c = s0 + u * G + g;
-        ids[u] = (c < n_new) ? cand_id[c] : JX_NONE_ID;
+        ids[u] = cand_id[c < n_new ? c : n_new - 1];
     }
 #pragma unroll
     for (int u = 0; u < U; u++) {
+        if (s0 + u * G < n_new) {  // wave-uniform
 #pragma unroll
-        for (int j = 0; j < CPL; j++) {
-            int ch = lig + T * j;
-            data[u][j] = make_uint4(0, 0, 0, 0);
-            if (ids[u] != JX_NONE_ID && ch < a.nch)
-                data[u][j] = load16(a.recs + (size_t)ids[u] * (size_t)a.rec_stride + (size_t)ch * 16);
+            for (int j = 0; j < CPL; j++) {
+                int ch = lig + T * j;
+                if constexpr (FULL) {
+                    data[u][j] = load16(a.recs + (size_t)ids[u] * (size_t)a.rec_stride + (size_t)ch * 16);
+                } else {
+                    data[u][j] = make_uint4(0, 0, 0, 0);
+                    if (ch < a.nch) data[u][j] = load16(a.recs + (size_t)ids[u] * (size_t)a.rec_stride + (size_t)ch * 16);
+                }
+            }
         }
     }
 #pragma unroll
