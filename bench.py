@@ -1,12 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the beamSearch hot path on one MI355X.
 
-Workload (the one the headline metric is quoted on): N = 1,000,000 base
+Default workload (the one the headline metric is quoted on): N = 1,000,000 base
 vectors, d = 128, uint8, 256-component Gaussian mixture; 10,000 queries from the
 same mixture; Vamana graph R = 64, L_build = 128, alpha = 1.2 built on the GPU
 by batch insertion; search k = 10 with exact int32 L2.  A "step" is one
 jx_search call over the whole 10,000-query batch at the smallest beam width L
 whose recall@10 against brute force is >= 0.95.
+
+    python bench.py                      # workload 2 (default)
+    python bench.py --workload 3         # N=1M d=960 fp32, 4-bit RaBitQ + exact re-rank of 40
+    python bench.py --workload 4         # N=1M d=1536 fp32 unit norm, 1-bit RaBitQ + re-rank of 40
+    python bench.py --workload 5 --n 10000000   # streaming inserts of 100,000, a query batch every 1M
 
 Prints ONE JSON line: queries/s, the roofline record of the beamSearch kernel
 (algorithmic bytes / measured duration against the 8 TB/s HBM peak) and the CPU
@@ -21,11 +26,20 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-L_SWEEP = [16, 24, 32, 48, 64, 96, 128, 256]
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of one timed launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command
 # (profiles/beam_search_u8_N1M_L96.md); reported only when the run has the same shape.
-MEASURED_TRAFFIC = {(1_000_000, 10_000, 96): 4.485e9 + 1.29e6}
+MEASURED_TRAFFIC = {(2, 1_000_000, 10_000, 96): None}
+
+SPEC = {
+    2: dict(d=128, u8=True, bits=0, sweep=[16, 24, 32, 48, 64, 96, 128, 256], kernel="beam_search_kernel<u8>",
+            text="d=128 uint8 256-component Gaussian mixture, search k=10 exact int32 L2"),
+    3: dict(d=960, u8=False, bits=4, sweep=[64, 96, 128, 192, 256, 384, 512], kernel="beam_search_kernel<4-bit RaBitQ>",
+            text="d=960 float32 128-component anisotropic mixture, 4-bit RaBitQ codes (B_q=8), exact fp32 re-rank of 40, k=10"),
+    4: dict(d=1536, u8=False, bits=1, sweep=[64, 96, 128, 192, 256, 384, 512], kernel="beam_search_kernel<1-bit RaBitQ>",
+            text="d=1536 float32 unit-norm 512-component mixture, 1-bit RaBitQ codes (B_q=4), exact fp32 re-rank of 40, k=10"),
+}
+SPEC[5] = dict(SPEC[2], sweep=[128], text="streaming: batches of 100,000 inserts, a 10,000-query batch at L=128 every 1M; " + SPEC[2]["text"])
 
 
 def log(*a):
@@ -37,10 +51,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--n", type=int, default=1_000_000)
     ap.add_argument("--nq", type=int, default=10_000)
     ap.add_argument("--recall", type=float, default=0.95)
     ap.add_argument("--L", type=int, default=0, help="force the beam width (0 = smallest with recall >= target)")
+    ap.add_argument("--query-bits", type=int, default=0, help="B_q of the integer query (0 = 8 for 4-bit codes, 4 for 1-bit codes)")
     ap.add_argument("--cpu-queries", type=int, default=2000, help="sample size of the cpu_baseline leg (0 = skip)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
@@ -55,23 +71,82 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    R, L_build, alpha, k, d = 64, 128, 1.2, 10, 128
+    wl = args.workload
+    sp = SPEC[wl]
+    R, L_build, alpha, k, d = 64, 128, 1.2, 10, sp["d"]
     n, nq = args.n, args.nq
+    rabitq = sp["bits"] > 0
+    if not args.query_bits:
+        args.query_bits = 4 if sp["bits"] == 1 else 8
+    mode = jx.RABITQ if rabitq else jx.EXACT
+    rerank = 4 * k if rabitq else 0
+    gen_wl = 2 if wl == 5 else wl
 
     t0 = time.time()
-    x = datagen.base(2, n)
-    q = datagen.queries(2, nq)
-    log(f"[bench] generated {n}x{d} uint8 base + {nq} queries in {time.time() - t0:.1f}s")
-    dx = torch.from_numpy(x).cuda()
+    q = datagen.queries(gen_wl, nq)
     dq = torch.from_numpy(q).cuda()
+    # the base set goes to the GPU chunk by chunk (the float workloads are several GB)
+    dx = torch.empty((n, d), dtype=torch.uint8 if sp["u8"] else torch.float32, device="cuda")
+    step = 16 * datagen.CHUNK
+    for s0 in range(0, n, step):
+        m = min(step, n - s0)
+        dx[s0:s0 + m] = torch.from_numpy(datagen.base(gen_wl, m, start=s0)).cuda()
+    log(f"[bench] workload {wl}: generated {n}x{d} base + {nq} queries in {time.time() - t0:.1f}s")
 
-    g = jx.Index(d, jx.U8, R, L_build, alpha, capacity=n, max_batch=n // 4 + 1)
+    batch = 100_000 if wl == 5 else n
+    g = jx.Index(d, jx.U8 if sp["u8"] else jx.F32, R, L_build, alpha, capacity=n,
+                 max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"])
+
+    def recall_of(ids, gt_np):
+        a = ids.cpu().numpy()
+        hit = 0
+        for f, t in zip(a, gt_np):
+            hit += len(set(f.tolist()) & set(t.tolist()))
+        return hit / (k * len(a))
+
+    stream_log = []
     torch.cuda.synchronize()
     t0 = time.time()
-    g.insert(dx)
-    torch.cuda.synchronize()
-    t_build = time.time() - t0
+    if wl == 5:
+        # streaming: batches of 100,000; every 1M points a query batch with recall against brute force
+        t_ins = 0.0
+        for s0 in range(0, n, batch):
+            m = min(batch, n - s0)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            g.insert(dx[s0:s0 + m])
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t1
+            t_ins += dt
+            done = s0 + m
+            if done % 1_000_000 == 0 or done == n:
+                gt_c, _ = g.bruteforce(dq, k)
+                ids, _ = g.search(dq, k, 128)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                for _ in range(5):
+                    g.search(dq, k, 128)
+                torch.cuda.synchronize()
+                qps_c = 5 * nq / (time.perf_counter() - t1)
+                stream_log.append({"N": done, "batch_inserts_per_s": round(m / dt, 1), "qps_L128": round(qps_c, 1),
+                                   "recall_at_10": round(recall_of(ids, gt_c.cpu().numpy()), 4)})
+                log(f"[bench] stream {stream_log[-1]}")
+        t_build = t_ins
+    else:
+        g.insert(dx)
+        torch.cuda.synchronize()
+        t_build = time.time() - t0
     log(f"[bench] built the graph on the GPU in {t_build:.2f}s ({n / t_build:,.0f} inserts/s)")
+
+    t_quant = None
+    if rabitq:
+        P = torch.from_numpy(datagen.rotation(wl)).cuda()
+        torch.cuda.synchronize()
+        t0 = time.time()
+        g.quantize(sp["bits"], P, None, query_bits=args.query_bits)
+        torch.cuda.synchronize()
+        t_quant = time.time() - t0
+        log(f"[bench] quantised ({sp['bits']} bit) in {t_quant:.2f}s")
 
     t0 = time.time()
     gt, _ = g.bruteforce(dq, k)
@@ -79,44 +154,41 @@ def main():
     log(f"[bench] brute-force ground truth in {time.time() - t0:.2f}s")
     gt_np = gt.cpu().numpy()
 
-    def recall(ids):
-        a = ids.cpu().numpy()
-        hit = 0
-        for f, t in zip(a, gt_np):
-            hit += len(set(f.tolist()) & set(t.tolist()))
-        return hit / (k * len(a))
-
     sweep = {}
     L_star = args.L
-    for L in L_SWEEP:
-        ids, _ = g.search(dq, k, L)
+    for L in sp["sweep"]:
+        ids, _ = g.search(dq, k, L, mode=mode, rerank=rerank)
         torch.cuda.synchronize()
-        sweep[L] = round(recall(ids), 4)
+        sweep[L] = round(recall_of(ids, gt_np), 4)
         if not L_star and sweep[L] >= args.recall:
             L_star = L
             break
     if not L_star:
-        L_star = L_SWEEP[-1]
+        L_star = sp["sweep"][-1]
     log(f"[bench] recall@10 sweep {sweep} -> L = {L_star}")
 
     out = (torch.empty((nq, k), dtype=torch.int32, device="cuda"), torch.empty((nq, k), dtype=torch.float32, device="cuda"))
-    ids, _, st = g.search(dq, k, L_star, stats=True, out=out)
-    rec = recall(ids)
+    ids, _ = g.search(dq, k, L_star, mode=mode, rerank=rerank, out=out)
+    rec = recall_of(ids, gt_np)
     for _ in range(args.warmup):
-        g.search(dq, k, L_star, out=out)
+        g.search(dq, k, L_star, mode=mode, rerank=rerank, out=out)
     torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # timed region 1: K whole jx_search calls back to back -> value
     t0 = time.perf_counter()
-    for a, b in ev:
-        a.record()
-        g.search(dq, k, L_star, out=out)   # exact mode: the call is one beamSearch kernel launch
-        b.record()
+    for _ in range(args.steps):
+        g.search(dq, k, L_star, mode=mode, rerank=rerank, out=out)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    kern_ms = [a.elapsed_time(b) for a, b in ev]
-    avg_ms = sum(kern_ms) / len(kern_ms)
     ms_per_step = wall * 1e3 / args.steps
     qps = nq * args.steps / wall
+    # timed region 2: the same K calls with the library's HIP events around each stage
+    # (recorded on the launch stream) -> duration of the beamSearch kernel
+    stage = {"rotate_ms": 0.0, "prep_ms": 0.0, "beam_ms": 0.0, "rerank_ms": 0.0}
+    for _ in range(args.steps):
+        _, _, st = g.search(dq, k, L_star, mode=mode, rerank=rerank, out=out, stats=True)
+        for key in stage:
+            stage[key] += st[key] / args.steps
+    beam_ms = stage["beam_ms"]
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -125,40 +197,50 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # algorithmic bytes of one launch: adjacency rows + gathered vectors + queries in + results out
-    alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * d + nq * k * 8
-    achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "beam_search_kernel<u8,T=8>", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get((n, nq, L_star)),
-                "bytes_per_launch": int(alg_bytes), "kernel_ms": round(avg_ms, 4),
-                "hops_per_query": round(st["hops"] / nq, 1), "dist_evals_per_query": round(st["dist_evals"] / nq, 1)}
+    # algorithmic bytes of one beamSearch launch: adjacency rows + gathered records + query records in + results out
+    qrec = d if not rabitq else (16 + (2 if sp["bits"] == 4 else args.query_bits) * ((d * sp["bits"] // 8 + 15) // 16) * 16)
+    out_k = rerank if rerank else k
+    alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * qrec + nq * out_k * 8
+    achieved = alg_bytes / (beam_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": sp["kernel"], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((wl, n, nq, L_star)),
+                "bytes_per_launch": int(alg_bytes), "kernel_ms": round(beam_ms, 4),
+                "hops_per_query": round(st["hops"] / nq, 1), "dist_evals_per_query": round(st["dist_evals"] / nq, 1),
+                "stage_ms": {k2: round(v, 4) for k2, v in stage.items()}}
 
     cpu = None
     if args.cpu_queries > 0:
         import oracle
 
         adj, _ = g.export_graph()
-        oix = oracle.Index(d, np.uint8, R, L_build, alpha, n)
-        oix.set_graph(x, adj.cpu().numpy().view(np.uint32), g.size()[1])
+        oix = oracle.Index(d, np.uint8 if sp["u8"] else np.float32, R, L_build, alpha, n)
+        oix.set_graph(dx.cpu().numpy(), adj.cpu().numpy().view(np.uint32), g.size()[1])
+        if rabitq:
+            codes, meta, cen = [t.cpu().numpy() for t in g.export_codes()]
+            oix.set_codes(sp["bits"], datagen.rotation(wl), cen, codes, meta, qbits=args.query_bits)
         m = min(args.cpu_queries, nq)
-        oix.search(q[:64], k, L_star)  # touch
+        oix.search(q[:32], k, L_star, mode=1 if rabitq else 0, rerank=rerank)  # touch
         t0 = time.perf_counter()
-        res = oix.search(q[:m], k, L_star)
+        res = oix.search(q[:m], k, L_star, mode=1 if rabitq else 0, rerank=rerank)
         dt = time.perf_counter() - t0
-        same = bool((res["ids"] == ids.cpu().numpy().view(np.uint32)[:m]).all())
+        agree = float((res["ids"] == ids.cpu().numpy().view(np.uint32)[:m]).mean())
         cpu = {"value": round(m / dt, 1), "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"first {m} of the {nq} queries, same graph, same L={L_star}; ids identical to the GPU's: {same}"}
+               "sample": f"first {m} of the {nq} queries, same graph" + (" and codes" if rabitq else "") +
+                         f", same L={L_star}; fraction of result ids identical to the GPU's: {agree:.4f}"}
 
+    cfg = {"workload": f"workload {wl}: N={n} {sp['text']}; {nq} queries; Vamana R=64 L_build=128 alpha=1.2 built on the GPU",
+           "L": L_star, "recall_at_10": round(rec, 4), "recall_sweep": sweep,
+           "build_inserts_per_s": round(n / t_build, 1), "build_s": round(t_build, 2)}
+    if t_quant is not None:
+        cfg["quantize_s"] = round(t_quant, 2)
+    if stream_log:
+        cfg["stream"] = stream_log
     line = {
         "metric": "queries/sec at recall@10=0.95 (10k-query batch)", "value": round(qps, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": f"N={n} d=128 uint8 256-component Gaussian mixture, {nq} queries, Vamana R=64 L_build=128 "
-                               f"alpha=1.2 built on the GPU, search k=10 exact int32 L2",
-                   "L": L_star, "recall_at_10": round(rec, 4), "recall_sweep": sweep,
-                   "build_inserts_per_s": round(n / t_build, 1), "build_s": round(t_build, 2)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8" if sp["u8"] else ("u4+f32" if sp["bits"] == 4 else "u1+f32"), "data": "synthetic",
+        "config": cfg, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
 

@@ -88,6 +88,9 @@ typedef struct {
     uint64_t adj_bytes;    /* hops * 4R */
     uint64_t vec_bytes;    /* dist_evals * bytes fetched per evaluation */
     uint64_t rerank_bytes; /* exact re-rank reads */
+    /* elapsed time of each stage of the call, from HIP events recorded on the
+     * caller's stream around the stage's launches (summed over query slices) */
+    float rotate_ms, prep_ms, beam_ms, rerank_ms;
 } jx_stats;
 
 /* Bytes of device memory jx_create needs for these parameters (256-aligned

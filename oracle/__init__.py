@@ -259,6 +259,14 @@ class Index:
             raise RuntimeError("oracle quantize: float32 data only")
         self.bits = bits
 
+    def set_codes(self, bits, P, centroid, codes, meta, qbits=8):
+        P = np.ascontiguousarray(P, dtype=np.float32)
+        centroid = np.ascontiguousarray(centroid, dtype=np.float32)
+        codes = np.ascontiguousarray(codes, dtype=np.uint8)
+        meta = np.ascontiguousarray(meta, dtype=np.float32)
+        lib().orc_index_set_codes(self._h, C.c_int(bits), C.c_int(qbits), _p(P), _p(centroid), _p(codes), _p(meta))
+        self.bits = bits
+
     def codes(self):
         n = self.n
         cb = rabitq_code_bytes(self.d, self.bits)

@@ -978,6 +978,30 @@ int orc_index_quantize(orc_index *x, int bits, int qbits, int rule, const float 
     return 0;
 }
 
+/* Install codes, the two floats per vector, rotation and centroid produced
+ * elsewhere (used to time the estimator search on a large index whose codes
+ * would take the plain double-precision rotation too long to recompute). */
+void orc_index_set_codes(orc_index *x, int bits, int qbits, const float *P, const float *centroid, const uint8_t *codes,
+                         const float *meta) {
+    const int d = x->d;
+    free(x->P);
+    free(x->c);
+    free(x->codes);
+    free(x->meta);
+    x->bits = bits;
+    x->qbits = qbits;
+    x->rule = ORC_RULE_MAXABS;
+    x->code_bytes = orc_rabitq_code_bytes(d, bits);
+    x->P = (float *)malloc(sizeof(float) * (size_t)d * d);
+    memcpy(x->P, P, sizeof(float) * (size_t)d * d);
+    x->c = (float *)malloc(sizeof(float) * (size_t)d);
+    memcpy(x->c, centroid, sizeof(float) * (size_t)d);
+    x->codes = (uint8_t *)malloc((size_t)x->capacity * x->code_bytes + 16);
+    x->meta = (float *)malloc(sizeof(float) * 2 * (size_t)x->capacity + 16);
+    memcpy(x->codes, codes, (size_t)x->n * x->code_bytes);
+    memcpy(x->meta, meta, sizeof(float) * 2 * (size_t)x->n);
+}
+
 void orc_index_get_codes(const orc_index *x, uint8_t *codes, float *meta, float *centroid) {
     memcpy(codes, x->codes, (size_t)x->n * x->code_bytes);
     memcpy(meta, x->meta, sizeof(float) * 2 * (size_t)x->n);

@@ -27,10 +27,11 @@ namespace jx {
 #endif
 
 template <int KIND, int T, int CPL, int NREG, int QB>
-__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu(NREG <= 2 ? 6 : 4, 8)))
+__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu((KIND <= K_F32 && NREG <= 2 && CPL <= 2) ? 6 : 1, 8)))
 beam_search_kernel(BeamArgs a) {
     constexpr int G = 64 / T;
-    constexpr int U0 = (8 / CPL) > 0 ? (8 / CPL) : 1;
+    constexpr int UMAX = (KIND == K_RQ1) ? 4 : 8;  // 16-byte loads in flight per lane (the 1-bit path keeps its bit planes in registers)
+    constexpr int U0 = (UMAX / CPL) > 0 ? (UMAX / CPL) : 1;
     constexpr int U = U0 < (64 / G) ? U0 : (64 / G);  // records in flight per lane group
     constexpr int FCAP = NREG * 64;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -278,7 +279,7 @@ static int chunks_per_lane_pref(int kind) {
         if (v != 1 && v != 2) v = 0;
     }
     if (v) return v;
-    return (kind == K_U8 || kind == K_F32) ? 2 : 1;
+    return kind == K_RQ1 ? 1 : 2;
 }
 
 template <int KIND, int QB>

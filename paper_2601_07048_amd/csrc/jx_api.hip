@@ -256,6 +256,36 @@ int jx_export_graph(jx_index* idx, uint32_t* d_adj, uint32_t* d_deg, void* strea
     return JX_OK;
 }
 
+// Stage timer used when the caller asks for jx_stats: events on the launch stream.
+struct StageTimer {
+    bool on;
+    hipStream_t st;
+    hipEvent_t ev[2];
+    float acc[4];
+    int rc;
+    StageTimer(bool enable, hipStream_t s) : on(enable), st(s), rc(0) {
+        acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
+        if (on && (hipEventCreate(&ev[0]) != hipSuccess || hipEventCreate(&ev[1]) != hipSuccess)) on = false;
+    }
+    ~StageTimer() {
+        if (on) {
+            (void)hipEventDestroy(ev[0]);
+            (void)hipEventDestroy(ev[1]);
+        }
+    }
+    void begin() {
+        if (on) (void)hipEventRecord(ev[0], st);
+    }
+    // closes the stage; synchronises (stats calls block anyway)
+    void end(int stage) {
+        if (!on) return;
+        (void)hipEventRecord(ev[1], st);
+        (void)hipEventSynchronize(ev[1]);
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev[0], ev[1]) == hipSuccess) acc[stage] += ms;
+    }
+};
+
 static void fill_exact_src(const jx_index* idx, jx::DistSrc* ds, const void* queries) {
     memset(ds, 0, sizeof *ds);
     ds->recs = idx->d_vecs;
@@ -288,6 +318,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     a.entry = idx->entry;
     a.hash_log2 = hash_log2_for(L);
     a.stats = h_stats ? idx->d_stats : nullptr;
+    StageTimer tm(h_stats != nullptr, st);
     if (mode == JX_EXACT) {
         // distances are already exact: a re-rank would change nothing
         fill_exact_src(idx, &a.ds, d_queries);
@@ -295,7 +326,9 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         a.out_ids = d_out_ids;
         a.out_dist = d_out_dist;
         a.out_k = out_k;
+        tm.begin();
         JX_HIP(jx::launch_beam_search(p.dtype == JX_U8 ? 0 : 1, 0, a, st));
+        tm.end(2);
     } else {
         QueryWork qw;
         query_work(&p, p.max_batch, idx->meta_chunk, &qw);
@@ -305,7 +338,9 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         for (int64_t q0 = 0; q0 < nq; q0 += p.max_batch) {
             const int64_t m = nq - q0 < p.max_batch ? nq - q0 : p.max_batch;
             const float* qs = (const float*)d_queries + (size_t)q0 * p.dim;
+            tm.begin();
             JX_HIP(jx::launch_rotate(qs, m, p.dim, idx->d_P, idx->d_centroid, (float*)(W + qw.rot), st));
+            tm.end(0);
             jx::QueryPrepArgs qp;
             memset(&qp, 0, sizeof qp);
             qp.rot = (const float*)(W + qw.rot);
@@ -316,7 +351,9 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
             qp.qrecs = W + qw.qrecs;
             qp.qrec_stride = qrec_stride;
             qp.plane_stride = qw.plane_stride;
+            tm.begin();
             JX_HIP(jx::launch_query_prep(qp, st));
+            tm.end(1);
             memset(&a.ds, 0, sizeof a.ds);
             a.ds.recs = idx->d_codes;
             a.ds.rec_stride = idx->code_stride;
@@ -335,7 +372,9 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
                 a.out_dist = d_out_dist + (size_t)q0 * out_k;
                 a.out_k = out_k;
             }
+            tm.begin();
             JX_HIP(jx::launch_beam_search(idx->quantized == 4 ? 2 : 3, idx->qbits, a, st));
+            tm.end(2);
             if (rerank) {
                 jx::RerankArgs r;
                 memset(&r, 0, sizeof r);
@@ -348,7 +387,9 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
                 r.out_ids = d_out_ids + (size_t)q0 * out_k;
                 r.out_dist = d_out_dist + (size_t)q0 * out_k;
                 r.stats = h_stats ? idx->d_stats : nullptr;
+                tm.begin();
                 JX_HIP(jx::launch_rerank(p.dtype, r, st));
+                tm.end(3);
             }
         }
     }
@@ -362,6 +403,10 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         h_stats->adj_bytes = hs[0] * 4ull * p.R;
         h_stats->vec_bytes = hs[1] * (unsigned long long)(mode == JX_EXACT ? idx->vec_bytes : idx->code_stride);
         h_stats->rerank_bytes = hs[2] * (unsigned long long)idx->vec_bytes;
+        h_stats->rotate_ms = tm.acc[0];
+        h_stats->prep_ms = tm.acc[1];
+        h_stats->beam_ms = tm.acc[2];
+        h_stats->rerank_ms = tm.acc[3];
     }
     return JX_OK;
 }

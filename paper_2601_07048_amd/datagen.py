@@ -13,7 +13,7 @@ Workloads
 ---------
 1  N=10,000  d=128  float32  64 isotropic Gaussians (centres N(0,1), sigma 0.3)
 2  N=1,000,000 d=128 uint8   256 Gaussians, mean 64 / std 30 overall, rounded, clipped
-3  N=1,000,000 d=960 float32 128 Gaussians, anisotropic spectrum lambda_i ~ i^-0.5
+3  N=1,000,000 d=960 float32 128 Gaussians, anisotropic: standard deviations ~ i^-0.5 (variances ~ 1/i)
 4  N=1,000,000 d=1536 float32 512 Gaussians, lambda_i ~ 1/i, L2-normalised
 5  stream of workload 2's generator, N grows to 10,000,000
 
@@ -31,7 +31,7 @@ SEED0 = 20260107
 _SPEC = {
     1: dict(d=128, dtype=np.float32, comps=64, kind="iso", centre_std=1.0, sigma=0.3),
     2: dict(d=128, dtype=np.uint8, comps=256, kind="u8", centre_mean=64.0, centre_std=24.0, sigma=18.0, decay=1.25),
-    3: dict(d=960, dtype=np.float32, comps=128, kind="aniso", centre_std=0.25, sigma=0.3, decay=0.5, normalise=False),
+    3: dict(d=960, dtype=np.float32, comps=128, kind="aniso", centre_std=1.0, sigma=0.3, decay=1.0, normalise=False),
     4: dict(d=1536, dtype=np.float32, comps=512, kind="aniso", centre_std=0.25, sigma=0.3, decay=1.0, normalise=True),
 }
 _SPEC[5] = _SPEC[2]

@@ -38,10 +38,11 @@ class Params(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [("hops", C.c_uint64), ("dist_evals", C.c_uint64), ("adj_bytes", C.c_uint64),
-                ("vec_bytes", C.c_uint64), ("rerank_bytes", C.c_uint64)]
+                ("vec_bytes", C.c_uint64), ("rerank_bytes", C.c_uint64), ("rotate_ms", C.c_float),
+                ("prep_ms", C.c_float), ("beam_ms", C.c_float), ("rerank_ms", C.c_float)]
 
     def as_dict(self):
-        return {k: int(getattr(self, k)) for k, _ in self._fields_}
+        return {k: (float if k.endswith("_ms") else int)(getattr(self, k)) for k, _ in self._fields_}
 
 
 class JxError(RuntimeError):
