@@ -514,11 +514,12 @@ static hipError_t launch_prune_pair(bool forward, const InsertArgs& a, hipStream
 
 template <int KIND>
 static hipError_t launch_prune_shape(bool forward, const InsertArgs& a, hipStream_t st) {
+    // same record-to-lane mapping as beamSearch: 2 chunks per lane up to 64 chunks
     const int nch = a.ds.nch;
-    if (nch <= 8) return launch_prune_pair<KIND, 8, 1>(forward, a, st);
-    if (nch <= 16) return launch_prune_pair<KIND, 16, 1>(forward, a, st);
-    if (nch <= 32) return launch_prune_pair<KIND, 32, 1>(forward, a, st);
-    if (nch <= 64) return launch_prune_pair<KIND, 64, 1>(forward, a, st);
+    if (nch <= 8) return launch_prune_pair<KIND, 4, 2>(forward, a, st);
+    if (nch <= 16) return launch_prune_pair<KIND, 8, 2>(forward, a, st);
+    if (nch <= 32) return launch_prune_pair<KIND, 16, 2>(forward, a, st);
+    if (nch <= 64) return launch_prune_pair<KIND, 32, 2>(forward, a, st);
     if (nch <= 128) return launch_prune_pair<KIND, 64, 2>(forward, a, st);
     if (nch <= 256) return launch_prune_pair<KIND, 64, 4>(forward, a, st);
     if (nch <= 384) return launch_prune_pair<KIND, 64, 6>(forward, a, st);

@@ -368,10 +368,10 @@ static hipError_t launch_rerank_shape(const RerankArgs& a, hipStream_t st) {
         hipLaunchKernelGGL((rerank_kernel<KIND, T, C>), grid, block, 0, st, a); \
         return hipGetLastError();                                               \
     }
-    if (nch <= 8) JX_RR(8, 1)
-    if (nch <= 16) JX_RR(16, 1)
-    if (nch <= 32) JX_RR(32, 1)
-    if (nch <= 64) JX_RR(64, 1)
+    if (nch <= 8) JX_RR(4, 2)
+    if (nch <= 16) JX_RR(8, 2)
+    if (nch <= 32) JX_RR(16, 2)
+    if (nch <= 64) JX_RR(32, 2)
     if (nch <= 128) JX_RR(64, 2)
     if (nch <= 256) JX_RR(64, 4)
     if (nch <= 384) JX_RR(64, 6)
