@@ -49,6 +49,8 @@ extern "C" {
 
 /* rule that picks the m-bit code for m > 1 (Sec. 5.1 says only "simple scalar
  * quantization") */
+#define JX_RULE_MAXCOS 0 /* the grid point whose direction is closest to r ("extended" codes): exact sweep
+                           over the breakpoints of the grid scale; 4-bit codes, dim <= 1170 */
 #define JX_RULE_MAXABS 1 /* grid scale t = (2^(m-1) - 1/2) / max_i |r_i| */
 
 /* error codes */
@@ -132,7 +134,8 @@ int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream);
  * bits: 1 or 4 (must equal params.quant_bits).  d_rotation: orthogonal matrix P,
  * float32 [dim][dim] row-major, applied as r = P (v - c).  d_centroid: c
  * (float32 [dim]) or NULL = mean of the current base set.  query_bits: width
- * B_q of the integer query (4 or 8).  rule: JX_RULE_MAXABS.
+ * B_q of the integer query (4 or 8).  rule: JX_RULE_MAXCOS or JX_RULE_MAXABS
+ * (ignored for 1-bit codes).
  * Per vector the record is  dim*bits/8 code bytes, zero padding to a multiple
  * of 16, then data_add = ||r||^2 and data_rescale = -2||r||^2/<xbar,r> as two
  * floats, then padding to a multiple of 16 bytes.  The matrix, centroid and

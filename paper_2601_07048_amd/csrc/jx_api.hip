@@ -595,6 +595,7 @@ static int encode_range(jx_index* idx, int64_t first, int64_t count, hipStream_t
         e.n = m;
         e.d = p.dim;
         e.bits = idx->quantized;
+        e.rule = idx->rule;
         e.codes = idx->d_codes + (size_t)(first + s0) * idx->code_stride;
         e.code_stride = idx->code_stride;
         e.code_bytes = idx->code_bytes;
@@ -614,7 +615,9 @@ int jx_quantize(jx_index* idx, int32_t bits, const float* d_rotation, const floa
     if (!p.quant_bits) return fail(JX_ESTATE, "the index was created with quant_bits = 0");
     if (bits != p.quant_bits) return fail(JX_EINVAL, "bits must equal params.quant_bits (%d)", p.quant_bits);
     if (query_bits != 4 && query_bits != 8) return fail(JX_EINVAL, "query_bits must be 4 or 8");
-    if (rule != JX_RULE_MAXABS) return fail(JX_EINVAL, "only JX_RULE_MAXABS is supported");
+    if (rule != JX_RULE_MAXABS && rule != JX_RULE_MAXCOS) return fail(JX_EINVAL, "unknown code rule");
+    if (rule == JX_RULE_MAXCOS && bits == 4 && p.dim * 7 > 8192)
+        return fail(JX_EINVAL, "JX_RULE_MAXCOS supports dim <= 1170; use JX_RULE_MAXABS");
     if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
     hipStream_t st = as_stream(stream);
     JX_HIP(hipMemcpyAsync(idx->d_P, d_rotation, (size_t)p.dim * p.dim * 4, hipMemcpyDeviceToDevice, st));
@@ -682,6 +685,7 @@ int jx_encode_rotated(jx_index* idx, const float* d_rot, int64_t n, uint8_t* d_c
     e.n = n;
     e.d = idx->p.dim;
     e.bits = idx->quantized;
+    e.rule = idx->rule;
     e.codes = d_codes;
     e.code_stride = idx->code_bytes;
     e.code_bytes = idx->code_bytes;

@@ -68,7 +68,7 @@ hipError_t launch_segment_heads(const uint64_t* keys, long long n, uint32_t* hea
 struct EncodeArgs {
     const float* rot;   // [n][d]
     long long n;
-    int d, bits;
+    int d, bits, rule;
     uint8_t* codes;     // record i at codes + i*code_stride
     long long code_stride;
     int code_bytes;     // d*bits/8

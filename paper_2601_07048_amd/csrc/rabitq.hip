@@ -173,8 +173,188 @@ __global__ void __launch_bounds__(256) encode_kernel(EncodeArgs a) {
     }
 }
 
+// ---- max-cosine rule (m > 1): the grid point whose direction is closest to r.
+// One workgroup per vector.  The breakpoints t = j/|r_i| (j = 1 .. 2^(m-1)-1),
+// where coordinate i steps to level j, are sorted in LDS (bitonic network on the
+// double-precision keys); prefix sums in sorted order give <xbar,|r|> and
+// ||xbar||^2 after every breakpoint; the cosine is evaluated at the end of every
+// group of equal t and the first maximum wins (smallest t).  The level of a
+// coordinate is then the number of its own breakpoints that are <= t.
+#define MC_CAP 8192
+
+__device__ __forceinline__ double block_scan_incl(double v, double* ws, int tid) {
+    // inclusive scan over the 256 threads of the workgroup
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        double o = __shfl_up(v, s, 64);
+        if (lane >= s) v += o;
+    }
+    if (lane == 63) ws[wave] = v;
+    __syncthreads();
+    double off = 0.0;
+    for (int w = 0; w < wave; w++) off += ws[w];
+    __syncthreads();
+    return v + off;
+}
+
+__global__ void __launch_bounds__(256) encode_maxcos_kernel(EncodeArgs a) {
+    extern __shared__ __align__(16) unsigned char dyn[];
+    double* key = reinterpret_cast<double*>(dyn);                       // [MC_CAP]
+    uint16_t* pay = reinterpret_cast<uint16_t*>(key + MC_CAP);          // [MC_CAP] (i << 3) | j
+    __shared__ double ws[8];
+    __shared__ double red_c[256];
+    __shared__ int red_k[256];
+    __shared__ double s_l1, s_l2, s_ip, s_best_t;
+    const int tid = threadIdx.x;
+    const long long v = blockIdx.x;
+    const float* r = a.rot + (size_t)v * a.d;
+    uint8_t* code = a.codes + (size_t)v * a.code_stride;
+    const int half = 1 << (a.bits - 1);
+    const int nbp = a.d * (half - 1);
+
+    // ---- sums and breakpoints
+    double l1 = 0.0, l2 = 0.0;
+    for (int i = tid; i < a.d; i += 256) {
+        const double x = fabs((double)r[i]);
+        l1 += x;
+        l2 += x * x;
+    }
+    for (int e = tid; e < MC_CAP; e += 256) {
+        double t = __builtin_inf();
+        uint16_t p = 0xFFFF;
+        if (e < nbp) {
+            const int i = e / (half - 1), j = e % (half - 1) + 1;
+            const double x = fabs((double)r[i]);
+            if (x > 0.0) {
+                t = (double)j / x;
+                p = (uint16_t)((i << 3) | j);
+            }
+        }
+        key[e] = t;
+        pay[e] = p;
+    }
+    {   // block sums (fixed order)
+        const double t1 = block_scan_incl(l1, ws, tid);
+        if (tid == 255) s_l1 = t1;
+        const double t2 = block_scan_incl(l2, ws, tid);
+        if (tid == 255) s_l2 = t2;
+    }
+    __syncthreads();
+    // ---- bitonic sort by (t, payload)
+    for (int k = 2; k <= MC_CAP; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int e = tid; e < MC_CAP / 2; e += 256) {
+                const int lo = ((e & ~(j - 1)) << 1) | (e & (j - 1));
+                const int hi = lo | j;
+                const bool up = (lo & k) == 0;
+                const double tl = key[lo], th = key[hi];
+                const uint16_t pl = pay[lo], ph = pay[hi];
+                const bool gt = tl > th || (tl == th && pl > ph);
+                if (gt == up) {
+                    key[lo] = th;
+                    key[hi] = tl;
+                    pay[lo] = ph;
+                    pay[hi] = pl;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // ---- prefix sums in sorted order: thread t owns the 32 consecutive entries [32t, 32t+32)
+    constexpr int PER = MC_CAP / 256;
+    const int e0 = tid * PER;
+    double sa = 0.0, sn = 0.0;
+    for (int e = e0; e < e0 + PER; e++) {
+        const uint16_t p = pay[e];
+        if (p != 0xFFFF) {
+            sa += fabs((double)r[p >> 3]);
+            sn += 2.0 * (double)(p & 7);
+        }
+    }
+    const double off_a = block_scan_incl(sa, ws, tid) - sa;
+    const double off_n = block_scan_incl(sn, ws, tid) - sn;
+    const double ip0 = 0.5 * s_l1, nn0 = 0.25 * (double)a.d;
+    double best = -1.0;
+    int best_k = 0x7FFFFFFF;
+    {
+        double ca = off_a, cn = off_n;
+        for (int e = e0; e < e0 + PER; e++) {
+            const uint16_t p = pay[e];
+            if (p == 0xFFFF) break;
+            ca += fabs((double)r[p >> 3]);
+            cn += 2.0 * (double)(p & 7);
+            const bool last_of_group = (e + 1 >= MC_CAP) || key[e + 1] != key[e];
+            if (last_of_group) {
+                const double c = (ip0 + ca) / sqrt(nn0 + cn);
+                if (c > best) {
+                    best = c;
+                    best_k = e;
+                }
+            }
+        }
+    }
+    red_c[tid] = best;
+    red_k[tid] = best_k;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) {
+            const double oc = red_c[tid + s];
+            const int ok = red_k[tid + s];
+            if (oc > red_c[tid] || (oc == red_c[tid] && ok < red_k[tid])) {
+                red_c[tid] = oc;
+                red_k[tid] = ok;
+            }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        // the all-zero-level grid (t -> 0+) competes too; a later cosine must be strictly larger
+        const double c0 = ip0 / sqrt(nn0);
+        s_best_t = (red_k[0] != 0x7FFFFFFF && red_c[0] > c0) ? key[red_k[0]] : 0.0;
+    }
+    __syncthreads();
+    const double bt = s_best_t;
+    // ---- codes: 8 consecutive coordinates per thread -> one dword
+    const double cb = ((double)(1 << a.bits) - 1.0) * 0.5;
+    double ip = 0.0;
+    for (int i0 = tid * 8; i0 < a.d; i0 += 2048) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const float x = r[i0 + j];
+            const double ax = fabs((double)x);
+            int lv = 0;
+            if (ax > 0.0)
+                while (lv + 1 < half && (double)(lv + 1) / ax <= bt) lv++;
+            const int u = x >= 0.0f ? half + lv : half - 1 - lv;
+            w |= (uint32_t)u << (4 * j);
+            ip += ((double)u - cb) * (double)x;
+        }
+        *reinterpret_cast<uint32_t*>(code + i0 / 2) = w;
+    }
+    const double tip = block_scan_incl(ip, ws, tid);
+    if (tid == 255) s_ip = tip;
+    __syncthreads();
+    for (int b = a.code_bytes + tid * 4; b < a.pad_to; b += 1024) *reinterpret_cast<uint32_t*>(code + b) = 0u;
+    if (tid == 0) {
+        float* m = reinterpret_cast<float*>(a.meta + (size_t)v * a.meta_stride);
+        m[0] = s_l2 > 0.0 ? (float)s_l2 : 0.f;
+        m[1] = s_l2 > 0.0 ? (float)(-2.0 * s_l2 / s_ip) : 0.f;
+        for (int b = 0; b < a.meta_pad; b += 4) m[2 + b / 4] = 0.f;
+    }
+}
+
 hipError_t launch_encode(const EncodeArgs& a, hipStream_t st) {
     if (a.n <= 0) return hipSuccess;
+    if (a.bits > 1 && a.rule == JX_RULE_MAXCOS) {
+        if (a.bits != 4 || a.d * ((1 << (a.bits - 1)) - 1) > MC_CAP) return hipErrorInvalidValue;
+        const size_t sh = (size_t)MC_CAP * (8 + 2);
+        hipError_t e = hipFuncSetAttribute((const void*)encode_maxcos_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(encode_maxcos_kernel, dim3((unsigned)a.n), dim3(256), sh, st, a);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(encode_kernel, dim3((unsigned)((a.n + 3) / 4)), dim3(256), 0, st, a);
     return hipGetLastError();
 }

@@ -18,7 +18,7 @@ NONE = 0xFFFFFFFF
 U8, F32 = 0, 1
 EXACT, RABITQ = 0, 1
 CAND_FRONTIER = 0
-RULE_MAXABS = 1
+RULE_MAXCOS, RULE_MAXABS = 0, 1
 MAX_L, MAX_R, MAX_BF_K = 512, 256, 128
 
 EXPORTS = [
@@ -149,8 +149,10 @@ class Index:
         return adj, deg
 
     # -- jx_quantize / jx_export_codes / stage entry points
-    def quantize(self, bits, rotation, centroid=None, query_bits=8, rule=RULE_MAXABS):
+    def quantize(self, bits, rotation, centroid=None, query_bits=8, rule=None):
         assert rotation.dtype == torch.float32 and rotation.shape == (self.dim, self.dim)
+        if rule is None:  # the max-cosine rule where the library offers it
+            rule = RULE_MAXCOS if (bits == 4 and self.dim * 7 <= 8192) else RULE_MAXABS
         with torch.cuda.device(self.device):
             _check(_lib.jx_quantize(self._h, C.c_int32(bits), _ptr(rotation), _ptr(centroid), C.c_int32(query_bits),
                                     C.c_int32(rule), _stream()))
