@@ -135,7 +135,9 @@ struct BList {
 
 // Evaluate d(pivot, c) for the live elements of one 64-wide chunk and discard
 // those with alpha * d(pivot,c) <= d(p,c).
-template <int KIND, int T, int CPL, bool IS_A>
+// CACHED: the candidates' vectors sit in an LDS cache, slot i = position i of
+// list A; the record "id" handed to the distance provider is then the slot.
+template <int KIND, int T, int CPL, bool IS_A, bool CACHED = false>
 __device__ __forceinline__ void kill_chunk(const QueryRegs<KIND, CPL, 0>& q, const DistSrc& ds, PruneLds* L, const BList& B,
                                            int c0, int n, float alpha, int g, int lig, int lane) {
     constexpr int G = 64 / T;
@@ -147,7 +149,7 @@ __device__ __forceinline__ void kill_chunk(const QueryRegs<KIND, CPL, 0>& q, con
     if (i < n) {
         if (IS_A) {
             alive = L->a_dead[i] == 0;
-            id = (uint32_t)L->a_key[i];
+            id = CACHED ? (uint32_t)i : (uint32_t)L->a_key[i];
         } else {
             alive = B.dead[i] == 0;
             id = B.ids[(size_t)i * B.id_stride];
@@ -186,7 +188,7 @@ __device__ __forceinline__ void kill_chunk(const QueryRegs<KIND, CPL, 0>& q, con
 
 // Alg. 3 over the merged sequence of A (LDS, nA entries) and B.  Returns the
 // number of selected ids (L->sel_id / L->sel_dist, selection order).
-template <int KIND, int T, int CPL>
+template <int KIND, int T, int CPL, bool CACHED = false>
 __device__ __forceinline__ int robust_prune_wave(const DistSrc& ds, PruneLds* L, int nA, const BList& B, int R, float alpha) {
     const int lane = lane_id();
     const int g = lane / T, lig = lane % T;
@@ -211,17 +213,128 @@ __device__ __forceinline__ int robust_prune_wave(const DistSrc& ds, PruneLds* L,
         if (hasB) kB = ((uint64_t)B.dbits[(size_t)iB * B.d_stride] << 32) | B.ids[(size_t)iB * B.id_stride];
         const bool takeA = kA < kB;
         const uint64_t kp = takeA ? kA : kB;
+        const uint32_t pid = (CACHED && takeA) ? (uint32_t)iA : (uint32_t)kp;  // record to load as the pivot
         if (takeA) iA++; else iB++;
-        const uint32_t pid = (uint32_t)kp;
         if (lane == 0) {
-            L->sel_id[nsel] = pid;
+            L->sel_id[nsel] = (uint32_t)kp;
             L->sel_dist[nsel] = (uint32_t)(kp >> 32);
         }
         nsel++;
         if (nsel >= R) break;
         load_query<KIND, T, CPL, 0>(q, ds, (int64_t)pid, lig);
-        for (int c0 = iA; c0 < nA; c0 += 64) kill_chunk<KIND, T, CPL, true>(q, ds, L, B, c0, nA, alpha, g, lig, lane);
-        for (int c0 = iB; c0 < B.n; c0 += 64) kill_chunk<KIND, T, CPL, false>(q, ds, L, B, c0, B.n, alpha, g, lig, lane);
+        for (int c0 = iA; c0 < nA; c0 += 64) kill_chunk<KIND, T, CPL, true, CACHED>(q, ds, L, B, c0, nA, alpha, g, lig, lane);
+        for (int c0 = iB; c0 < B.n; c0 += 64) kill_chunk<KIND, T, CPL, false, false>(q, ds, L, B, c0, B.n, alpha, g, lig, lane);
+    }
+    wave_sync();
+    return nsel;
+}
+
+
+// robustPrune for the common small case on uint8 vectors of exactly 128 bytes:
+// up to 128 candidates, already merged and sorted in L->a_key, their vectors
+// cached in LDS (slot i = position i, the cache covers whole tiles of 32 slots).
+//
+// The discard relation "i discards j" (alpha * d(i,j) <= d(p,j), i before j)
+// does not depend on the order of selection, so it is computed for all pairs at
+// once: d(i,j) = ||x_i||^2 + ||x_j||^2 - 2 <x_i,x_j> and the Gram matrix is a
+// dense contraction done on the matrix cores (int8 MFMA 32x32x16 on the
+// vectors shifted by -128, which leaves distances unchanged and exact).  Each
+// accumulator element gives one ballot = one 32-column stripe of the relation
+// for two rows.  The sequential part of Alg. 3 is then a scalar walk over
+// bit masks: take the first live candidate, clear everything it discards.
+typedef int i32x16_t __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ int prune_cached_u8_mfma(PruneLds* L, const unsigned char* vc, int M, int R, float alpha) {
+    const int lane = lane_id();
+    const int col = lane & 31, half = lane >> 5;
+    const int nt = (M + 31) >> 5;  // tiles of 32 slots
+    uint32_t* nrm = reinterpret_cast<uint32_t*>(L->a_tmp);          // [128] squared norms of the shifted vectors
+    uint32_t* kmat = reinterpret_cast<uint32_t*>(L->a_tmp) + 128;   // [96][4] discard relation, row i = mask over j (M <= 96)
+    // ---- norms: 4 lanes per slot (32 bytes each), 16 slots per step
+    {
+        const int sb = lane & 15, part = lane >> 4;
+        for (int s0 = 0; s0 < nt * 32; s0 += 16) {
+            const unsigned char* cv = vc + (size_t)(s0 + sb) * 128 + part * 32;
+            uint4 c0 = *reinterpret_cast<const uint4*>(cv), c1 = *reinterpret_cast<const uint4*>(cv + 16);
+            c0.x ^= 0x80808080u; c0.y ^= 0x80808080u; c0.z ^= 0x80808080u; c0.w ^= 0x80808080u;
+            c1.x ^= 0x80808080u; c1.y ^= 0x80808080u; c1.z ^= 0x80808080u; c1.w ^= 0x80808080u;
+            int32_t nn = 0;
+            nn = __builtin_amdgcn_sdot4((int)c0.x, (int)c0.x, nn, false);
+            nn = __builtin_amdgcn_sdot4((int)c0.y, (int)c0.y, nn, false);
+            nn = __builtin_amdgcn_sdot4((int)c0.z, (int)c0.z, nn, false);
+            nn = __builtin_amdgcn_sdot4((int)c0.w, (int)c0.w, nn, false);
+            nn = __builtin_amdgcn_sdot4((int)c1.x, (int)c1.x, nn, false);
+            nn = __builtin_amdgcn_sdot4((int)c1.y, (int)c1.y, nn, false);
+            nn = __builtin_amdgcn_sdot4((int)c1.z, (int)c1.z, nn, false);
+            nn = __builtin_amdgcn_sdot4((int)c1.w, (int)c1.w, nn, false);
+            nn += shfl_xor(nn, 16);
+            nn += shfl_xor(nn, 32);
+            if (part == 0) nrm[s0 + sb] = (uint32_t)nn;
+        }
+    }
+    wave_sync();
+    // ---- discard relation, tile by tile (rows ti <= columns tj)
+    for (int ti = 0; ti < nt; ti++) {
+        long af[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++)
+            af[ks] = *reinterpret_cast<const long*>(vc + (size_t)(ti * 32 + col) * 128 + ks * 16 + half * 8) ^ (long)0x8080808080808080ULL;
+        for (int tj = ti; tj < nt; tj++) {
+            i32x16_t acc;
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[e] = 0;
+#pragma unroll
+            for (int ks = 0; ks < 8; ks++) {
+                const long bf = *reinterpret_cast<const long*>(vc + (size_t)(tj * 32 + col) * 128 + ks * 16 + half * 8) ^ (long)0x8080808080808080ULL;
+                acc = __builtin_amdgcn_mfma_i32_32x32x16_i8(af[ks], bf, acc, 0, 0, 0);
+            }
+            const int j = tj * 32 + col;
+            const uint32_t nj = nrm[j];
+            const float d2 = j < M ? __uint_as_float((uint32_t)(L->a_key[j] >> 32)) : 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const int i = ti * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                const uint32_t dij = nrm[i] + nj - 2u * (uint32_t)acc[e];
+                const bool kill = j < M && (__fmul_rn(alpha, (float)dij) <= d2);
+                const uint64_t km = ballot(kill);
+                if (lane == 0) {
+                    const int r0 = ti * 32 + 8 * (e >> 2) + (e & 3);
+                    kmat[r0 * 4 + tj] = (uint32_t)km;
+                    kmat[(r0 + 4) * 4 + tj] = (uint32_t)(km >> 32);
+                }
+            }
+        }
+    }
+    wave_sync();
+    // ---- Alg. 3 on bit masks
+    uint64_t alive0 = M >= 64 ? ~0ull : ((1ull << M) - 1ull);
+    uint64_t alive1 = M <= 64 ? 0ull : (M >= 128 ? ~0ull : ((1ull << (M - 64)) - 1ull));
+    int nsel = 0;
+    while (nsel < R) {
+        int i;
+        if (alive0) {
+            i = __builtin_ctzll(alive0);
+            alive0 &= alive0 - 1;
+        } else if (alive1) {
+            i = 64 + __builtin_ctzll(alive1);
+            alive1 &= alive1 - 1;
+        } else {
+            break;
+        }
+        const uint64_t kp = L->a_key[i];
+        if (lane == 0) {
+            L->sel_id[nsel] = (uint32_t)kp;
+            L->sel_dist[nsel] = (uint32_t)(kp >> 32);
+        }
+        nsel++;
+        // words of columns left of the row's own tile were never written and are
+        // not needed: every slot before i is already selected or discarded
+        const int ti = i >> 5;
+        uint32_t w[4];
+#pragma unroll
+        for (int t = 0; t < 4; t++) w[t] = (t >= ti && t < nt) ? kmat[i * 4 + t] : 0u;
+        alive0 &= ~(((uint64_t)w[1] << 32) | w[0]);
+        alive1 &= ~(((uint64_t)w[3] << 32) | w[2]);
     }
     wave_sync();
     return nsel;
@@ -273,6 +386,7 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
     const int wave = threadIdx.x >> 6, lane = lane_id();
     const int g = lane / T, lig = lane % T;
     PruneLds* L = &lds[wave];
+    extern __shared__ __align__(16) unsigned char vcache[];  // INS_WPB x vec_cache_bytes
     const long long nseg = *a.nseg;
     const long long total = a.B * a.R;
     for (long long s = (long long)blockIdx.x * INS_WPB + wave; s < nseg; s += (long long)gridDim.x * INS_WPB) {
@@ -314,24 +428,63 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
             }
             wave_sync();
         }
-        for (int j = lane; j < deg; j += 64) {
+        // Small case (the usual one: a full row plus a few new edges): merge both
+        // lists into one, pull all candidate vectors into LDS once, and run the
+        // selection loop on the cache -- no global load on its critical path.
+        const int M = deg + m;
+        const bool cached = M <= INS_RA && (long long)M * a.ds.rec_stride <= a.vec_cache_bytes;
+        if (cached) {
+            for (int j = lane; j < m; j += 64)
+                L->a_tmp[deg + j] = ((uint64_t)reinterpret_cast<const uint32_t*>(a.keys + lo + j)[0] << 32) | a.vals[lo + j];
+            wave_sync();
+        }
+        const int nsort = cached ? M : deg;
+        for (int j = lane; j < nsort; j += 64) {
             const uint64_t k = L->a_tmp[j];
             int rank = 0;
-            for (int t = 0; t < deg; t++) rank += (L->a_tmp[t] < k) ? 1 : 0;
+            for (int t = 0; t < nsort; t++) rank += (L->a_tmp[t] < k) ? 1 : 0;
             L->a_key[rank] = k;
             L->a_dead[j] = 0;
         }
-        BList B;
-        B.ids = a.vals + lo;
-        B.dbits = reinterpret_cast<const uint32_t*>(a.keys + lo);
-        B.id_stride = 1;
-        B.d_stride = 2;
-        B.n = m;
-        B.dead = a.dead + lo;
-        for (int j = lane; j < m; j += 64) B.dead[j] = 0;
-        __threadfence_block();
-        wave_sync();
-        const int nsel = robust_prune_wave<KIND, T, CPL>(a.ds, L, deg, B, a.R, a.alpha);
+        int nsel;
+        if (cached) {
+            wave_sync();
+            unsigned char* vc = vcache + (size_t)wave * a.vec_cache_bytes;
+            const int nch = a.ds.nch;
+            for (int c = lane; c < M * nch; c += 64) {
+                const int sl = c / nch, ch = c - sl * nch;
+                const uint32_t id = (uint32_t)L->a_key[sl];
+                *reinterpret_cast<uint4*>(vc + (size_t)sl * a.ds.rec_stride + ch * 16) =
+                    load16(a.ds.recs + (size_t)id * (size_t)a.ds.rec_stride + (size_t)ch * 16);
+            }
+            DistSrc cds = a.ds;
+            cds.recs = vc;
+            cds.qrecs = vc;
+            BList none;
+            none.ids = nullptr;
+            none.dbits = nullptr;
+            none.id_stride = none.d_stride = 1;
+            none.n = 0;
+            none.dead = nullptr;
+            __threadfence_block();
+            wave_sync();
+            if (KIND == K_U8 && a.ds.rec_stride == 128 && M <= 96 && (long long)((M + 31) & ~31) * 128 <= a.vec_cache_bytes)
+                nsel = prune_cached_u8_mfma(L, vc, M, a.R, a.alpha);
+            else
+                nsel = robust_prune_wave<KIND, T, CPL, true>(cds, L, M, none, a.R, a.alpha);
+        } else {
+            BList B;
+            B.ids = a.vals + lo;
+            B.dbits = reinterpret_cast<const uint32_t*>(a.keys + lo);
+            B.id_stride = 1;
+            B.d_stride = 2;
+            B.n = m;
+            B.dead = a.dead + lo;
+            for (int j = lane; j < m; j += 64) B.dead[j] = 0;
+            __threadfence_block();
+            wave_sync();
+            nsel = robust_prune_wave<KIND, T, CPL, false>(a.ds, L, deg, B, a.R, a.alpha);
+        }
         for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? L->sel_id[j] : JX_NONE_ID;
         wave_sync();
     }
@@ -507,7 +660,8 @@ static hipError_t launch_prune_pair(bool forward, const InsertArgs& a, hipStream
     } else {
         long long want = (a.B * a.R + INS_WPB - 1) / INS_WPB;
         unsigned grid = (unsigned)(want < 4096 ? (want < 1 ? 1 : want) : 4096);
-        hipLaunchKernelGGL((reverse_merge_kernel<KIND, T, CPL>), dim3(grid), dim3(INS_WPB * 64), 0, st, a);
+        hipLaunchKernelGGL((reverse_merge_kernel<KIND, T, CPL>), dim3(grid), dim3(INS_WPB * 64),
+                           (size_t)INS_WPB * a.vec_cache_bytes, st, a);
     }
     return hipGetLastError();
 }

@@ -510,6 +510,9 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     a.vals = (uint32_t*)(W + w.vals0);
     a.heads = (const uint32_t*)(W + w.heads);
     a.nseg = (const uint32_t*)(W + w.counters);
+    // LDS room per wavefront for the vectors of a full row plus up to 32 new edges (96 x 128 bytes);
+    // larger merges take the path that reads from global memory
+    a.vec_cache_bytes = 12288;
     JX_HIP(jx::launch_forward_prune(p.dtype, a, st));
     // 3. one global sort by (target, distance, source)
     int tbits = 1;

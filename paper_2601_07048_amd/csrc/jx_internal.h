@@ -54,6 +54,7 @@ struct InsertArgs {
     uint32_t* vals;             // [B*R] edge sources
     const uint32_t* heads;      // segment starts (reverse merge)
     const uint32_t* nseg;       // number of segments (device)
+    int vec_cache_bytes;        // reverse merge: LDS bytes per wavefront for candidate vectors (0 = never cache)
 };
 
 hipError_t launch_entry_point(const void* vecs, int dtype, long long n, int d, double* partial, float* mean, double* dist,
