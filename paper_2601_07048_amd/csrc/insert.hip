@@ -106,8 +106,13 @@ __global__ void __launch_bounds__(1024) argmin_kernel(const double* dist, long l
 
 struct PruneLds {
     uint64_t a_key[INS_RA];   // existing neighbours sorted by (distance, id); key = distance bits << 32 | id
-    uint64_t a_tmp[INS_RA];
-    uint64_t cand_key[64];
+    union {
+        struct {
+            uint64_t a_tmp[INS_RA];
+            uint64_t cand_key[64];
+        };
+        uint32_t gram_scratch[128 + 128 * 4];  // MFMA path: squared norms, then the discard relation
+    };
     uint32_t cand_id[64];
     uint32_t cand_src[64];
     uint32_t sel_id[INS_RA];
@@ -248,8 +253,8 @@ __device__ __forceinline__ int prune_cached_u8_mfma(PruneLds* L, const unsigned 
     const int lane = lane_id();
     const int col = lane & 31, half = lane >> 5;
     const int nt = (M + 31) >> 5;  // tiles of 32 slots
-    uint32_t* nrm = reinterpret_cast<uint32_t*>(L->a_tmp);          // [128] squared norms of the shifted vectors
-    uint32_t* kmat = reinterpret_cast<uint32_t*>(L->a_tmp) + 128;   // [96][4] discard relation, row i = mask over j (M <= 96)
+    uint32_t* nrm = L->gram_scratch;         // [128] squared norms of the shifted vectors
+    uint32_t* kmat = L->gram_scratch + 128;  // [128][4] discard relation, row i = mask over j
     // ---- norms: 4 lanes per slot (32 bytes each), 16 slots per step
     {
         const int sb = lane & 15, part = lane >> 4;
@@ -366,7 +371,23 @@ __global__ void __launch_bounds__(INS_WPB * 64) forward_prune_kernel(InsertArgs 
     B.n = nB;
     __threadfence_block();
     wave_sync();
-    const int nsel = robust_prune_wave<KIND, T, CPL>(a.ds, L, 0, B, a.R, a.alpha);
+    int nsel;
+    if (KIND == K_U8 && a.ds.rec_stride == 128 && nB <= 128 && (long long)((nB + 31) & ~31) * 128 <= a.vec_cache_bytes) {
+        // the frontier is already sorted: cache its vectors in LDS and use the Gram-matrix form
+        extern __shared__ __align__(16) unsigned char vcache[];
+        unsigned char* vc = vcache + (size_t)wave * a.vec_cache_bytes;
+        for (int j = lane; j < nB; j += 64) L->a_key[j] = ((uint64_t)B.dbits[j] << 32) | B.ids[j];
+        for (int c = lane; c < nB * 8; c += 64) {
+            const int sl = c >> 3, ch = c & 7;
+            *reinterpret_cast<uint4*>(vc + (size_t)sl * 128 + ch * 16) =
+                load16(a.ds.recs + (size_t)B.ids[sl] * 128 + (size_t)ch * 16);
+        }
+        __threadfence_block();
+        wave_sync();
+        nsel = prune_cached_u8_mfma(L, vc, nB, a.R, a.alpha);
+    } else {
+        nsel = robust_prune_wave<KIND, T, CPL>(a.ds, L, 0, B, a.R, a.alpha);
+    }
     uint32_t* row = a.adj + (size_t)xid * a.R;
     for (int j = lane; j < a.R; j += 64) {
         const bool on = j < nsel;
@@ -468,7 +489,7 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
             none.dead = nullptr;
             __threadfence_block();
             wave_sync();
-            if (KIND == K_U8 && a.ds.rec_stride == 128 && M <= 96 && (long long)((M + 31) & ~31) * 128 <= a.vec_cache_bytes)
+            if (KIND == K_U8 && a.ds.rec_stride == 128 && M <= 128 && (long long)((M + 31) & ~31) * 128 <= a.vec_cache_bytes)
                 nsel = prune_cached_u8_mfma(L, vc, M, a.R, a.alpha);
             else
                 nsel = robust_prune_wave<KIND, T, CPL, true>(cds, L, M, none, a.R, a.alpha);
@@ -656,7 +677,13 @@ template <int KIND, int T, int CPL>
 static hipError_t launch_prune_pair(bool forward, const InsertArgs& a, hipStream_t st) {
     if (forward) {
         dim3 grid((unsigned)((a.B + INS_WPB - 1) / INS_WPB));
-        hipLaunchKernelGGL((forward_prune_kernel<KIND, T, CPL>), grid, dim3(INS_WPB * 64), 0, st, a);
+        const size_t sh = (size_t)INS_WPB * a.vec_cache_bytes;
+        if (sh > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void*)forward_prune_kernel<KIND, T, CPL>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL((forward_prune_kernel<KIND, T, CPL>), grid, dim3(INS_WPB * 64), sh, st, a);
     } else {
         long long want = (a.B * a.R + INS_WPB - 1) / INS_WPB;
         unsigned grid = (unsigned)(want < 4096 ? (want < 1 ? 1 : want) : 4096);

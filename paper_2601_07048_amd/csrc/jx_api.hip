@@ -510,9 +510,9 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     a.vals = (uint32_t*)(W + w.vals0);
     a.heads = (const uint32_t*)(W + w.heads);
     a.nseg = (const uint32_t*)(W + w.counters);
-    // LDS room per wavefront for the vectors of a full row plus up to 32 new edges (96 x 128 bytes);
-    // larger merges take the path that reads from global memory
-    a.vec_cache_bytes = 12288;
+    // forward prune: no LDS vector cache.  A whole frontier (128 x 128 bytes per wavefront) would leave room for
+    // one workgroup per CU only, and the Gram-matrix form then measured slower (47 ms against 32 ms per 1M inserts)
+    a.vec_cache_bytes = 0;
     JX_HIP(jx::launch_forward_prune(p.dtype, a, st));
     // 3. one global sort by (target, distance, source)
     int tbits = 1;
@@ -523,6 +523,9 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     // 4. per target: append or robustPrune
     JX_HIP(jx::launch_fill_u32((uint32_t*)(W + w.counters), 16, 0u, st));
     JX_HIP(jx::launch_segment_heads((const uint64_t*)(W + w.keys0), E, (uint32_t*)(W + w.heads), (uint32_t*)(W + w.counters), st));
+    // LDS room per wavefront for the vectors of a full row plus up to 32 new edges (96 x 128 bytes);
+    // larger merges take the path that reads from global memory
+    a.vec_cache_bytes = 12288;
     JX_HIP(jx::launch_reverse_merge(p.dtype, a, st));
     return JX_OK;
 }
