@@ -47,6 +47,9 @@ def _graphs(ref, g):
     (3000, 128, 32, 64, [1, 1, 2, 996, 2000], 0.5),
     (4000, 64, 16, 100, [1500, 2500], 0.25),
     (2500, 128, 70, 130, None, 0.3),      # R > 64: rows span two lane blocks
+    (6000, 128, 20, 40, None, 0.25),      # small merges: one or two 32-slot tiles of the Gram-matrix path
+    (6000, 128, 90, 128, None, 0.25),     # merges beyond 96 candidates: the global-memory path
+    (5000, 128, 64, 64, [2500, 2500], 0.25),
 ])
 def test_insert_u8_graph_bit_exact(jx, n, d, R, L, calls, growth):
     x = random_data(n, d, np.uint8, seed=n + R)
