@@ -224,7 +224,17 @@ def main():
         res = oix.search(q[:m], k, L_star, mode=1 if rabitq else 0, rerank=rerank)
         dt = time.perf_counter() - t0
         agree = float((res["ids"] == ids.cpu().numpy().view(np.uint32)[:m]).mean())
+        # the oracle's batch insertion on a bounded prefix of the same base set (uint8 workloads)
+        ins = None
+        if sp["u8"]:
+            pre = min(n, 50_000)
+            oins = oracle.Index(d, np.uint8, R, L_build, alpha, pre)
+            t0 = time.perf_counter()
+            oins.insert(dx[:pre].cpu().numpy())
+            ins = round(pre / (time.perf_counter() - t0), 1)
+            del oins
         cpu = {"value": round(m / dt, 1), "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "inserts_per_s": ins, "insert_sample": "first 50,000 base vectors inserted into an empty index" if ins else None,
                "sample": f"first {m} of the {nq} queries, same graph" + (" and codes" if rabitq else "") +
                          f", same L={L_star}; fraction of result ids identical to the GPU's: {agree:.4f}"}
 
