@@ -86,3 +86,66 @@ def test_fullsize_build_matches_oracle(jx, big):
     assert ref.entry == g.size()[1]
     bad = np.nonzero((u32(adj) != oadj).any(axis=1))[0]
     assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+
+
+def _device_base(workload, n, d):
+    dx = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    step = 16 * datagen.CHUNK
+    for s0 in range(0, n, step):
+        m = min(step, n - s0)
+        dx[s0:s0 + m] = torch.from_numpy(datagen.base(workload, m, start=s0)).cuda()
+    return dx
+
+
+@pytest.mark.parametrize("workload,bits,qbits", [(3, 4, 8), (4, 1, 4)])
+def test_fullsize_rabitq_sampled_against_oracle(jx, workload, bits, qbits):
+    """Workloads 3 and 4 at N = 1,000,000 (d = 960 with 4-bit codes, d = 1536
+    with 1-bit codes), built and quantised on the GPU.  The oracle runs the
+    estimated-distance beamSearch and the exact re-rank for sampled queries on
+    the exported graph and codes; distances differ only by the float32 rotation
+    of the query, so nearly all ids must agree and recall must match."""
+    n = 1_000_000
+    d = datagen.spec(workload)["d"]
+    dx = _device_base(workload, n, d)
+    q = datagen.queries(workload, 2000)
+    g = jx.Index(d, jx.F32, R, LB, 1.2, capacity=n, max_batch=n // 4 + 1, quant_bits=bits)
+    g.insert(dx)
+    P = datagen.rotation(workload)
+    g.quantize(bits, dev(P), None, query_bits=qbits)
+    torch.cuda.synchronize()
+    adj, deg = g.export_graph()
+    codes, meta, cen = [t.cpu().numpy() for t in g.export_codes()]
+    assert int(deg.max()) <= R and int(deg.min()) >= 1
+    x = dx.cpu().numpy()
+    ref = oracle.Index(d, np.float32, R, LB, 1.2, n)
+    ref.set_graph(x, u32(adj), g.size()[1])
+    ref.set_codes(bits, P, cen, codes, meta, qbits=qbits)
+    # codes of sampled vectors against the oracle's encoder fed with the oracle's double rotation
+    srows = np.random.default_rng(1).choice(n, 64, replace=False)
+    r32, r64 = oracle.rabitq_rotate(x[srows], P, cen)
+    rule = oracle.RULE_MAXCOS if bits == 4 else oracle.RULE_MAXABS
+    wc, wm, _ = oracle.rabitq_encode(r32, bits, rule)
+    same_rows = (wc == codes[srows]).all(axis=1)
+    if bits == 1:
+        U = np.stack([oracle.rabitq_unpack(c, 1, d) for c in wc])
+        G = np.stack([oracle.rabitq_unpack(c, 1, d) for c in codes[srows]])
+        assert (np.abs(r64[U != G]) < 1e-6).all()
+    else:
+        assert same_rows.mean() >= 0.9  # a different float32 rotation may move a vector to a neighbouring sweep optimum
+    assert np.allclose(meta[srows][same_rows], wm[same_rows], rtol=1e-4)
+    # searches
+    sample = np.arange(0, 2000, 10)
+    dq = dev(q)
+    L = 128
+    ids, dist, st = g.search(dq, 10, L, mode=jx.RABITQ, rerank=40, stats=True)
+    want = ref.search(q[sample], 10, L, mode=1, rerank=40)
+    gi = u32(ids)[sample]
+    assert (gi == want["ids"]).mean() >= 0.99
+    m = gi == want["ids"]
+    assert np.allclose(dist.cpu().numpy().astype(np.float64)[sample][m], want["dist"][m], rtol=1e-4)
+    gt, _ = g.bruteforce(dq, 10)
+    gtn = u32(gt)[sample]
+    assert abs(oracle.recall_at_k(gi, gtn) - oracle.recall_at_k(want["ids"], gtn)) <= 0.005
+    oid, od = oracle.bruteforce(x, q[sample[:4]], 10)
+    assert (u32(gt)[sample[:4]] == oid).mean() >= 0.95  # float32 vs double near-ties may swap neighbours
+    assert st["rerank_bytes"] == 40 * 2000 * d * 4
