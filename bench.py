@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--L", type=int, default=0, help="force the beam width (0 = smallest with recall >= target)")
     ap.add_argument("--query-bits", type=int, default=0, help="B_q of the integer query (0 = 8 for 4-bit codes, 4 for 1-bit codes)")
     ap.add_argument("--cpu-queries", type=int, default=2000, help="sample size of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--f16", action="store_true", help="store the float workloads (3, 4) as binary16 (App. D of the paper)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -86,15 +87,20 @@ def main():
     q = datagen.queries(gen_wl, nq)
     dq = torch.from_numpy(q).cuda()
     # the base set goes to the GPU chunk by chunk (the float workloads are several GB)
-    dx = torch.empty((n, d), dtype=torch.uint8 if sp["u8"] else torch.float32, device="cuda")
+    f16 = args.f16 and not sp["u8"]
+    tdt = torch.uint8 if sp["u8"] else (torch.float16 if f16 else torch.float32)
+    dx = torch.empty((n, d), dtype=tdt, device="cuda")
     step = 16 * datagen.CHUNK
     for s0 in range(0, n, step):
         m = min(step, n - s0)
-        dx[s0:s0 + m] = torch.from_numpy(datagen.base(gen_wl, m, start=s0)).cuda()
+        dx[s0:s0 + m] = torch.from_numpy(datagen.base(gen_wl, m, start=s0)).cuda().to(tdt)
+    if f16:
+        dq = dq.half()
+        q = q.astype(np.float16)
     log(f"[bench] workload {wl}: generated {n}x{d} base + {nq} queries in {time.time() - t0:.1f}s")
 
     batch = 100_000 if wl == 5 else n
-    g = jx.Index(d, jx.U8 if sp["u8"] else jx.F32, R, L_build, alpha, capacity=n,
+    g = jx.Index(d, jx.U8 if sp["u8"] else (jx.F16 if f16 else jx.F32), R, L_build, alpha, capacity=n,
                  max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"])
 
     def recall_of(ids, gt_np):
@@ -213,7 +219,7 @@ def main():
         import oracle
 
         adj, _ = g.export_graph()
-        oix = oracle.Index(d, np.uint8 if sp["u8"] else np.float32, R, L_build, alpha, n)
+        oix = oracle.Index(d, np.uint8 if sp["u8"] else (np.float16 if f16 else np.float32), R, L_build, alpha, n)
         oix.set_graph(dx.cpu().numpy(), adj.cpu().numpy().view(np.uint32), g.size()[1])
         if rabitq:
             codes, meta, cen = [t.cpu().numpy() for t in g.export_codes()]
@@ -238,7 +244,7 @@ def main():
                "sample": f"first {m} of the {nq} queries, same graph" + (" and codes" if rabitq else "") +
                          f", same L={L_star}; fraction of result ids identical to the GPU's: {agree:.4f}"}
 
-    cfg = {"workload": f"workload {wl}: N={n} {sp['text']}; {nq} queries; Vamana R=64 L_build=128 alpha=1.2 built on the GPU",
+    cfg = {"workload": f"workload {wl}: N={n} {sp['text']}{' (stored as binary16)' if f16 else ''}; {nq} queries; Vamana R=64 L_build=128 alpha=1.2 built on the GPU",
            "L": L_star, "recall_at_10": round(rec, 4), "recall_sweep": sweep,
            "build_inserts_per_s": round(n / t_build, 1), "build_s": round(t_build, 2)}
     if t_quant is not None:

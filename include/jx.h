@@ -39,6 +39,7 @@ extern "C" {
 /* element types of the stored vectors and of the queries */
 #define JX_U8 0  /* uint8, distances accumulated exactly in int32 */
 #define JX_F32 1 /* float32 */
+#define JX_F16 2 /* IEEE binary16 storage of float data (App. D); distances accumulated in float32 */
 
 /* search modes */
 #define JX_EXACT 0  /* distances on the stored full-precision vectors */
@@ -68,8 +69,8 @@ extern "C" {
 typedef struct jx_index jx_index; /* opaque, host side */
 
 typedef struct {
-    int32_t dim;       /* d.  uint8: multiple of 16; float32: multiple of 4 */
-    int32_t dtype;     /* JX_U8 | JX_F32 */
+    int32_t dim;       /* d.  uint8: multiple of 16; float32: multiple of 4; binary16: multiple of 8 */
+    int32_t dtype;     /* JX_U8 | JX_F32 | JX_F16 (queries have the same type) */
     int32_t R;         /* maximum out-degree (Sec. 3.1), 1..JX_MAX_R */
     int32_t L_build;   /* beam width used by insertion (Alg. 4), R.. JX_MAX_L is not required; 1..JX_MAX_L */
     float alpha;       /* robustPrune factor, applied to squared distances (Alg. 3) */
@@ -130,7 +131,7 @@ int jx_destroy(jx_index* idx);
 int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream);
 
 /*
- * RaBitQ quantisation of the current base set (Sec. 5.1), float32 data only.
+ * RaBitQ quantisation of the current base set (Sec. 5.1), float32 or binary16 data.
  * bits: 1 or 4 (must equal params.quant_bits).  d_rotation: orthogonal matrix P,
  * float32 [dim][dim] row-major, applied as r = P (v - c).  d_centroid: c
  * (float32 [dim]) or NULL = mean of the current base set.  query_bits: width

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libjx_oracle.so")
 _SRC = os.path.join(_HERE, "jx_oracle.c")
 
-U8, F32 = 0, 1
+U8, F32, F16 = 0, 1, 2
 NONE = 0xFFFFFFFF
 CAND_FRONTIER, CAND_VISITED = 0, 1
 FILTER_EXACT, FILTER_NONE = 0, 1
@@ -44,6 +44,7 @@ def lib():
         L = _lib
         L.orc_l2sq_u8.restype = C.c_int64
         L.orc_l2sq_f32.restype = C.c_double
+        L.orc_l2sq_f16.restype = C.c_double
         L.orc_robust_prune.restype = C.c_int
         L.orc_index_create.restype = C.c_void_p
         L.orc_index_size.restype = C.c_int64
@@ -67,6 +68,8 @@ def _dt(a) -> int:
         return U8
     if a.dtype == np.float32:
         return F32
+    if a.dtype == np.float16:
+        return F16
     raise TypeError(a.dtype)
 
 
@@ -84,6 +87,8 @@ def l2sq(a: np.ndarray, b: np.ndarray):
     b = np.ascontiguousarray(b)
     if a.dtype == np.uint8:
         return int(lib().orc_l2sq_u8(_p(a), _p(b), C.c_int(a.size)))
+    if a.dtype == np.float16:
+        return float(lib().orc_l2sq_f16(_p(a), _p(b), C.c_int(a.size)))
     return float(lib().orc_l2sq_f32(_p(a), _p(b), C.c_int(a.size)))
 
 
@@ -211,7 +216,7 @@ class Index:
     def __init__(self, d, dtype, R, L_build, alpha, capacity, cand_mode=CAND_FRONTIER, batch_growth=0.25):
         self.d, self.R, self.L_build, self.alpha, self.capacity = d, R, L_build, alpha, capacity
         self.np_dtype = np.dtype(dtype)
-        self.dtype = U8 if self.np_dtype == np.uint8 else F32
+        self.dtype = _dt(np.empty(0, self.np_dtype))
         self._h = C.c_void_p(lib().orc_index_create(C.c_int(d), C.c_int(self.dtype), C.c_int(R), C.c_int(L_build),
                                                     C.c_float(alpha), C.c_int64(capacity), C.c_int(cand_mode),
                                                     C.c_float(batch_growth)))
@@ -256,7 +261,7 @@ class Index:
         rc = lib().orc_index_quantize(self._h, C.c_int(bits), C.c_int(qbits), C.c_int(rule), _p(P), _p(c),
                                       C.c_int(_nt(nthreads)))
         if rc != 0:
-            raise RuntimeError("oracle quantize: float32 data only")
+            raise RuntimeError("oracle quantize: float data only")
         self.bits = bits
 
     def set_codes(self, bits, P, centroid, codes, meta, qbits=8):

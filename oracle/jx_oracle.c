@@ -35,6 +35,7 @@
 
 #define ORC_U8 0
 #define ORC_F32 1
+#define ORC_F16 2 /* IEEE binary16 storage (App. D: float datasets are stored as FP16); arithmetic in double */
 #define ORC_NONE 0xFFFFFFFFu
 
 #define ORC_CAND_FRONTIER 0
@@ -86,10 +87,39 @@ double orc_l2sq_f32(const float *a, const float *b, int d) {
     return s;
 }
 
-static size_t esize(int dtype) { return dtype == ORC_U8 ? 1 : 4; }
+/* exact value of an IEEE binary16 number */
+static double half_to_double(uint16_t h) {
+    const int sign = h >> 15, ex = (h >> 10) & 31, man = h & 1023;
+    double v;
+    if (ex == 0)
+        v = ldexp((double)man, -24);
+    else if (ex == 31)
+        v = man ? NAN : INFINITY;
+    else
+        v = ldexp((double)(man | 1024), ex - 25);
+    return sign ? -v : v;
+}
+
+double orc_l2sq_f16(const uint16_t *a, const uint16_t *b, int d) {
+    double s = 0.0;
+    for (int i = 0; i < d; i++) {
+        double t = half_to_double(a[i]) - half_to_double(b[i]);
+        s += t * t;
+    }
+    return s;
+}
+
+static size_t esize(int dtype) { return dtype == ORC_U8 ? 1 : (dtype == ORC_F16 ? 2 : 4); }
+
+static double elem(int dtype, const void *v, size_t i) {
+    if (dtype == ORC_U8) return (double)((const uint8_t *)v)[i];
+    if (dtype == ORC_F16) return half_to_double(((const uint16_t *)v)[i]);
+    return (double)((const float *)v)[i];
+}
 
 static double l2sq(int dtype, const void *a, const void *b, int d) {
     if (dtype == ORC_U8) return (double)orc_l2sq_u8((const uint8_t *)a, (const uint8_t *)b, d);
+    if (dtype == ORC_F16) return orc_l2sq_f16((const uint16_t *)a, (const uint16_t *)b, d);
     return orc_l2sq_f32((const float *)a, (const float *)b, d);
 }
 
@@ -636,16 +666,14 @@ int orc_index_insert(orc_index *x, const void *vecs, int64_t n, int nthreads) {
         double *mean = (double *)calloc((size_t)d, sizeof(double));
         for (int64_t i = 0; i < n; i++)
             for (int j = 0; j < d; j++)
-                mean[j] += x->dtype == ORC_U8 ? (double)((const uint8_t *)vecs)[(size_t)i * d + j]
-                                              : (double)((const float *)vecs)[(size_t)i * d + j];
+                mean[j] += elem(x->dtype, vecs, (size_t)i * d + j);
         for (int j = 0; j < d; j++) mean[j] = (double)(float)(mean[j] / (double)n);
         double best = INFINITY;
         uint32_t bi = 0;
         for (int64_t i = 0; i < n; i++) {
             double s = 0.0;
             for (int j = 0; j < d; j++) {
-                double v = x->dtype == ORC_U8 ? (double)((const uint8_t *)vecs)[(size_t)i * d + j]
-                                              : (double)((const float *)vecs)[(size_t)i * d + j];
+                double v = elem(x->dtype, vecs, (size_t)i * d + j);
                 double t = v - mean[j];
                 s += t * t;
             }
@@ -947,7 +975,7 @@ void orc_rabitq_unpack(const uint8_t *code, int bits, int d, uint8_t *out) {
  */
 int orc_index_quantize(orc_index *x, int bits, int qbits, int rule, const float *P, const float *centroid,
                        int nthreads) {
-    if (x->dtype != ORC_F32) return -1;
+    if (x->dtype == ORC_U8) return -1;
     const int d = x->d;
     free(x->P);
     free(x->c);
@@ -965,14 +993,22 @@ int orc_index_quantize(orc_index *x, int bits, int qbits, int rule, const float 
     } else {
         double *m = (double *)calloc((size_t)d, sizeof(double));
         for (int64_t i = 0; i < x->n; i++)
-            for (int j = 0; j < d; j++) m[j] += (double)((const float *)x->base)[(size_t)i * d + j];
+            for (int j = 0; j < d; j++) m[j] += elem(x->dtype, x->base, (size_t)i * d + j);
         for (int j = 0; j < d; j++) x->c[j] = (float)(m[j] / (double)(x->n > 0 ? x->n : 1));
         free(m);
     }
     x->codes = (uint8_t *)malloc((size_t)x->capacity * x->code_bytes + 16);
     x->meta = (float *)malloc(sizeof(float) * 2 * (size_t)x->capacity + 16);
     float *r = (float *)malloc(sizeof(float) * (size_t)x->n * d + 16);
-    orc_rabitq_rotate((const float *)x->base, x->n, d, x->P, x->c, r, NULL, nthreads);
+    const float *src = (const float *)x->base;
+    float *tmp = NULL;
+    if (x->dtype == ORC_F16) { /* binary16 -> float32 is exact */
+        tmp = (float *)malloc(sizeof(float) * (size_t)x->n * d + 16);
+        for (size_t i = 0; i < (size_t)x->n * d; i++) tmp[i] = (float)half_to_double(((const uint16_t *)x->base)[i]);
+        src = tmp;
+    }
+    orc_rabitq_rotate(src, x->n, d, x->P, x->c, r, NULL, nthreads);
+    free(tmp);
     orc_rabitq_encode(r, x->n, d, bits, rule, x->codes, x->meta, NULL, nthreads);
     free(r);
     return 0;
@@ -1047,7 +1083,14 @@ int orc_index_search(const orc_index *x, const void *queries, int64_t nq, int k,
             ctx.query = q;
             if (mode == 1) {
                 float m4[4];
-                orc_rabitq_rotate((const float *)q, 1, d, x->P, x->c, qr, NULL, 1);
+                if (x->dtype == ORC_F16) {
+                    float *qf = (float *)malloc(sizeof(float) * (size_t)d);
+                    for (int j = 0; j < d; j++) qf[j] = (float)half_to_double(((const uint16_t *)q)[j]);
+                    orc_rabitq_rotate(qf, 1, d, x->P, x->c, qr, NULL, 1);
+                    free(qf);
+                } else {
+                    orc_rabitq_rotate((const float *)q, 1, d, x->P, x->c, qr, NULL, 1);
+                }
                 orc_rabitq_query_prep(qr, d, x->bits, x->qbits, qint, m4);
                 ctx.mode = 1;
                 ctx.bits = x->bits;

@@ -27,7 +27,7 @@ namespace jx {
 #endif
 
 template <int KIND, int T, int CPL, int NREG, int QB>
-__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu((KIND <= K_F32 && NREG <= 2 && CPL <= 2) ? 6 : 1, 8)))
+__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu(((KIND <= K_F32 || KIND == K_F16) && NREG <= 2 && CPL <= 2) ? 6 : 1, 8)))
 beam_search_kernel(BeamArgs a) {
     constexpr int G = 64 / T;
     constexpr int UMAX = (KIND == K_RQ1) ? 4 : 8;  // 16-byte loads in flight per lane (the 1-bit path keeps its bit planes in registers)
@@ -316,6 +316,7 @@ hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_
     switch (kind) {
         case K_U8: return launch_shape<K_U8, 0>(a, st);
         case K_F32: return launch_shape<K_F32, 0>(a, st);
+        case K_F16: return launch_shape<K_F16, 0>(a, st);
         case K_RQ4: return qbits == 8 ? launch_shape<K_RQ4, 8>(a, st) : launch_shape<K_RQ4, 4>(a, st);
         case K_RQ1: return qbits == 8 ? launch_shape<K_RQ1, 8>(a, st) : launch_shape<K_RQ1, 4>(a, st);
     }

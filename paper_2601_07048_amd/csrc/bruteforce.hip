@@ -4,11 +4,11 @@
 // base set through LDS in tiles of 64 vectors.  Each thread accumulates a 4x4
 // block of the 64x64 distance tile (uint8: packed dot products, the distance is
 // ||a||^2 + ||q||^2 - 2<a,q> in exact integers; float32: sum of squared
-// differences).  A wavefront then folds each row of the tile into that query's
+// differences; binary16: packed half dot products in float32 and the same
+// norm form, clamped at 0).  A wavefront then folds each row of the tile into that query's
 // sorted top-k list in LDS; only candidates that beat the current k-th key do
 // any work.  A second kernel merges the per-slice lists.
-#include "jx_device.h"
-#include "jx_internal.h"
+#include "jx_distance.h"
 
 namespace jx {
 
@@ -29,7 +29,7 @@ __global__ void __launch_bounds__(256) bruteforce_tile_kernel(BfArgs a) {
     const int tx = tid & 15, ty = tid >> 4;
     const int k = a.k;
     const long long q0 = (long long)blockIdx.x * BF_TQ;
-    const int dw = (DT == JX_U8) ? a.d / 4 : a.d;  // dwords per vector
+    const int dw = (DT == JX_U8) ? a.d / 4 : (DT == JX_F16 ? a.d / 2 : a.d);  // dwords per vector
     const long long per = (a.n + a.nsplit - 1) / a.nsplit;
     const long long b_begin = (long long)blockIdx.y * per;
     const long long b_end = b_begin + per < a.n ? b_begin + per : a.n;
@@ -50,6 +50,7 @@ __global__ void __launch_bounds__(256) bruteforce_tile_kernel(BfArgs a) {
                 acc_f[i][j] = 0.f;
             }
         uint32_t nacc = 0;  // threads 0..63: ||b||^2, threads 64..127: ||q||^2
+        float naccf = 0.f;
         for (int ks = 0; ks < dw; ks += BF_KS) {
             // stage one slab of both tiles, transposed to [kk][row]
 #pragma unroll
@@ -65,11 +66,14 @@ __global__ void __launch_bounds__(256) bruteforce_tile_kernel(BfArgs a) {
                 Bs[kk][row] = bv;
             }
             __syncthreads();
-            if (DT == JX_U8 && tid < 128) {
+            if (DT != JX_F32 && tid < 128) {
 #pragma unroll
                 for (int kk = 0; kk < BF_KS; kk++) {
                     uint32_t v = tid < 64 ? Bs[kk][tid] : Qs[kk][tid - 64];
-                    nacc = __builtin_amdgcn_udot4(v, v, nacc, false);
+                    if (DT == JX_U8)
+                        nacc = __builtin_amdgcn_udot4(v, v, nacc, false);
+                    else
+                        naccf = hdot2(v, v, naccf);
                 }
             }
 #pragma unroll
@@ -86,6 +90,8 @@ __global__ void __launch_bounds__(256) bruteforce_tile_kernel(BfArgs a) {
                     for (int j = 0; j < 4; j++) {
                         if (DT == JX_U8) {
                             acc_u[i][j] = __builtin_amdgcn_udot4(qv[i], bv[j], acc_u[i][j], false);
+                        } else if (DT == JX_F16) {
+                            acc_f[i][j] = hdot2(qv[i], bv[j], acc_f[i][j]);
                         } else {
                             float df = __uint_as_float(qv[i]) - __uint_as_float(bv[j]);
                             acc_f[i][j] = fmaf(df, df, acc_f[i][j]);
@@ -94,9 +100,10 @@ __global__ void __launch_bounds__(256) bruteforce_tile_kernel(BfArgs a) {
             }
             __syncthreads();
         }
-        if (DT == JX_U8) {
-            if (tid < 64) bn[tid] = nacc;
-            else if (tid < 128) qn[tid - 64] = nacc;
+        if (DT != JX_F32) {
+            const uint32_t nv = (DT == JX_U8) ? nacc : __float_as_uint(naccf);
+            if (tid < 64) bn[tid] = nv;
+            else if (tid < 128) qn[tid - 64] = nv;
             __syncthreads();
         }
 #pragma unroll
@@ -106,6 +113,8 @@ __global__ void __launch_bounds__(256) bruteforce_tile_kernel(BfArgs a) {
                 uint32_t code;
                 if (DT == JX_U8)
                     code = qn[ty * 4 + i] + bn[tx * 4 + j] - 2u * acc_u[i][j];
+                else if (DT == JX_F16)
+                    code = f32_to_ordered(fmaxf(__uint_as_float(qn[ty * 4 + i]) + __uint_as_float(bn[tx * 4 + j]) - 2.f * acc_f[i][j], 0.f));
                 else
                     code = f32_to_ordered(acc_f[i][j]);
                 Dt[ty * 4 + i][tx * 4 + j] = code;
@@ -201,6 +210,13 @@ hipError_t launch_bruteforce(const BfArgs& a, hipStream_t st) {
         (void)hipFuncSetAttribute((const void*)kt, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         hipLaunchKernelGGL(kt, grid, dim3(256), sh, st, a);
         auto km = bruteforce_merge_kernel<JX_U8>;
+        (void)hipFuncSetAttribute((const void*)km, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipLaunchKernelGGL(km, dim3((unsigned)a.nq), dim3(64), shm, st, a);
+    } else if (a.dtype == JX_F16) {
+        auto kt = bruteforce_tile_kernel<JX_F16>;
+        (void)hipFuncSetAttribute((const void*)kt, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipLaunchKernelGGL(kt, grid, dim3(256), sh, st, a);
+        auto km = bruteforce_merge_kernel<JX_F16>;
         (void)hipFuncSetAttribute((const void*)km, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         hipLaunchKernelGGL(km, dim3((unsigned)a.nq), dim3(64), shm, st, a);
     } else {

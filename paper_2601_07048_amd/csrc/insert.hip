@@ -31,6 +31,13 @@ namespace jx {
 // ------------------------------------------------------------------ entry point
 
 template <int DT>
+__device__ __forceinline__ double elem_f64(const void* vecs, size_t i) {
+    if (DT == JX_U8) return (double)reinterpret_cast<const uint8_t*>(vecs)[i];
+    if (DT == JX_F16) return (double)(float)reinterpret_cast<const _Float16*>(vecs)[i];
+    return (double)reinterpret_cast<const float*>(vecs)[i];
+}
+
+template <int DT>
 __global__ void __launch_bounds__(256) col_partial_kernel(const void* vecs, long long n, int d, int nblk, double* partial) {
     const long long per = (n + nblk - 1) / nblk;
     const long long r0 = (long long)blockIdx.x * per;
@@ -38,10 +45,7 @@ __global__ void __launch_bounds__(256) col_partial_kernel(const void* vecs, long
     for (int j = threadIdx.x; j < d; j += 256) {
         double s = 0.0;
         for (long long i = r0; i < r1; i++) {
-            if (DT == JX_U8)
-                s += (double)reinterpret_cast<const uint8_t*>(vecs)[(size_t)i * d + j];
-            else
-                s += (double)reinterpret_cast<const float*>(vecs)[(size_t)i * d + j];
+            s += elem_f64<DT>(vecs, (size_t)i * d + j);
         }
         partial[(size_t)blockIdx.x * d + j] = s;
     }
@@ -62,8 +66,7 @@ __global__ void __launch_bounds__(256) dist_to_mean_kernel(const void* vecs, lon
     const int lane = lane_id();
     double s = 0.0;
     for (int j = lane; j < d; j += 64) {
-        double v = (DT == JX_U8) ? (double)reinterpret_cast<const uint8_t*>(vecs)[(size_t)i * d + j]
-                                 : (double)reinterpret_cast<const float*>(vecs)[(size_t)i * d + j];
+        double v = elem_f64<DT>(vecs, (size_t)i * d + j);
         double t = v - (double)mean[j];
         s += t * t;
     }
@@ -644,11 +647,15 @@ hipError_t launch_entry_point(const void* vecs, int dtype, long long n, int d, d
     if (nblk < 1) nblk = 1;
     if (dtype == JX_U8)
         hipLaunchKernelGGL(col_partial_kernel<JX_U8>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
+    else if (dtype == JX_F16)
+        hipLaunchKernelGGL(col_partial_kernel<JX_F16>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
     else
         hipLaunchKernelGGL(col_partial_kernel<JX_F32>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
     hipLaunchKernelGGL(mean_finalize_kernel, dim3((d + 255) / 256), dim3(256), 0, st, partial, nblk, d, n, mean);
     if (dtype == JX_U8)
         hipLaunchKernelGGL(dist_to_mean_kernel<JX_U8>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, vecs, n, d, mean, dist);
+    else if (dtype == JX_F16)
+        hipLaunchKernelGGL(dist_to_mean_kernel<JX_F16>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, vecs, n, d, mean, dist);
     else
         hipLaunchKernelGGL(dist_to_mean_kernel<JX_F32>, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, vecs, n, d, mean, dist);
     hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, st, dist, n, out_id);
@@ -662,6 +669,8 @@ hipError_t launch_column_mean(const void* vecs, int dtype, long long n, int d, d
     if (nblk < 1) nblk = 1;
     if (dtype == JX_U8)
         hipLaunchKernelGGL(col_partial_kernel<JX_U8>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
+    else if (dtype == JX_F16)
+        hipLaunchKernelGGL(col_partial_kernel<JX_F16>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
     else
         hipLaunchKernelGGL(col_partial_kernel<JX_F32>, dim3(nblk), dim3(256), 0, st, vecs, n, d, nblk, partial);
     hipLaunchKernelGGL(mean_finalize_kernel, dim3((d + 255) / 256), dim3(256), 0, st, partial, nblk, d, n, mean);
@@ -708,11 +717,15 @@ static hipError_t launch_prune_shape(bool forward, const InsertArgs& a, hipStrea
 }
 
 hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st) {
-    return dtype == JX_U8 ? launch_prune_shape<K_U8>(true, a, st) : launch_prune_shape<K_F32>(true, a, st);
+    if (dtype == JX_U8) return launch_prune_shape<K_U8>(true, a, st);
+    if (dtype == JX_F16) return launch_prune_shape<K_F16>(true, a, st);
+    return launch_prune_shape<K_F32>(true, a, st);
 }
 
 hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st) {
-    return dtype == JX_U8 ? launch_prune_shape<K_U8>(false, a, st) : launch_prune_shape<K_F32>(false, a, st);
+    if (dtype == JX_U8) return launch_prune_shape<K_U8>(false, a, st);
+    if (dtype == JX_F16) return launch_prune_shape<K_F16>(false, a, st);
+    return launch_prune_shape<K_F32>(false, a, st);
 }
 
 // Sorts n (key, value) pairs on key bits [0, nbits), stable.  The result is in

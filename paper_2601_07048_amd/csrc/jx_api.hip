@@ -34,13 +34,20 @@ struct Layout {
     int vec_bytes, code_bytes, meta_chunk, code_stride;
 };
 
+int elem_bytes(int dtype) { return dtype == JX_U8 ? 1 : (dtype == JX_F16 ? 2 : 4); }
+
+// distance provider of the exact path for a storage type (0 uint8, 1 float32, 4 binary16)
+int exact_kind(int dtype) { return dtype == JX_U8 ? 0 : (dtype == JX_F16 ? 4 : 1); }
+
 int check_params(const jx_params* p) {
     if (!p) return fail(JX_EINVAL, "params is NULL");
-    if (p->dtype != JX_U8 && p->dtype != JX_F32) return fail(JX_EINVAL, "dtype must be JX_U8 or JX_F32");
+    if (p->dtype != JX_U8 && p->dtype != JX_F32 && p->dtype != JX_F16)
+        return fail(JX_EINVAL, "dtype must be JX_U8, JX_F32 or JX_F16");
     if (p->dim <= 0) return fail(JX_EINVAL, "dim must be positive");
     if (p->dtype == JX_U8 && p->dim % 16) return fail(JX_EINVAL, "uint8 dim must be a multiple of 16");
     if (p->dtype == JX_F32 && p->dim % 4) return fail(JX_EINVAL, "float32 dim must be a multiple of 4");
-    int vb = p->dim * (p->dtype == JX_U8 ? 1 : 4);
+    if (p->dtype == JX_F16 && p->dim % 8) return fail(JX_EINVAL, "binary16 dim must be a multiple of 8");
+    int vb = p->dim * elem_bytes(p->dtype);
     if (vb > 384 * 16) return fail(JX_EINVAL, "vectors larger than 6144 bytes are not supported");
     if (p->R < 1 || p->R > JX_MAX_R) return fail(JX_EINVAL, "R out of range");
     if (p->L_build < 1 || p->L_build > JX_MAX_L) return fail(JX_EINVAL, "L_build out of range");
@@ -50,7 +57,7 @@ int check_params(const jx_params* p) {
     if (p->max_batch < 1) return fail(JX_EINVAL, "max_batch must be positive");
     if (p->quant_bits != 0 && p->quant_bits != 1 && p->quant_bits != 4)
         return fail(JX_EINVAL, "quant_bits must be 0, 1 or 4");
-    if (p->quant_bits && p->dtype != JX_F32) return fail(JX_EINVAL, "RaBitQ needs float32 data");
+    if (p->quant_bits && p->dtype == JX_U8) return fail(JX_EINVAL, "RaBitQ needs float data (float32 or binary16)");
     if (p->quant_bits && p->dim % 32) return fail(JX_EINVAL, "RaBitQ needs dim to be a multiple of 32");
     if (!(p->batch_growth >= 0.0f) || p->batch_growth > 1.0f) return fail(JX_EINVAL, "batch_growth must be in [0, 1]");
     return JX_OK;
@@ -107,7 +114,7 @@ int64_t query_work(const jx_params* p, int64_t B, int meta_chunk, QueryWork* w) 
 }
 
 void layout(const jx_params* p, Layout* L) {
-    L->vec_bytes = p->dim * (p->dtype == JX_U8 ? 1 : 4);
+    L->vec_bytes = p->dim * elem_bytes(p->dtype);
     L->code_bytes = p->quant_bits ? p->dim * p->quant_bits / 8 : 0;
     L->meta_chunk = (L->code_bytes + 15) / 16;
     L->code_stride = p->quant_bits ? (L->meta_chunk + 1) * 16 : 0;
@@ -327,7 +334,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         a.out_dist = d_out_dist;
         a.out_k = out_k;
         tm.begin();
-        JX_HIP(jx::launch_beam_search(p.dtype == JX_U8 ? 0 : 1, 0, a, st));
+        JX_HIP(jx::launch_beam_search(exact_kind(p.dtype), 0, a, st));
         tm.end(2);
     } else {
         QueryWork qw;
@@ -337,9 +344,9 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         const int qrec_stride = 16 + nplanes * qw.plane_stride;
         for (int64_t q0 = 0; q0 < nq; q0 += p.max_batch) {
             const int64_t m = nq - q0 < p.max_batch ? nq - q0 : p.max_batch;
-            const float* qs = (const float*)d_queries + (size_t)q0 * p.dim;
+            const uint8_t* qs = (const uint8_t*)d_queries + (size_t)q0 * idx->vec_bytes;
             tm.begin();
-            JX_HIP(jx::launch_rotate(qs, m, p.dim, idx->d_P, idx->d_centroid, (float*)(W + qw.rot), st));
+            JX_HIP(jx::launch_rotate(qs, p.dtype == JX_F16, m, p.dim, idx->d_P, idx->d_centroid, (float*)(W + qw.rot), st));
             tm.end(0);
             jx::QueryPrepArgs qp;
             memset(&qp, 0, sizeof qp);
@@ -491,7 +498,7 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     b.out_dist = (float*)(W + w.cand_dist);
     b.out_k = p.L_build;
     b.stats = nullptr;
-    JX_HIP(jx::launch_beam_search(p.dtype == JX_U8 ? 0 : 1, 0, b, st));
+    JX_HIP(jx::launch_beam_search(exact_kind(p.dtype), 0, b, st));
     // 2. robustPrune of the frontier, new rows, reverse edges
     jx::InsertArgs a;
     memset(&a, 0, sizeof a);
@@ -593,8 +600,8 @@ static int encode_range(jx_index* idx, int64_t first, int64_t count, hipStream_t
     float* rot = (float*)(W + part);
     for (int64_t s0 = 0; s0 < count; s0 += slice) {
         const int64_t m = count - s0 < slice ? count - s0 : slice;
-        const float* src = (const float*)(idx->d_vecs + (size_t)(first + s0) * idx->vec_bytes);
-        JX_HIP(jx::launch_rotate(src, m, p.dim, idx->d_P, idx->d_centroid, rot, st));
+        const uint8_t* src = idx->d_vecs + (size_t)(first + s0) * idx->vec_bytes;
+        JX_HIP(jx::launch_rotate(src, p.dtype == JX_F16, m, p.dim, idx->d_P, idx->d_centroid, rot, st));
         jx::EncodeArgs e;
         memset(&e, 0, sizeof e);
         e.rot = rot;
@@ -675,7 +682,7 @@ int jx_rotate(jx_index* idx, const float* d_in, int64_t n, float* d_out, void* s
     if (n < 0) return fail(JX_EINVAL, "n < 0");
     if (n == 0) return JX_OK;
     if (!d_in || !d_out) return fail(JX_EINVAL, "NULL argument");
-    JX_HIP(jx::launch_rotate(d_in, n, idx->p.dim, idx->d_P, idx->d_centroid, d_out, as_stream(stream)));
+    JX_HIP(jx::launch_rotate(d_in, false, n, idx->p.dim, idx->d_P, idx->d_centroid, d_out, as_stream(stream)));
     return JX_OK;
 }
 

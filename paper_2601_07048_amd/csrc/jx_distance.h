@@ -6,13 +6,20 @@
 //   K_RQ4 : 4-bit RaBitQ codes, packed 4-bit dot products against the two
 //           nibble planes of an 8-bit integer query
 //   K_RQ1 : 1-bit RaBitQ codes, AND + popcount against the query's bit planes
+//   K_F16 : binary16 vectors, ||a||^2 - 2<a,q> + ||q||^2 with packed half dot
+//           products accumulated in float32 (clamped at 0)
 #pragma once
 #include "jx_device.h"
 #include "jx_internal.h"
 
 namespace jx {
 
-enum { K_U8 = 0, K_F32 = 1, K_RQ4 = 2, K_RQ1 = 3 };
+enum { K_U8 = 0, K_F32 = 1, K_RQ4 = 2, K_RQ1 = 3, K_F16 = 4 };
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float hdot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), c, false);
+}
 
 template <int KIND, int CPL, int QB>
 struct QueryRegs {
@@ -22,13 +29,14 @@ struct QueryRegs {
     uint32_t cmask[CPL];  // RaBitQ: all-ones for code chunks, 0 for the meta chunk and beyond
     // per-query scalars
     int32_t qq;           // U8: sum q^2
+    float qqf;            // F16: sum q^2
     float lo, delta, qadd, qsumq;
 };
 
 template <int KIND, int T, int CPL, int QB>
 __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const DistSrc& a, int64_t qi, int lig) {
     const uint8_t* base = a.qrecs + qi * a.qrec_stride;
-    if constexpr (KIND == K_U8 || KIND == K_F32) {
+    if constexpr (KIND == K_U8 || KIND == K_F32 || KIND == K_F16) {
 #pragma unroll
         for (int j = 0; j < CPL; j++) {
             int ch = lig + T * j;
@@ -44,6 +52,12 @@ __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const Di
 #pragma unroll
             for (int i = 0; i < 4 * CPL; i++) s = (int32_t)__builtin_amdgcn_udot4(q.w[i], q.w[i], (uint32_t)s, false);
             q.qq = group_sum<T>(s);
+        }
+        if constexpr (KIND == K_F16) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4 * CPL; i++) s = hdot2(q.w[i], q.w[i], s);
+            q.qqf = group_sum<T>(s);
         }
     } else {
         constexpr int PL = QueryRegs<KIND, CPL, QB>::PLANES;
@@ -125,6 +139,22 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
             int32_t part = (int32_t)aa - 2 * (int32_t)aq;
             part = group_sum<T>(part);
             dist_code = (uint32_t)(part + q.qq);
+        } else if constexpr (KIND == K_F16) {
+            float aa = 0.f, aq = 0.f;
+#pragma unroll
+            for (int j = 0; j < CPL; j++) {
+                const uint4 v = data[u][j];
+                aa = hdot2(v.x, v.x, aa);
+                aa = hdot2(v.y, v.y, aa);
+                aa = hdot2(v.z, v.z, aa);
+                aa = hdot2(v.w, v.w, aa);
+                aq = hdot2(v.x, q.w[4 * j + 0], aq);
+                aq = hdot2(v.y, q.w[4 * j + 1], aq);
+                aq = hdot2(v.z, q.w[4 * j + 2], aq);
+                aq = hdot2(v.w, q.w[4 * j + 3], aq);
+            }
+            float part = group_sum<T>(aa - 2.f * aq);
+            dist_code = f32_to_ordered(fmaxf(part + q.qqf, 0.f));
         } else if constexpr (KIND == K_F32) {
             float acc = 0.f;
 #pragma unroll

@@ -21,7 +21,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define GK 32
 #define GLD 36  // padded LDS row (floats)
 
-__global__ void __launch_bounds__(256) rotate_gemm_kernel(const float* __restrict__ in, long long n, int d,
+template <bool IN_F16>
+__global__ void __launch_bounds__(256) rotate_gemm_kernel(const void* __restrict__ in_v, long long n, int d,
                                                           const float* __restrict__ P, const float* __restrict__ c,
                                                           float* __restrict__ out) {
     __shared__ __align__(16) float As[GT][GLD];
@@ -46,7 +47,13 @@ __global__ void __launch_bounds__(256) rotate_gemm_kernel(const float* __restric
             float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
             if (k0 + c4 < d) {
                 if (m0 + row < n) {
-                    const float4 v = *reinterpret_cast<const float4*>(in + (size_t)(m0 + row) * d + k0 + c4);
+                    float4 v;
+                    if (IN_F16) {
+                        const _Float16* hp = reinterpret_cast<const _Float16*>(in_v) + (size_t)(m0 + row) * d + k0 + c4;
+                        v = make_float4((float)hp[0], (float)hp[1], (float)hp[2], (float)hp[3]);
+                    } else {
+                        v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(in_v) + (size_t)(m0 + row) * d + k0 + c4);
+                    }
                     const float4 cc = *reinterpret_cast<const float4*>(c + k0 + c4);
                     a = make_float4(v.x - cc.x, v.y - cc.y, v.z - cc.z, v.w - cc.w);
                 }
@@ -88,10 +95,14 @@ __global__ void __launch_bounds__(256) rotate_gemm_kernel(const float* __restric
             }
 }
 
-hipError_t launch_rotate(const float* in, long long n, int d, const float* P, const float* c, float* out, hipStream_t st) {
+hipError_t launch_rotate(const void* in, bool in_f16, long long n, int d, const float* P, const float* c, float* out,
+                         hipStream_t st) {
     if (n <= 0) return hipSuccess;
     dim3 grid((unsigned)((d + GT - 1) / GT), (unsigned)((n + GT - 1) / GT));
-    hipLaunchKernelGGL(rotate_gemm_kernel, grid, dim3(256), 0, st, in, n, d, P, c, out);
+    if (in_f16)
+        hipLaunchKernelGGL(rotate_gemm_kernel<true>, grid, dim3(256), 0, st, in, n, d, P, c, out);
+    else
+        hipLaunchKernelGGL(rotate_gemm_kernel<false>, grid, dim3(256), 0, st, in, n, d, P, c, out);
     return hipGetLastError();
 }
 
@@ -561,7 +572,9 @@ static hipError_t launch_rerank_shape(const RerankArgs& a, hipStream_t st) {
 
 hipError_t launch_rerank(int dtype, const RerankArgs& a, hipStream_t st) {
     if (a.nq <= 0) return hipSuccess;
-    return dtype == JX_U8 ? launch_rerank_shape<K_U8>(a, st) : launch_rerank_shape<K_F32>(a, st);
+    if (dtype == JX_U8) return launch_rerank_shape<K_U8>(a, st);
+    if (dtype == JX_F16) return launch_rerank_shape<K_F16>(a, st);
+    return launch_rerank_shape<K_F32>(a, st);
 }
 
 }  // namespace jx

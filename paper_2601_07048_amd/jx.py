@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("JX_LIB", os.path.join(_HERE, "libjx.so"))
 
 NONE = 0xFFFFFFFF
-U8, F32 = 0, 1
+U8, F32, F16 = 0, 1, 2
 EXACT, RABITQ = 0, 1
 CAND_FRONTIER = 0
 RULE_MAXCOS, RULE_MAXABS = 0, 1
@@ -84,7 +84,7 @@ def _stream():
 
 
 def _torch_dtype(dtype):
-    return torch.uint8 if dtype == U8 else torch.float32
+    return {U8: torch.uint8, F32: torch.float32, F16: torch.float16}[dtype]
 
 
 def jx_arena_bytes(params: Params) -> int:

@@ -33,9 +33,13 @@ def oracle_index(x, R, L_build, alpha=1.2):
     return ix
 
 
+def jx_dtype(jx, x):
+    return {np.dtype(np.uint8): jx.U8, np.dtype(np.float32): jx.F32, np.dtype(np.float16): jx.F16}[x.dtype]
+
+
 def gpu_index_from_oracle(jx, x, ix, R, L_build, quant_bits=0, capacity=None):
     adj, deg = ix.graph()
-    g = jx.Index(x.shape[1], jx.U8 if x.dtype == np.uint8 else jx.F32, R, L_build, 1.2,
+    g = jx.Index(x.shape[1], jx_dtype(jx, x), R, L_build, 1.2,
                  capacity=capacity or len(x), max_batch=max(1024, len(x)), quant_bits=quant_bits)
     g.import_graph(dev(x), dev(adj), ix.entry)
     return g

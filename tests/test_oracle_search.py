@@ -32,6 +32,15 @@ def test_distance_matches_numpy():
     assert oracle.l2sq(x, x) == 0.0
 
 
+def test_oracle_half_distance_is_exact():
+    rng = np.random.default_rng(0)
+    a = rng.standard_normal(96).astype(np.float16)
+    b = rng.standard_normal(96).astype(np.float16)
+    assert oracle.l2sq(a, b) == float(((a.astype(np.float64) - b.astype(np.float64)) ** 2).sum())
+    h = np.array([0, 1, 0x03FF, 0x0400, 0x7BFF, 0x8001, 0xFBFF], np.uint16).view(np.float16)  # subnormals, extremes
+    assert oracle.l2sq(h, np.zeros(7, np.float16)) == float((h.astype(np.float64) ** 2).sum())
+
+
 @pytest.mark.parametrize("dtype", [np.uint8, np.float32])
 def test_bruteforce_matches_scipy(dtype):
     from scipy.spatial.distance import cdist
