@@ -56,6 +56,7 @@ def lib():
         L.orc_rabitq_est_float.restype = C.c_double
         L.orc_rabitq_est_int.restype = C.c_float
         L.orc_num_threads.restype = C.c_int
+        L.orc_index_deleted_count.restype = C.c_int64
     return _lib
 
 
@@ -254,6 +255,17 @@ class Index:
         deg = np.empty(n, np.uint32)
         lib().orc_index_get_graph(self._h, _p(adj), _p(deg))
         return adj, deg
+
+    def delete(self, ids):
+        ids = np.ascontiguousarray(ids, dtype=np.uint32)
+        lib().orc_index_delete(self._h, _p(ids), C.c_int64(ids.size))
+
+    @property
+    def n_deleted(self):
+        return int(lib().orc_index_deleted_count(self._h))
+
+    def consolidate(self, nthreads=None):
+        lib().orc_index_consolidate(self._h, C.c_int(_nt(nthreads)))
 
     def quantize(self, bits, P, centroid=None, qbits=8, rule=RULE_MAXCOS, nthreads=None):
         P = np.ascontiguousarray(P, dtype=np.float32)

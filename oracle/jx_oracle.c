@@ -359,6 +359,16 @@ void orc_beam_search(const uint32_t *adj, int R, const void *base, int dtype, in
     free(seen);
 }
 
+/* Sec. 4.6: a logically deleted vertex is still traversed but must not appear in
+ * any output: drop the deleted entries of a frontier, keeping the order. */
+static int drop_deleted(orc_fent *F, int nF, const uint8_t *deleted) {
+    int w = 0;
+    if (!deleted) return nF;
+    for (int i = 0; i < nF; i++)
+        if (!deleted[F[i].id]) F[w++] = F[i];
+    return w;
+}
+
 /* ------------------------------------------------------------------ */
 /* robustPrune (Alg. 3)                                                */
 /* ------------------------------------------------------------------ */
@@ -425,6 +435,8 @@ typedef struct orc_index {
     uint32_t entry;
     void *base;    /* [capacity][d] */
     uint32_t *adj; /* [capacity][R] */
+    uint8_t *deleted; /* [capacity] 1 = logically deleted (Sec. 4.6) */
+    int64_t n_deleted;
     /* RaBitQ state (Sec. 5.1) */
     int bits, qbits, rule, code_bytes;
     float *P;       /* [d][d] row-major */
@@ -449,6 +461,7 @@ orc_index *orc_index_create(int d, int dtype, int R, int L_build, float alpha, i
     x->base = malloc((size_t)capacity * d * esize(dtype) + 16);
     x->adj = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)capacity * R + 16);
     memset(x->adj, 0xFF, sizeof(uint32_t) * (size_t)capacity * R);
+    x->deleted = (uint8_t *)calloc((size_t)capacity + 1, 1);
     return x;
 }
 
@@ -456,6 +469,7 @@ void orc_index_destroy(orc_index *x) {
     if (!x) return;
     free(x->base);
     free(x->adj);
+    free(x->deleted);
     free(x->P);
     free(x->c);
     free(x->codes);
@@ -545,6 +559,7 @@ static void insert_subbatch(orc_index *x, const uint32_t *ids, int64_t B, int nt
             int nF = 0, nV = 0;
             beam_search_one(x->adj, R, nsnap, &ctx, L, x->entry, ORC_FILTER_EXACT, seen, F, &nF, V, V_cap, &nV, NULL,
                             NULL);
+            nF = drop_deleted(F, nF, x->deleted); /* new points never link to deleted vertices */
             int nc = 0;
             if (x->cand_mode == ORC_CAND_FRONTIER) {
                 for (int i = 0; i < nF; i++) {
@@ -713,6 +728,85 @@ int orc_index_insert(orc_index *x, const void *vecs, int64_t n, int nthreads) {
     }
     free(ids);
     return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Batch deletion (Sec. 4.6; the algorithm of FreshDiskANN)             */
+/* ------------------------------------------------------------------ */
+
+/* Mark: a lightweight in-place operation.  Unknown / repeated ids are ignored. */
+void orc_index_delete(orc_index *x, const uint32_t *ids, int64_t n) {
+    for (int64_t i = 0; i < n; i++)
+        if ((int64_t)ids[i] < x->n && !x->deleted[ids[i]]) {
+            x->deleted[ids[i]] = 1;
+            x->n_deleted++;
+        }
+}
+
+int64_t orc_index_deleted_count(const orc_index *x) { return x->n_deleted; }
+
+/*
+ * Consolidate: every live vertex v that points to a deleted vertex gets, in
+ * place of each deleted neighbour u, all of u's out-neighbours; the candidate
+ * set (live vertices only, v itself excluded) is pruned with robustPrune.  All
+ * new rows are computed from the graph as it stood before the call.  Then the
+ * rows of the deleted vertices are emptied (nothing points to them any more).
+ * If the entry point is deleted, the live vertex nearest to it (distance, then
+ * id) becomes the new entry point.  Ids are not reused or renumbered.
+ */
+void orc_index_consolidate(orc_index *x, int nthreads) {
+    const int R = x->R, d = x->d;
+    const size_t vs = (size_t)d * esize(x->dtype);
+    const int64_t n = x->n;
+    uint32_t *newadj = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)n * R + 16);
+    memcpy(newadj, x->adj, sizeof(uint32_t) * (size_t)n * R);
+#pragma omp parallel for schedule(dynamic, 64) num_threads(nthreads)
+    for (int64_t v = 0; v < n; v++) {
+        if (x->deleted[v]) continue;
+        const uint32_t *row = x->adj + (size_t)v * R;
+        int g = row_degree(row, R), hit = 0;
+        for (int j = 0; j < g; j++) hit |= x->deleted[row[j]];
+        if (!hit) continue;
+        uint32_t *cid = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(R + R * R));
+        double *cd = (double *)malloc(sizeof(double) * (size_t)(R + R * R));
+        int m = 0;
+        const char *pv = (const char *)x->base + (size_t)v * vs;
+        for (int j = 0; j < g; j++) {
+            uint32_t u = row[j];
+            if (!x->deleted[u]) {
+                cid[m++] = u;
+            } else {
+                const uint32_t *ru = x->adj + (size_t)u * R;
+                int gu = row_degree(ru, R);
+                for (int t = 0; t < gu; t++)
+                    if (!x->deleted[ru[t]] && ru[t] != (uint32_t)v) cid[m++] = ru[t];
+            }
+        }
+        for (int i = 0; i < m; i++) cd[i] = l2sq(x->dtype, pv, (const char *)x->base + (size_t)cid[i] * vs, d);
+        uint32_t *out = newadj + (size_t)v * R;
+        int k = orc_robust_prune((uint32_t)v, cid, cd, m, x->base, x->dtype, d, R, x->alpha, out);
+        for (int j = k; j < R; j++) out[j] = ORC_NONE;
+        free(cid);
+        free(cd);
+    }
+    for (int64_t v = 0; v < n; v++)
+        if (x->deleted[v]) memset(newadj + (size_t)v * R, 0xFF, sizeof(uint32_t) * (size_t)R);
+    memcpy(x->adj, newadj, sizeof(uint32_t) * (size_t)n * R);
+    free(newadj);
+    if (x->entry != ORC_NONE && x->deleted[x->entry]) {
+        const char *pe = (const char *)x->base + (size_t)x->entry * vs;
+        double best = INFINITY;
+        uint32_t bi = ORC_NONE;
+        for (int64_t v = 0; v < n; v++) {
+            if (x->deleted[v]) continue;
+            double dv = l2sq(x->dtype, pe, (const char *)x->base + (size_t)v * vs, d);
+            if (dv < best) {
+                best = dv;
+                bi = (uint32_t)v;
+            }
+        }
+        x->entry = bi;
+    }
 }
 
 /* ------------------------------------------------------------------ */
@@ -1107,6 +1201,7 @@ int orc_index_search(const orc_index *x, const void *queries, int64_t nq, int k,
             int nF = 0;
             int64_t h = 0, e = 0;
             beam_search_one(x->adj, R, x->n, &ctx, L, x->entry, filter, seen, F, &nF, NULL, 0, NULL, &h, &e);
+            nF = drop_deleted(F, nF, x->deleted);
             tot_h += h;
             tot_e += e;
             if (out_F_ids)

@@ -1,0 +1,67 @@
+"""Pins for the oracle's batch deletion (Sec. 4.6).  No GPU."""
+import os
+
+import numpy as np
+
+import oracle
+from paper_2601_07048_amd import datagen
+
+
+def test_delete_1d_golden(golden_dir):
+    lines = [l for l in open(os.path.join(golden_dir, "delete_1d.txt")) if l.strip() and not l.startswith("#")]
+    entry = int(lines[0].split()[1])
+    rows = {int(l.split("|")[0]): [int(t) for t in l.split("|")[1].split()] for l in lines[1:]}
+    base = np.zeros((5, 4), np.float32)
+    base[:, 0] = [0, 10, 4, 5, 20]
+    ix = oracle.Index(4, np.float32, 2, 4, 1.2, 8, batch_growth=1.0)
+    ix.insert(base)
+    ix.delete([1, 1, 77])  # repeated / unknown ids are ignored
+    assert ix.n_deleted == 1
+    # marked only: still traversed, never returned
+    r = ix.search(np.array([[9.0, 0, 0, 0]], np.float32), 2, 4)
+    assert r["ids"][0].tolist() == [3, 2]
+    ix.consolidate()
+    adj, deg = ix.graph()
+    assert ix.entry == entry
+    for i in range(5):
+        assert adj[i, :deg[i]].tolist() == rows[i], (i, adj[i])
+
+
+def test_delete_invariants_and_recall():
+    n = 6000
+    x = datagen.base(2, n)
+    q = datagen.queries(2, 300)
+    ix = oracle.Index(128, np.uint8, 32, 64, 1.2, n)
+    ix.insert(x)
+    rng = np.random.default_rng(1)
+    dele = np.unique(np.concatenate([rng.choice(n, 600, replace=False), [ix.entry]])).astype(np.uint32)
+    live = np.ones(n, bool)
+    live[dele] = False
+    lid = np.nonzero(live)[0]
+    gt = lid[oracle.bruteforce(x[live], q, 10)[0]]
+    before = oracle.recall_at_k(ix.search(q, 10, 64)["ids"], oracle.bruteforce(x, q, 10)[0])
+    ix.delete(dele)
+    r = ix.search(q, 10, 64, want_frontier=True)
+    assert not np.isin(r["ids"], dele).any() and not np.isin(r["F_ids"], dele).any()
+    marked = oracle.recall_at_k(r["ids"], gt)
+    ix.consolidate()
+    adj, deg = ix.graph()
+    assert (deg[~live] == 0).all()
+    assert not np.isin(adj[live][adj[live] != oracle.NONE], dele).any()
+    assert live[ix.entry]
+    for i in lid[::97]:
+        row = adj[i, :deg[i]]
+        assert i not in row and len(set(row.tolist())) == len(row)
+    after = oracle.recall_at_k(ix.search(q, 10, 64)["ids"], gt)
+    # Sec. 6.5: deletion + consolidation keeps recall (0.986 -> 0.988 in the paper's Table 2)
+    assert marked >= before - 0.02 and after >= before - 0.02
+    # a second consolidate changes nothing; inserts after it never link to deleted vertices
+    ix.consolidate()
+    adj2, _ = ix.graph()
+    assert np.array_equal(adj, adj2)
+    ix2 = oracle.Index(128, np.uint8, 32, 64, 1.2, n + 500)
+    ix2.insert(x)
+    ix2.delete(dele)
+    ix2.insert(datagen.base(2, 500, start=n))
+    a3, d3 = ix2.graph()
+    assert not np.isin(a3[n:][a3[n:] != oracle.NONE], dele).any()
