@@ -177,6 +177,35 @@ int jx_beam_frontier(jx_index* idx, const void* d_queries, int64_t nq, int32_t L
 int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, uint32_t* d_out_ids,
                   float* d_out_dist, void* stream);
 
+/* Batch deletion (Sec. 4.6; the two-step scheme of FreshDiskANN that the
+ * paper adopts).
+ *
+ * jx_delete marks the n vertices d_ids[n] (device) as deleted: an in-place,
+ * asynchronous flag update.  Ids >= the number of points and ids already
+ * marked are ignored.  From then on a deleted vertex is still traversed by
+ * beamSearch (its out-edges keep the graph connected) but never appears in
+ * any output: not in search results, not in the frontier returned by
+ * jx_beam_frontier, not among re-rank candidates, and not among the insertion
+ * candidates of later jx_insert calls.  jx_bruteforce ignores the marks.
+ *
+ * jx_consolidate repairs the graph, in place: every live vertex v with at
+ * least one deleted out-neighbour gets as candidate set its live neighbours
+ * plus the live out-neighbours (other than v) of each deleted neighbour, and
+ * its row becomes robustPrune (Alg. 3, the index's alpha and R) of that set;
+ * all rows are computed from the graph as it stood at the call.  The rows of
+ * deleted vertices are then emptied.  If the entry point is deleted, the
+ * live vertex nearest to it (distance, then id) takes its place.  Ids are
+ * never reused and the vector store is not compacted; deleted vertices stay
+ * marked.  Synchronises with the stream (it needs counts on the host).
+ * JX_ECAPACITY if one vertex has more than max_batch * R candidates
+ * (max_batch >= R always suffices).
+ *
+ * jx_deleted_count returns the number of vertices marked so far
+ * (synchronises with the stream). */
+int jx_delete(jx_index* idx, const uint32_t* d_ids, int64_t n, void* stream);
+int jx_consolidate(jx_index* idx, void* stream);
+int jx_deleted_count(jx_index* idx, int64_t* n_deleted, void* stream);
+
 /* Number of points and entry id (host values; no device work). */
 int jx_size(const jx_index* idx, int64_t* n, uint32_t* entry_id);
 

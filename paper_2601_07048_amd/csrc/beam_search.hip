@@ -220,22 +220,33 @@ beam_search_kernel(BeamArgs a) {
         }
     }
 
-    // ---- results: the first out_k frontier entries
+    // ---- results: the first out_k frontier entries that are not logically
+    // deleted (Sec. 4.6: deleted vertices are traversed but never returned)
+    int base_pos = 0;
 #pragma unroll
     for (int r = 0; r < NREG; r++) {
-        int p = r * 64 + lane;
-        if (p < a.out_k) {
-            uint64_t k = fk[r];
-            bool valid = (p < count);
-            uint32_t dc = key_dist(k);
+        const int p = r * 64 + lane;
+        const uint64_t k = fk[r];
+        const uint32_t id = key_id(k);
+        bool keep = p < count;
+        if (keep && a.deleted) keep = a.deleted[id] == 0;
+        const uint64_t km = ballot(keep);
+        const int pos = base_pos + prefix_count(km);
+        if (keep && pos < a.out_k) {
+            const uint32_t dc = key_dist(k);
             float d;
             if constexpr (KIND == K_U8)
                 d = (float)dc;
             else
                 d = ordered_to_f32(dc);
-            a.out_ids[qi * a.out_k + p] = valid ? key_id(k) : JX_NONE_ID;
-            a.out_dist[qi * a.out_k + p] = valid ? d : __builtin_inff();
+            a.out_ids[qi * a.out_k + pos] = id;
+            a.out_dist[qi * a.out_k + pos] = d;
         }
+        base_pos += __builtin_popcountll(km);
+    }
+    for (int p = base_pos + lane; p < a.out_k; p += 64) {
+        a.out_ids[qi * a.out_k + p] = JX_NONE_ID;
+        a.out_dist[qi * a.out_k + p] = __builtin_inff();
     }
     if (a.stats && lane == 0) {
         atomicAdd(&a.stats[0], (unsigned long long)hops);

@@ -412,10 +412,11 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
     PruneLds* L = &lds[wave];
     extern __shared__ __align__(16) unsigned char vcache[];  // INS_WPB x vec_cache_bytes
     const long long nseg = *a.nseg;
-    const long long total = a.B * a.R;
+    const long long total = a.E ? a.E : a.B * a.R;
     for (long long s = (long long)blockIdx.x * INS_WPB + wave; s < nseg; s += (long long)gridDim.x * INS_WPB) {
         const long long lo = a.heads[s];
         const uint32_t v = (uint32_t)(a.keys[lo] >> 32);
+        if (v == JX_NONE_ID) continue;  // tail of empty keys
         // segment length
         int m = 0;
         for (long long c0 = lo; c0 < total; c0 += 64) {
@@ -431,7 +432,8 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
             const bool on = rb + lane < a.R && row[rb + lane] != JX_NONE_ID;
             deg += __builtin_popcountll(ballot(on));
         }
-        if (deg + m <= a.R) {
+        if (a.force_prune) deg = 0;  // consolidation: the segment holds the whole candidate set
+        if (!a.force_prune && deg + m <= a.R) {
             for (int j = lane; j < m; j += 64) row[deg + j] = a.vals[lo + j];
             continue;
         }
@@ -694,7 +696,7 @@ static hipError_t launch_prune_pair(bool forward, const InsertArgs& a, hipStream
         }
         hipLaunchKernelGGL((forward_prune_kernel<KIND, T, CPL>), grid, dim3(INS_WPB * 64), sh, st, a);
     } else {
-        long long want = (a.B * a.R + INS_WPB - 1) / INS_WPB;
+        long long want = ((a.E ? a.E : a.B * a.R) + INS_WPB - 1) / INS_WPB;
         unsigned grid = (unsigned)(want < 4096 ? (want < 1 ? 1 : want) : 4096);
         hipLaunchKernelGGL((reverse_merge_kernel<KIND, T, CPL>), dim3(grid), dim3(INS_WPB * 64),
                            (size_t)INS_WPB * a.vec_cache_bytes, st, a);
@@ -746,6 +748,17 @@ hipError_t launch_radix_sort(uint64_t* keys_a, uint32_t* vals_a, uint64_t* keys_
         uint64_t* tk = ki; ki = ko; ko = tk;
         uint32_t* tv = vi; vi = vo; vo = tv;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_scan_u32(uint32_t* data, long long n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(radix_scan_kernel, dim3(1), dim3(1024), 0, st, data, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_argmin(const double* dist, long long n, uint32_t* out_id, hipStream_t st) {
+    hipLaunchKernelGGL(argmin_kernel, dim3(1), dim3(1024), 0, st, dist, n, out_id);
     return hipGetLastError();
 }
 

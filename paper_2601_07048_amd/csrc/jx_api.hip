@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include <new>
+#include <vector>
 #include "jx_internal.h"
 
 namespace {
@@ -30,7 +31,7 @@ int fail(int code, const char* fmt, ...) {
 inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 
 struct Layout {
-    int64_t vecs, adj, codes, P, centroid, stats, work, work_bytes, total;
+    int64_t vecs, adj, codes, P, centroid, stats, deleted, work, work_bytes, total;
     int vec_bytes, code_bytes, meta_chunk, code_stride;
 };
 
@@ -84,7 +85,7 @@ int64_t insert_work(const jx_params* p, int64_t B, InsertWork* w) {
     w->counters = take(256);
     w->partial = take((int64_t)512 * p->dim * 8);
     w->mean = take((int64_t)p->dim * 4);
-    w->dist = take(p->capacity * 8);
+    w->dist = take(p->capacity * 8);  // entry-point distances (double), or consolidation counts + offsets
     w->total = off;
     return off;
 }
@@ -131,6 +132,8 @@ void layout(const jx_params* p, Layout* L) {
     off += align256((int64_t)p->dim * 4);
     L->stats = off;
     off += 256;
+    L->deleted = off;
+    off += align256((int64_t)p->capacity + 4);
     // workspace: the larger of the insert phase and the query phase, at least 64 MiB
     const int64_t B = p->max_batch;
     InsertWork iw;
@@ -214,15 +217,18 @@ int jx_create(const jx_params* p, void* d_arena, int64_t arena_bytes, void* stre
     x->d_P = (float*)(x->d_arena + L.P);
     x->d_centroid = (float*)(x->d_arena + L.centroid);
     x->d_stats = (unsigned long long*)(x->d_arena + L.stats);
+    x->d_deleted = x->d_arena + L.deleted;
     x->d_work = x->d_arena + L.work;
     x->work_bytes = L.work_bytes;
     x->code_bytes = L.code_bytes;
     x->meta_chunk = L.meta_chunk;
     x->code_stride = L.code_stride;
     hipError_t e = jx::launch_fill_u32(x->d_adj, (long long)p->capacity * p->R, JX_NONE, as_stream(stream));
+    if (e == hipSuccess) e = jx::launch_fill_u32((uint32_t*)x->d_stats, 64, 0u, as_stream(stream));
+    if (e == hipSuccess) e = jx::launch_fill_u32((uint32_t*)x->d_deleted, (p->capacity + 3) / 4, 0u, as_stream(stream));
     if (e != hipSuccess) {
         delete x;
-        return fail(JX_EHIP, "fill adjacency: %s", hipGetErrorString(e));
+        return fail(JX_EHIP, "arena initialisation: %s", hipGetErrorString(e));
     }
     *out = x;
     return JX_OK;
@@ -248,6 +254,11 @@ int jx_import_graph(jx_index* idx, const void* d_vecs, int64_t n, const uint32_t
     JX_HIP(hipMemcpyAsync(idx->d_vecs, d_vecs, (size_t)n * idx->vec_bytes, hipMemcpyDeviceToDevice, st));
     JX_HIP(hipMemcpyAsync(idx->d_adj, d_adj, (size_t)n * idx->p.R * 4, hipMemcpyDeviceToDevice, st));
     if (n < idx->n) JX_HIP(jx::launch_fill_u32(idx->d_adj + (size_t)n * idx->p.R, (idx->n - n) * idx->p.R, JX_NONE, st));
+    if (idx->any_delete) {
+        JX_HIP(jx::launch_fill_u32((uint32_t*)idx->d_deleted, (idx->p.capacity + 3) / 4, 0u, st));
+        JX_HIP(jx::launch_fill_u32((uint32_t*)(idx->d_stats + 8), 2, 0u, st));
+        idx->any_delete = 0;
+    }
     idx->n = n;
     idx->entry = entry_id;
     idx->quantized = 0;
@@ -311,6 +322,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     if (out_k < 1 || out_k > L) return fail(JX_EINVAL, "k must be in [1, L]");
     if (rerank != 0 && (rerank < out_k || rerank > L)) return fail(JX_EINVAL, "rerank must be 0 or in [k, L]");
     if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
+    if (idx->entry == JX_NONE) return fail(JX_ESTATE, "every vertex has been deleted");
     if (mode != JX_EXACT && mode != JX_RABITQ) return fail(JX_EINVAL, "unknown mode");
     if (mode == JX_RABITQ && !idx->quantized) return fail(JX_ESTATE, "index is not quantised");
     if (nq == 0) return JX_OK;
@@ -325,6 +337,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     a.entry = idx->entry;
     a.hash_log2 = hash_log2_for(L);
     a.stats = h_stats ? idx->d_stats : nullptr;
+    a.deleted = idx->any_delete ? idx->d_deleted : nullptr;
     StageTimer tm(h_stats != nullptr, st);
     if (mode == JX_EXACT) {
         // distances are already exact: a re-rank would change nothing
@@ -498,6 +511,7 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     b.out_dist = (float*)(W + w.cand_dist);
     b.out_k = p.L_build;
     b.stats = nullptr;
+    b.deleted = idx->any_delete ? idx->d_deleted : nullptr;  // new points never link to deleted vertices
     JX_HIP(jx::launch_beam_search(exact_kind(p.dtype), 0, b, st));
     // 2. robustPrune of the frontier, new rows, reverse edges
     jx::InsertArgs a;
@@ -544,6 +558,7 @@ int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream) {
     if (!d_vecs) return fail(JX_EINVAL, "d_vecs is NULL");
     const jx_params& p = idx->p;
     const int64_t first = idx->n;
+    if (first > 0 && idx->entry == JX_NONE) return fail(JX_ESTATE, "every vertex has been deleted");
     if (first + n > p.capacity) return fail(JX_ECAPACITY, "%lld + %lld points exceed the capacity %lld", (long long)first, (long long)n, (long long)p.capacity);
     // the internal batch schedule: min(remaining, max(1, floor(batch_growth * linked)))
     {
@@ -707,6 +722,142 @@ int jx_encode_rotated(jx_index* idx, const float* d_rot, int64_t n, uint8_t* d_c
     e.meta_stride = 8;
     e.meta_pad = 0;
     JX_HIP(jx::launch_encode(e, as_stream(stream)));
+    return JX_OK;
+}
+
+static int read_deleted_count(jx_index* idx, hipStream_t st, int64_t* out) {
+    unsigned long long c = 0;
+    if (idx->any_delete) {
+        JX_HIP(hipMemcpyAsync(&c, idx->d_stats + 8, sizeof c, hipMemcpyDeviceToHost, st));
+        JX_HIP(hipStreamSynchronize(st));
+    }
+    *out = (int64_t)c;
+    return JX_OK;
+}
+
+int jx_delete(jx_index* idx, const uint32_t* d_ids, int64_t n, void* stream) {
+    if (!idx) return fail(JX_EINVAL, "index is NULL");
+    if (n < 0) return fail(JX_EINVAL, "n < 0");
+    if (n == 0) return JX_OK;
+    if (!d_ids) return fail(JX_EINVAL, "d_ids is NULL");
+    idx->any_delete = 1;
+    JX_HIP(jx::launch_mark_deleted(idx->d_deleted, d_ids, n, idx->n, idx->d_stats + 8, as_stream(stream)));
+    return JX_OK;
+}
+
+int jx_deleted_count(jx_index* idx, int64_t* n_deleted, void* stream) {
+    if (!idx || !n_deleted) return fail(JX_EINVAL, "NULL argument");
+    return read_deleted_count(idx, as_stream(stream), n_deleted);
+}
+
+int jx_consolidate(jx_index* idx, void* stream) {
+    if (!idx) return fail(JX_EINVAL, "index is NULL");
+    hipStream_t st = as_stream(stream);
+    int64_t ndel = 0;
+    int rc = read_deleted_count(idx, st, &ndel);
+    if (rc) return rc;
+    if (ndel == 0 || idx->n == 0) return JX_OK;
+    const jx_params& p = idx->p;
+    const int64_t n = idx->n;
+    InsertWork w;
+    insert_work(&p, p.max_batch, &w);
+    if (w.total > idx->work_bytes) return fail(JX_ECAPACITY, "workspace too small");
+    const int64_t Ecap = (int64_t)p.max_batch * p.R;
+    if (Ecap > 0xFFFFFFFFLL) return fail(JX_ECAPACITY, "max_batch * R exceeds 2^32");
+    uint8_t* W = idx->d_work;
+    jx::ConsolArgs c;
+    memset(&c, 0, sizeof c);
+    fill_exact_src(idx, &c.ds, idx->d_vecs);
+    c.adj = idx->d_adj;
+    c.R = p.R;
+    c.n = n;
+    c.deleted = idx->d_deleted;
+    c.cnt = (uint32_t*)(W + w.dist);
+    uint32_t* d_offs = c.cnt + p.capacity;
+    c.offs = d_offs;
+    // 1. candidates per vertex on the graph as it stands
+    JX_HIP(jx::launch_consol_count(c, st));
+    std::vector<uint32_t> cnt;
+    try {
+        cnt.resize((size_t)n);
+    } catch (...) {
+        return fail(JX_EINVAL, "out of host memory");
+    }
+    JX_HIP(hipMemcpyAsync(cnt.data(), c.cnt, (size_t)n * 4, hipMemcpyDeviceToHost, st));
+    JX_HIP(hipStreamSynchronize(st));
+    for (int64_t v = 0; v < n; v++)
+        if (cnt[(size_t)v] > Ecap)  // checked before any row changes
+            return fail(JX_ECAPACITY, "vertex %lld has %u consolidation candidates, the edge buffer holds max_batch * R = %lld",
+                        (long long)v, cnt[(size_t)v], (long long)Ecap);
+    int tbits = 1;
+    while (((int64_t)1 << tbits) <= n) tbits++;
+    jx::InsertArgs a;
+    memset(&a, 0, sizeof a);
+    a.ds = c.ds;
+    a.adj = idx->d_adj;
+    a.R = p.R;
+    a.L = p.L_build;
+    a.alpha = p.alpha;
+    a.dead = W + w.dead;
+    a.keys = (uint64_t*)(W + w.keys1);
+    a.vals = (uint32_t*)(W + w.vals1);
+    a.heads = (const uint32_t*)(W + w.heads);
+    a.nseg = (const uint32_t*)(W + w.counters);
+    a.force_prune = 1;
+    a.vec_cache_bytes = 12288;
+    // 2. slices of consecutive vertices whose candidate lists fit the edge buffers; every new row is
+    //    computed from its own old row and from rows of deleted vertices, none of which is rewritten here
+    int64_t v0 = 0;
+    while (v0 < n) {
+        int64_t v1 = v0, E = 0;
+        while (v1 < n && E + cnt[(size_t)v1] <= Ecap) E += cnt[(size_t)v1++];
+        if (E > 0) {
+            const int64_t nv = v1 - v0;
+            JX_HIP(hipMemcpyAsync(d_offs, c.cnt + v0, (size_t)nv * 4, hipMemcpyDeviceToDevice, st));
+            JX_HIP(jx::launch_scan_u32(d_offs, nv, st));
+            c.v0 = v0;
+            c.v1 = v1;
+            c.E = E;
+            c.keys = (uint64_t*)(W + w.keys0);
+            c.vals = (uint32_t*)(W + w.vals0);
+            JX_HIP(jx::launch_consol_emit(c, st));
+            // (v, candidate) order brings repeated candidates together
+            JX_HIP(jx::launch_radix_sort((uint64_t*)(W + w.keys0), (uint32_t*)(W + w.vals0), (uint64_t*)(W + w.keys1),
+                                         (uint32_t*)(W + w.vals1), E, 32 + tbits, (uint32_t*)(W + w.table), st));
+            JX_HIP(jx::launch_consol_dist(p.dtype, c, (uint64_t*)(W + w.keys1), (uint32_t*)(W + w.vals1), st));
+            // (v, distance) order; the sort is stable, so equal distances stay in id order
+            JX_HIP(jx::launch_radix_sort((uint64_t*)(W + w.keys1), (uint32_t*)(W + w.vals1), (uint64_t*)(W + w.keys0),
+                                         (uint32_t*)(W + w.vals0), E, 32 + tbits, (uint32_t*)(W + w.table), st));
+            JX_HIP(jx::launch_fill_u32((uint32_t*)(W + w.counters), 16, 0u, st));
+            JX_HIP(jx::launch_segment_heads((const uint64_t*)(W + w.keys1), E, (uint32_t*)(W + w.heads),
+                                            (uint32_t*)(W + w.counters), st));
+            a.E = E;
+            a.B = (E + p.R - 1) / p.R;
+            JX_HIP(jx::launch_reverse_merge(p.dtype, a, st));
+        }
+        v0 = v1;
+    }
+    // 3. nothing points to a deleted vertex any more: empty their rows
+    JX_HIP(jx::launch_clear_deleted_rows(idx->d_adj, p.R, n, idx->d_deleted, st));
+    // 4. a deleted entry point hands over to the nearest live vertex
+    uint8_t entry_dead = 0;
+    if (idx->entry == JX_NONE) return JX_OK;
+    JX_HIP(hipMemcpyAsync(&entry_dead, idx->d_deleted + idx->entry, 1, hipMemcpyDeviceToHost, st));
+    JX_HIP(hipStreamSynchronize(st));
+    if (entry_dead) {
+        if (ndel >= n) {
+            idx->entry = JX_NONE;
+        } else {
+            uint32_t* d_best = (uint32_t*)(W + w.counters) + 32;
+            JX_HIP(jx::launch_nearest_live(idx->d_vecs, p.dtype, n, p.dim, idx->entry, idx->d_deleted, (double*)(W + w.dist),
+                                           d_best, st));
+            uint32_t e = JX_NONE;
+            JX_HIP(hipMemcpyAsync(&e, d_best, 4, hipMemcpyDeviceToHost, st));
+            JX_HIP(hipStreamSynchronize(st));
+            if (e >= (uint64_t)n) return fail(JX_EHIP, "entry point selection returned %u", e);
+            idx->entry = e;
+        }
+    }
     return JX_OK;
 }
 

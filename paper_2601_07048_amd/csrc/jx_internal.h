@@ -35,6 +35,7 @@ struct BeamArgs {
     float* out_dist;       // [nq][out_k]
     int out_k;
     unsigned long long* stats;  // {hops, dist_evals} or NULL
+    const uint8_t* deleted;     // [N] 1 = logically deleted (never returned), or NULL
 };
 hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st);
 
@@ -54,6 +55,8 @@ struct InsertArgs {
     uint32_t* vals;             // [B*R] edge sources
     const uint32_t* heads;      // segment starts (reverse merge)
     const uint32_t* nseg;       // number of segments (device)
+    long long E;                // reverse merge: number of sorted edges (0 = B * R)
+    int force_prune;            // consolidation: ignore the existing row, always prune the candidate segment
     int vec_cache_bytes;        // reverse merge: LDS bytes per wavefront for candidate vectors (0 = never cache)
 };
 
@@ -63,6 +66,7 @@ hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st);
 hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st);
 hipError_t launch_radix_sort(uint64_t* keys_a, uint32_t* vals_a, uint64_t* keys_b, uint32_t* vals_b, long long n, int nbits,
                              uint32_t* table, hipStream_t st);
+hipError_t launch_argmin(const double* dist, long long n, uint32_t* out_id, hipStream_t st);
 hipError_t launch_segment_heads(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg, hipStream_t st);
 
 // ---- RaBitQ -----------------------------------------------------------------
@@ -109,6 +113,29 @@ hipError_t launch_query_prep(const QueryPrepArgs& a, hipStream_t st);
 hipError_t launch_rerank(int dtype, const RerankArgs& a, hipStream_t st);
 hipError_t launch_column_mean(const void* vecs, int dtype, long long n, int d, double* partial, float* mean, hipStream_t st);
 
+// ---- batch deletion ---------------------------------------------------------
+struct ConsolArgs {
+    DistSrc ds;
+    const uint32_t* adj;
+    int R;
+    long long n;
+    const uint8_t* deleted;
+    uint32_t* cnt;        // [n] candidates per vertex (0 = row untouched)
+    const uint32_t* offs; // [v1 - v0] exclusive prefix of cnt over the slice
+    long long v0, v1;     // vertex range of this slice
+    uint64_t* keys;       // slice edge buffer
+    uint32_t* vals;
+    long long E;          // elements in the slice
+};
+hipError_t launch_mark_deleted(uint8_t* deleted, const uint32_t* ids, long long n, long long nvert, unsigned long long* counter, hipStream_t st);
+hipError_t launch_consol_count(const ConsolArgs& a, hipStream_t st);
+hipError_t launch_scan_u32(uint32_t* data, long long n, hipStream_t st);
+hipError_t launch_consol_emit(const ConsolArgs& a, hipStream_t st);
+hipError_t launch_consol_dist(int dtype, const ConsolArgs& a, uint64_t* keys_out, uint32_t* vals_out, hipStream_t st);
+hipError_t launch_clear_deleted_rows(uint32_t* adj, int R, long long n, const uint8_t* deleted, hipStream_t st);
+hipError_t launch_nearest_live(const void* vecs, int dtype, long long n, int d, uint32_t target, const uint8_t* deleted,
+                               double* dist, uint32_t* out_id, hipStream_t st);
+
 // ---- brute force ------------------------------------------------------------
 struct BfArgs {
     const void* base;
@@ -146,7 +173,9 @@ struct jx_index {
     float* d_centroid;   // [dim]
     uint8_t* d_work;     // workspace shared by the phases
     int64_t work_bytes;
-    unsigned long long* d_stats;  // [8] counters
+    unsigned long long* d_stats;  // [8] search counters, [8] = vertices marked deleted so far
+    uint8_t* d_deleted;  // [capacity] 1 = logically deleted
+    int any_delete;      // a delete call has been made since the graph was created / imported
     // RaBitQ state
     int quantized;    // 0 or bits
     int qbits, rule;

@@ -24,7 +24,7 @@ MAX_L, MAX_R, MAX_BF_K = 512, 256, 128
 EXPORTS = [
     "jx_arena_bytes", "jx_create", "jx_destroy", "jx_insert", "jx_quantize", "jx_search", "jx_beam_frontier",
     "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_import_codes", "jx_rotate",
-    "jx_encode_rotated", "jx_strerror", "jx_last_error",
+    "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_deleted_count", "jx_strerror", "jx_last_error",
 ]
 
 
@@ -220,6 +220,22 @@ class Index:
             _check(_lib.jx_bruteforce(self._h, _ptr(queries), C.c_int64(nq), C.c_int32(k), _ptr(ids), _ptr(dist),
                                       _stream()))
         return ids, dist
+
+    # -- jx_delete / jx_consolidate / jx_deleted_count
+    def delete(self, ids: torch.Tensor):
+        assert ids.dtype == torch.int32 and ids.dim() == 1
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_delete(self._h, _ptr(ids), C.c_int64(ids.shape[0]), _stream()))
+
+    def consolidate(self):
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_consolidate(self._h, _stream()))
+
+    def deleted_count(self):
+        n = C.c_int64()
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_deleted_count(self._h, C.byref(n), _stream()))
+        return n.value
 
 
 def ids_to_numpy(t: torch.Tensor):
