@@ -65,3 +65,42 @@ def test_delete_invariants_and_recall():
     ix2.insert(datagen.base(2, 500, start=n))
     a3, d3 = ix2.graph()
     assert not np.isin(a3[n:][a3[n:] != oracle.NONE], dele).any()
+
+
+def test_consolidate_rows_equal_prune_of_stated_candidates():
+    """Each row after consolidation = robustPrune (pinned on its own) of the candidate set assembled here in
+    numpy from the graph before the call; rows without a deleted neighbour do not change."""
+    n, R = 1500, 12
+    x = datagen.base(2, n)
+    ix = oracle.Index(128, np.uint8, R, 32, 1.2, n)
+    ix.insert(x)
+    adj0, deg0 = ix.graph()
+    rng = np.random.default_rng(8)
+    dele = rng.choice(n, 300, replace=False).astype(np.uint32)
+    dead = np.zeros(n, bool)
+    dead[dele] = True
+    ix.delete(dele)
+    ix.consolidate()
+    adj1, deg1 = ix.graph()
+    xi = x.astype(np.int64)
+    touched = 0
+    for v in range(n):
+        row = adj0[v, :deg0[v]]
+        if dead[v]:
+            assert deg1[v] == 0
+            continue
+        if not dead[row].any():
+            assert np.array_equal(adj1[v], adj0[v])
+            continue
+        touched += 1
+        cand = []
+        for u in row:
+            if not dead[u]:
+                cand.append(int(u))
+            else:
+                cand += [int(w) for w in adj0[u, :deg0[u]] if not dead[w] and w != v]
+        cand = np.array(sorted(set(cand)), np.uint32)
+        dist = ((xi[cand] - xi[v]) ** 2).sum(axis=1).astype(np.float64)
+        want = oracle.robust_prune(v, cand, dist, x, R, 1.2)
+        assert adj1[v, :deg1[v]].tolist() == want.tolist(), v
+    assert touched > 300

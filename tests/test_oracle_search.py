@@ -41,6 +41,19 @@ def test_oracle_half_distance_is_exact():
     assert oracle.l2sq(h, np.zeros(7, np.float16)) == float((h.astype(np.float64) ** 2).sum())
 
 
+def test_oracle_half_conversion_all_bit_patterns():
+    """Every finite binary16 value, one at a time: (h - 0)^2 and (h - 1)^2 against numpy's conversion."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    h = bits.view(np.float16)
+    fin = np.isfinite(h)
+    zero, one = np.zeros(1, np.float16), np.ones(1, np.float16)
+    h64 = h.astype(np.float64)
+    for i in np.nonzero(fin)[0]:
+        assert oracle.l2sq(h[i:i + 1], zero) == h64[i] * h64[i], hex(i)
+    for i in np.nonzero(fin)[0][::7]:
+        assert oracle.l2sq(one, h[i:i + 1]) == (1.0 - h64[i]) ** 2, hex(i)
+
+
 @pytest.mark.parametrize("dtype", [np.uint8, np.float32])
 def test_bruteforce_matches_scipy(dtype):
     from scipy.spatial.distance import cdist
