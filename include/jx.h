@@ -206,6 +206,17 @@ int jx_delete(jx_index* idx, const uint32_t* d_ids, int64_t n, void* stream);
 int jx_consolidate(jx_index* idx, void* stream);
 int jx_deleted_count(jx_index* idx, int64_t* n_deleted, void* stream);
 
+/* Calibration aid for the roofline of beamSearch (Sec. 6.6 prices the kernel
+ * against memory bandwidth): reads the n_ids records d_ids[i] (all < n_rec;
+ * not checked on the device -- the caller guarantees it) of a table of
+ * rec_bytes-byte records (64, 128, 256 or 512) with independent 16-byte
+ * loads, rec_bytes/16 lanes per record, eight loads in flight per lane, from
+ * `blocks` workgroups of 256 threads, and writes one checksum word per thread
+ * to d_sink [blocks*256].  Gives the rate at which this GPU serves gathers of
+ * that record size when nothing else limits them. */
+int jx_probe_gather(const void* d_table, int64_t n_rec, int32_t rec_bytes, const uint32_t* d_ids, int64_t n_ids,
+                    int32_t blocks, uint32_t* d_sink, void* stream);
+
 /* Number of points and entry id (host values; no device work). */
 int jx_size(const jx_index* idx, int64_t* n, uint32_t* entry_id);
 

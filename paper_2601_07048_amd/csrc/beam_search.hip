@@ -25,12 +25,18 @@ namespace jx {
 #ifndef JX_BEAM_PREFETCH
 #define JX_BEAM_PREFETCH 0
 #endif
+#ifndef JX_UMAX_EXACT
+#define JX_UMAX_EXACT 8
+#endif
+#ifndef JX_WPE_EXACT
+#define JX_WPE_EXACT 6
+#endif
 
 template <int KIND, int T, int CPL, int NREG, int QB>
-__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu(((KIND <= K_F32 || KIND == K_F16) && NREG <= 2 && CPL <= 2) ? 6 : 1, 8)))
+__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu(((KIND <= K_F32 || KIND == K_F16) && NREG <= 2 && CPL <= 2) ? JX_WPE_EXACT : 1, 8)))
 beam_search_kernel(BeamArgs a) {
     constexpr int G = 64 / T;
-    constexpr int UMAX = (KIND == K_RQ1) ? 4 : 8;  // 16-byte loads in flight per lane (the 1-bit path keeps its bit planes in registers)
+    constexpr int UMAX = (KIND == K_RQ1) ? 4 : ((KIND == K_U8) ? JX_UMAX_EXACT : 8);  // 16-byte loads in flight per lane (the 1-bit path keeps its bit planes in registers)
     constexpr int U0 = (UMAX / CPL) > 0 ? (UMAX / CPL) : 1;
     constexpr int U = U0 < (64 / G) ? U0 : (64 / G);  // records in flight per lane group
     constexpr int FCAP = NREG * 64;
@@ -41,7 +47,7 @@ beam_search_kernel(BeamArgs a) {
     const int64_t qi = (int64_t)blockIdx.x * JX_BEAM_WPB + wave;
     if (qi >= a.nq) return;  // whole wavefront leaves; there is no block-level barrier below
 
-    const int H = 1 << a.hash_log2;
+    const int H = a.hash_slots;
     const size_t per_wave = (size_t)FCAP * 8 + 64 * 8 + 64 * 4 + (size_t)H * 4;
     unsigned char* my = smem + per_wave * wave;
     uint64_t* fr = reinterpret_cast<uint64_t*>(my);
@@ -69,7 +75,7 @@ beam_search_kernel(BeamArgs a) {
     // seed: the entry vertex
     if (lane == 0) {
         cand_id[0] = a.entry;
-        tab[(a.entry * 0x9E3779B1u) >> (32 - a.hash_log2)] = a.entry;
+        tab[__umulhi(a.entry * 0x9E3779B1u, (uint32_t)H)] = a.entry;
     }
     wave_sync();
     eval_batch<KIND, T, CPL, QB, 1>(q, a.ds, 0, 1, cand_id, cand_key, g, lig);
@@ -145,7 +151,7 @@ beam_search_kernel(BeamArgs a) {
             bool is_new = false;
             // ---- 3. visited filter
             if (v != JX_NONE_ID) {
-                uint32_t h = (v * 0x9E3779B1u) >> (32 - a.hash_log2);
+                uint32_t h = __umulhi(v * 0x9E3779B1u, (uint32_t)H);
                 is_new = tab[h] != v;
                 if (is_new) tab[h] = v;
             }
@@ -259,7 +265,7 @@ beam_search_kernel(BeamArgs a) {
 template <int KIND, int T, int CPL, int QB>
 static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st) {
     const int nreg = (a.L + 63) / 64;
-    const int H = 1 << a.hash_log2;
+    const int H = a.hash_slots;
     dim3 grid((unsigned)((a.nq + JX_BEAM_WPB - 1) / JX_BEAM_WPB)), block(JX_BEAM_WPB * 64);
 #define JX_LAUNCH(NR)                                                                                   \
     {                                                                                                   \

@@ -261,4 +261,41 @@ hipError_t launch_row_degrees(const uint32_t* adj, long long n, int R, uint32_t*
     return hipGetLastError();
 }
 
+// Calibration: independent gathers of whole records in a given id order, T = rec_bytes / 16 lanes per record,
+// eight 16-byte loads in flight per lane; nothing depends on a loaded value except the final checksum.
+template <int T>
+__global__ void __launch_bounds__(256) gather_probe_kernel(const uint8_t* table, const uint32_t* ids, long long n_ids,
+                                                          uint32_t* sink) {
+    constexpr int G = 64 / T;
+    const int lane = threadIdx.x & 63, g = lane / T, lig = lane % T;
+    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long nwaves = (long long)gridDim.x * 4;
+    uint32_t acc = 0;
+    for (long long base = wave * (8 * G); base < n_ids; base += nwaves * (8 * G)) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            long long i = base + u * G + g;
+            if (i >= n_ids) i = n_ids - 1;
+            v[u] = *reinterpret_cast<const uint4*>(table + (size_t)ids[i] * (size_t)(T * 16) + (size_t)lig * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc;
+}
+
+hipError_t launch_gather_probe(const uint8_t* table, int rec_bytes, const uint32_t* ids, long long n_ids, int blocks,
+                               uint32_t* sink, hipStream_t st) {
+    dim3 grid((unsigned)blocks), block(256);
+    switch (rec_bytes) {
+        case 64: hipLaunchKernelGGL(gather_probe_kernel<4>, grid, block, 0, st, table, ids, n_ids, sink); break;
+        case 128: hipLaunchKernelGGL(gather_probe_kernel<8>, grid, block, 0, st, table, ids, n_ids, sink); break;
+        case 256: hipLaunchKernelGGL(gather_probe_kernel<16>, grid, block, 0, st, table, ids, n_ids, sink); break;
+        case 512: hipLaunchKernelGGL(gather_probe_kernel<32>, grid, block, 0, st, table, ids, n_ids, sink); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 }  // namespace jx

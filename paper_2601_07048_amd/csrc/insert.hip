@@ -372,6 +372,7 @@ __global__ void __launch_bounds__(INS_WPB * 64) forward_prune_kernel(InsertArgs 
         nB += __builtin_popcountll(ballot(valid));
     }
     B.n = nB;
+    if (a.gram && nB <= 128) return;  // served by the Gram-matrix kernel
     __threadfence_block();
     wave_sync();
     int nsel;
@@ -414,7 +415,9 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
     const long long nseg = *a.nseg;
     const long long total = a.E ? a.E : a.B * a.R;
     for (long long s = (long long)blockIdx.x * INS_WPB + wave; s < nseg; s += (long long)gridDim.x * INS_WPB) {
-        const long long lo = a.heads[s];
+        const uint32_t head = a.heads[s];
+        if (head & 0x80000000u) continue;  // merged by the Gram-matrix kernel, which marks what it has done
+        const long long lo = head;
         const uint32_t v = (uint32_t)(a.keys[lo] >> 32);
         if (v == JX_NONE_ID) continue;  // tail of empty keys
         // segment length
@@ -719,12 +722,20 @@ static hipError_t launch_prune_shape(bool forward, const InsertArgs& a, hipStrea
 }
 
 hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st) {
+    if (a.gram) {
+        hipError_t e = launch_forward_prune_gram(dtype, a, st);
+        if (e != hipSuccess || a.L <= 128) return e;  // wider frontiers: the list-based kernel takes the rest
+    }
     if (dtype == JX_U8) return launch_prune_shape<K_U8>(true, a, st);
     if (dtype == JX_F16) return launch_prune_shape<K_F16>(true, a, st);
     return launch_prune_shape<K_F32>(true, a, st);
 }
 
 hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st) {
+    if (a.gram) {
+        hipError_t e = launch_reverse_merge_gram(dtype, a, st);
+        if (e != hipSuccess) return e;
+    }
     if (dtype == JX_U8) return launch_prune_shape<K_U8>(false, a, st);
     if (dtype == JX_F16) return launch_prune_shape<K_F16>(false, a, st);
     return launch_prune_shape<K_F32>(false, a, st);

@@ -56,6 +56,7 @@ int check_params(const jx_params* p) {
     if (p->cand_mode != JX_CAND_FRONTIER) return fail(JX_EINVAL, "only JX_CAND_FRONTIER is supported");
     if (p->capacity < 1 || p->capacity > 0x7FFFFFFELL) return fail(JX_EINVAL, "capacity out of range");
     if (p->max_batch < 1) return fail(JX_EINVAL, "max_batch must be positive");
+    if ((int64_t)p->max_batch * p->R >= 0x7FFFFFFFLL) return fail(JX_EINVAL, "max_batch * R must stay below 2^31");
     if (p->quant_bits != 0 && p->quant_bits != 1 && p->quant_bits != 4)
         return fail(JX_EINVAL, "quant_bits must be 0, 1 or 4");
     if (p->quant_bits && p->dtype == JX_U8) return fail(JX_EINVAL, "RaBitQ needs float data (float32 or binary16)");
@@ -158,13 +159,31 @@ int64_t batch_cap(const jx_params& p, int64_t linked) {
     return c < 1 ? 1 : c;
 }
 
+// Gram-matrix robustPrune for float data (JX_GRAM=0 switches it off for comparisons)
+int gram_mode(int dtype) {
+    static int on = -1;
+    if (on < 0) {
+        const char* e = getenv("JX_GRAM");
+        on = (e && atoi(e) == 0) ? 0 : 1;
+    }
+    if (!on || dtype == JX_U8) return 0;
+    return dtype == JX_F16 ? 2 : 1;
+}
+
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
-int hash_log2_for(int L) {
+int hash_slots_for(int L) {
     // 1,024 slots at least: measured optimum of fewer repeated distance
     // evaluations against LDS footprint for L <= 256
-    int h = 10;
-    while ((1 << h) < 4 * L && h < 12) h++;
+    static int forced = -1;
+    if (forced < 0) {
+        const char* e = getenv("JX_HASH_SLOTS");  // experiments only
+        forced = e ? atoi(e) : 0;
+        if (forced < 64 || forced > 8192) forced = 0;
+    }
+    if (forced) return forced;
+    int h = 1024;
+    while (h < 4 * L && h < 4096) h *= 2;
     return h;
 }
 
@@ -335,7 +354,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     a.q_skip = 0x7FFFFFFFFFFFFFFFLL;
     a.L = L;
     a.entry = idx->entry;
-    a.hash_log2 = hash_log2_for(L);
+    a.hash_slots = hash_slots_for(L);
     a.stats = h_stats ? idx->d_stats : nullptr;
     a.deleted = idx->any_delete ? idx->d_deleted : nullptr;
     StageTimer tm(h_stats != nullptr, st);
@@ -506,7 +525,7 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     b.q_skip = id_skip >= id_base ? id_skip - id_base : 0;
     b.L = p.L_build;
     b.entry = idx->entry;
-    b.hash_log2 = hash_log2_for(p.L_build);
+    b.hash_slots = hash_slots_for(p.L_build);
     b.out_ids = (uint32_t*)(W + w.cand_ids);
     b.out_dist = (float*)(W + w.cand_dist);
     b.out_k = p.L_build;
@@ -534,6 +553,7 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     // forward prune: no LDS vector cache.  A whole frontier (128 x 128 bytes per wavefront) would leave room for
     // one workgroup per CU only, and the Gram-matrix form then measured slower (47 ms against 32 ms per 1M inserts)
     a.vec_cache_bytes = 0;
+    a.gram = gram_mode(p.dtype);
     JX_HIP(jx::launch_forward_prune(p.dtype, a, st));
     // 3. one global sort by (target, distance, source)
     int tbits = 1;
@@ -804,6 +824,7 @@ int jx_consolidate(jx_index* idx, void* stream) {
     a.heads = (const uint32_t*)(W + w.heads);
     a.nseg = (const uint32_t*)(W + w.counters);
     a.force_prune = 1;
+    a.gram = gram_mode(p.dtype);
     a.vec_cache_bytes = 12288;
     // 2. slices of consecutive vertices whose candidate lists fit the edge buffers; every new row is
     //    computed from its own old row and from rows of deleted vertices, none of which is rewritten here
@@ -858,6 +879,16 @@ int jx_consolidate(jx_index* idx, void* stream) {
             idx->entry = e;
         }
     }
+    return JX_OK;
+}
+
+int jx_probe_gather(const void* d_table, int64_t n_rec, int32_t rec_bytes, const uint32_t* d_ids, int64_t n_ids,
+                    int32_t blocks, uint32_t* d_sink, void* stream) {
+    if (!d_table || !d_ids || !d_sink) return fail(JX_EINVAL, "NULL argument");
+    if (rec_bytes != 64 && rec_bytes != 128 && rec_bytes != 256 && rec_bytes != 512)
+        return fail(JX_EINVAL, "rec_bytes must be 64, 128, 256 or 512");
+    if (n_rec < 1 || n_ids < 1 || blocks < 1 || blocks > 65536) return fail(JX_EINVAL, "sizes out of range");
+    JX_HIP(jx::launch_gather_probe((const uint8_t*)d_table, rec_bytes, d_ids, n_ids, blocks, d_sink, as_stream(stream)));
     return JX_OK;
 }
 

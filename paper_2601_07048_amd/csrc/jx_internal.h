@@ -30,7 +30,7 @@ struct BeamArgs {
     long long q_skip;      // query i reads record i + (i >= q_skip); used by insertion to skip the entry point
     int L;
     uint32_t entry;
-    int hash_log2;         // log2 of the visited-table size
+    int hash_slots;        // visited-table size (any value >= 64; slot = high word of hash * size)
     uint32_t* out_ids;     // [nq][out_k]
     float* out_dist;       // [nq][out_k]
     int out_k;
@@ -53,10 +53,11 @@ struct InsertArgs {
     uint8_t* dead;              // max(B*L, B*R) bytes
     uint64_t* keys;             // [B*R] edge keys
     uint32_t* vals;             // [B*R] edge sources
-    const uint32_t* heads;      // segment starts (reverse merge)
+    const uint32_t* heads;      // segment starts (reverse merge); bit 31 is set by a kernel that has merged the segment
     const uint32_t* nseg;       // number of segments (device)
     long long E;                // reverse merge: number of sorted edges (0 = B * R)
     int force_prune;            // consolidation: ignore the existing row, always prune the candidate segment
+    int gram;                   // float data: 1 (float32) / 2 (binary16) = prunes of at most 128 candidates go to the Gram-matrix kernels
     int vec_cache_bytes;        // reverse merge: LDS bytes per wavefront for candidate vectors (0 = never cache)
 };
 
@@ -64,6 +65,8 @@ hipError_t launch_entry_point(const void* vecs, int dtype, long long n, int d, d
                               uint32_t* out_id, hipStream_t st);
 hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st);
 hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st);
+hipError_t launch_forward_prune_gram(int dtype, const InsertArgs& a, hipStream_t st);
+hipError_t launch_reverse_merge_gram(int dtype, const InsertArgs& a, hipStream_t st);
 hipError_t launch_radix_sort(uint64_t* keys_a, uint32_t* vals_a, uint64_t* keys_b, uint32_t* vals_b, long long n, int nbits,
                              uint32_t* table, hipStream_t st);
 hipError_t launch_argmin(const double* dist, long long n, uint32_t* out_id, hipStream_t st);
@@ -153,6 +156,8 @@ hipError_t launch_bruteforce(const BfArgs& a, hipStream_t st);
 
 // ---- small utilities ----------------------------------------------------------
 hipError_t launch_fill_u32(uint32_t* p, long long n, uint32_t v, hipStream_t st);
+hipError_t launch_gather_probe(const uint8_t* table, int rec_bytes, const uint32_t* ids, long long n_ids, int blocks,
+                               uint32_t* sink, hipStream_t st);
 hipError_t launch_row_degrees(const uint32_t* adj, long long n, int R, uint32_t* deg, hipStream_t st);
 
 }  // namespace jx

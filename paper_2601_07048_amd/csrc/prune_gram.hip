@@ -1,0 +1,372 @@
+// robustPrune (Alg. 3) for float32 / binary16 vectors as a dense contraction.
+//
+// Whether candidate i discards candidate j (alpha * d(i,j) <= d(p,j)) does not
+// depend on the order in which Alg. 3 selects, so all pair distances of one
+// prune are computed at once from the Gram matrix of its candidate vectors,
+//     d(i,j) = G_ii + G_jj - 2 G_ij,   G = X X^T,
+// on the matrix cores, and every candidate vector is read exactly once (the
+// selection-centric form reads the surviving candidates again for every
+// selected neighbour: 20-30 times the bytes for 2-6 KB vectors).
+//
+// One wavefront per prune, up to 128 candidates = 4 blocks of 32 rows.  Operand
+// fragments go straight from global memory into the MFMA operand registers: a
+// lane (row r = lane % 32, half h = lane / 32) loads the 64 contiguous bytes
+// h*64 .. h*64+63 of each 128-byte piece of its row, and the k-th 16-byte
+// load is the operand of the k-th MFMA step for the A side (row block bi) and
+// the B side (row block bj) alike; since both sides use the same assignment of
+// vector coordinates to MFMA k-slots, any such assignment sums every
+// coordinate exactly once.
+//   float32 : v_mfma_f32_32x32x2f32 on rows centred at the pruned vertex p
+//             (x_j - x_p: distances are translation invariant and the
+//             cancellation in G_ii + G_jj - 2 G_ij then involves local
+//             magnitudes only); G_jj is d(p,j) itself.
+//   binary16: v_mfma_f32_32x32x16_f16 on the stored values (products exact,
+//             float32 accumulation, as in the binary16 distance provider);
+//             where d(p,.) is not known beforehand p joins as one more row.
+// The upper triangle of tiles is enough for candidates in any order: element
+// (i,j), i in an earlier block than j, yields both "i discards j" and "j
+// discards i" (two ballots per accumulator register = two 32-column stripes of
+// bit masks).  Alg. 3 itself is then a walk over the candidates in (distance,
+// id) order on 128-bit masks.
+#include "jx_distance.h"
+
+namespace jx {
+
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+
+#define GP_WPB 4
+#define GP_MAX 128
+
+struct GramLds {
+    uint64_t key[GP_MAX];
+    uint32_t id[GP_MAX];
+    float dp[GP_MAX];   // d(p, j)
+    float nrm[GP_MAX];  // G_jj
+    float gv[GP_MAX];   // G_jp (binary16, p as extra row)
+    uint32_t kill[GP_MAX * 4];  // row i: mask over j of "i discards j", words of column blocks >= block(i)
+    uint32_t kb[GP_MAX * 4];    // row i: mask over j of "j discards i", words of column blocks > block(i)
+    uint32_t sel_id[GP_MAX];
+    uint32_t sel_dist[GP_MAX];
+    uint8_t order[GP_MAX];      // rank in (distance, id) order -> candidate slot
+};
+
+__host__ __device__ constexpr int gp_tile(int nt, int bi, int bj) { return bi * nt - bi * (bi - 1) / 2 + (bj - bi); }
+
+// Preconditions: L->id[0..M) holds the candidates; with have_dp also L->dp[0..M), the candidates being in
+// (distance, id) order.  M + (binary16 && !have_dp ? 1 : 0) <= 32 * NT.  Returns the number selected
+// (L->sel_id / L->sel_dist, distance bits as float32).
+template <int DT, int NT>
+__device__ __forceinline__ int gram_prune_wave(const uint8_t* recs, size_t stride, int vec_bytes, GramLds* L, int M, uint32_t p,
+                                               bool have_dp, int R, float alpha) {
+    constexpr int NTILE = NT * (NT + 1) / 2;
+    const int lane = lane_id(), col = lane & 31, half = lane >> 5;
+    const bool extra = (DT == JX_F16) && !have_dp;
+    const int Mx = M + (extra ? 1 : 0);
+    const uint8_t* rp[NT];
+    bool rv[NT];
+    const uint8_t* pp = recs + (size_t)p * stride;
+#pragma unroll
+    for (int b = 0; b < NT; b++) {
+        const int i = b * 32 + col;
+        rv[b] = i < Mx;
+        const uint32_t id = i < M ? L->id[i] : p;
+        rp[b] = recs + (size_t)id * stride;
+    }
+    f32x16_t acc[NTILE];
+#pragma unroll
+    for (int t = 0; t < NTILE; t++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) acc[t][e] = 0.f;
+
+    for (int p0 = 0; p0 < vec_bytes; p0 += 128) {
+        const int off = p0 + half * 64;
+        if constexpr (DT == JX_F32) {
+            float f[NT][16];
+            float c[16];
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                const int o = off + s * 16;
+                uint4 x = make_uint4(0, 0, 0, 0);
+                if (o < vec_bytes) x = load16(pp + o);
+                c[4 * s + 0] = __uint_as_float(x.x);
+                c[4 * s + 1] = __uint_as_float(x.y);
+                c[4 * s + 2] = __uint_as_float(x.z);
+                c[4 * s + 3] = __uint_as_float(x.w);
+            }
+#pragma unroll
+            for (int b = 0; b < NT; b++)
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    const int o = off + s * 16;
+                    uint4 x = make_uint4(0, 0, 0, 0);
+                    if (o < vec_bytes) x = load16(rp[b] + o);  // rows beyond the last candidate point at p: they centre to zero
+                    f[b][4 * s + 0] = __uint_as_float(x.x) - c[4 * s + 0];
+                    f[b][4 * s + 1] = __uint_as_float(x.y) - c[4 * s + 1];
+                    f[b][4 * s + 2] = __uint_as_float(x.z) - c[4 * s + 2];
+                    f[b][4 * s + 3] = __uint_as_float(x.w) - c[4 * s + 3];
+                }
+#pragma unroll
+            for (int e = 0; e < 16; e++)
+#pragma unroll
+                for (int bi = 0; bi < NT; bi++)
+#pragma unroll
+                    for (int bj = bi; bj < NT; bj++)
+                        acc[gp_tile(NT, bi, bj)] =
+                            __builtin_amdgcn_mfma_f32_32x32x2f32(f[bi][e], f[bj][e], acc[gp_tile(NT, bi, bj)], 0, 0, 0);
+        } else {
+            uint4 f[NT][4];
+#pragma unroll
+            for (int b = 0; b < NT; b++)
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    const int o = off + s * 16;
+                    f[b][s] = make_uint4(0, 0, 0, 0);
+                    if (rv[b] && o < vec_bytes) f[b][s] = load16(rp[b] + o);
+                }
+#pragma unroll
+            for (int s = 0; s < 4; s++)
+#pragma unroll
+                for (int bi = 0; bi < NT; bi++)
+#pragma unroll
+                    for (int bj = bi; bj < NT; bj++)
+                        acc[gp_tile(NT, bi, bj)] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            __builtin_bit_cast(f16x8_t, f[bi][s]), __builtin_bit_cast(f16x8_t, f[bj][s]),
+                            acc[gp_tile(NT, bi, bj)], 0, 0, 0);
+        }
+    }
+
+    // Accumulator layout of the 32x32 tiles: register e of lane (col, half) holds row 8*(e/4) + 4*half + e%4, column col.
+    // ---- G_jj from the diagonal tiles
+    {
+        const int hcol = (col >> 2) & 1, ecol = ((col >> 3) << 2) | (col & 3);
+#pragma unroll
+        for (int b = 0; b < NT; b++) {
+            float dv = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; e++)
+                if (e == ecol) dv = acc[gp_tile(NT, b, b)][e];
+            if (half == hcol) L->nrm[b * 32 + col] = dv;
+        }
+    }
+    // ---- binary16 without known distances: column of the extra row p (slot M)
+    if (extra) {
+        const int bv = M >> 5, cv = M & 31;
+#pragma unroll
+        for (int bi = 0; bi < NT; bi++)
+#pragma unroll
+            for (int bj = bi; bj < NT; bj++)
+                if (bj == bv && col == cv) {
+#pragma unroll
+                    for (int e = 0; e < 16; e++) L->gv[bi * 32 + 8 * (e >> 2) + 4 * half + (e & 3)] = acc[gp_tile(NT, bi, bj)][e];
+                }
+    }
+    wave_sync();
+    if (!have_dp) {
+        for (int j = lane; j < M; j += 64) {
+            float d;
+            if constexpr (DT == JX_F32)
+                d = L->nrm[j];
+            else
+                d = fmaxf(L->nrm[M] + L->nrm[j] - 2.f * L->gv[j], 0.f);
+            L->dp[j] = d;
+            L->key[j] = ((uint64_t)__float_as_uint(d) << 32) | L->id[j];
+        }
+        wave_sync();
+        for (int j = lane; j < M; j += 64) {
+            const uint64_t k = L->key[j];
+            int rank = 0;
+            for (int t = 0; t < M; t++) {
+                const uint64_t o = L->key[t];
+                rank += (o < k || (o == k && t < j)) ? 1 : 0;
+            }
+            L->order[rank] = (uint8_t)j;
+        }
+    } else {
+        for (int j = lane; j < M; j += 64) L->order[j] = (uint8_t)j;
+    }
+    wave_sync();
+    // ---- the discard relation, tile by tile
+#pragma unroll
+    for (int bi = 0; bi < NT; bi++)
+#pragma unroll
+        for (int bj = bi; bj < NT; bj++) {
+            const int j = bj * 32 + col;
+            const float nj = L->nrm[j];
+            const float dpj = L->dp[j < M ? j : 0];
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const int r0 = bi * 32 + 8 * (e >> 2) + (e & 3);
+                const int i = r0 + 4 * half;
+                const float ni = L->nrm[i];
+                const float dpi = L->dp[i < M ? i : 0];
+                const float dij = fmaxf((ni + nj) - 2.f * acc[gp_tile(NT, bi, bj)][e], 0.f);
+                const float ad = __fmul_rn(alpha, dij);
+                const bool ok = i < M && j < M && i != j;
+                const uint64_t m1 = ballot(ok && ad <= dpj);
+                if (lane == 0) {
+                    L->kill[r0 * 4 + bj] = (uint32_t)m1;
+                    L->kill[(r0 + 4) * 4 + bj] = (uint32_t)(m1 >> 32);
+                }
+                if (bi != bj) {
+                    const uint64_t m2 = ballot(ok && ad <= dpi);
+                    if (lane == 0) {
+                        L->kb[r0 * 4 + bj] = (uint32_t)m2;
+                        L->kb[(r0 + 4) * 4 + bj] = (uint32_t)(m2 >> 32);
+                    }
+                }
+            }
+        }
+    wave_sync();
+    // ---- Alg. 3: candidates in (distance, id) order; a candidate is gone if a selected one discards it
+    uint32_t A[4], S[4];
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+        const int rem = M - 32 * t;
+        A[t] = rem >= 32 ? 0xFFFFFFFFu : (rem <= 0 ? 0u : ((1u << rem) - 1u));
+        S[t] = 0u;
+    }
+    int nsel = 0;
+    for (int r = 0; r < M && nsel < R; r++) {
+        const int c = L->order[r];
+        const int w = c >> 5;
+        const uint32_t bit = 1u << (c & 31);
+        uint32_t aw = 0u;
+#pragma unroll
+        for (int t = 0; t < 4; t++)
+            if (t == w) aw = A[t];
+        if (!(aw & bit)) continue;
+        const uint32_t cid = L->id[c];
+        if (cid == p) continue;
+        bool gone = false;
+#pragma unroll
+        for (int t = 1; t < NT; t++)
+            if (t > w) gone = gone || (L->kb[c * 4 + t] & S[t]) != 0u;
+        if (gone) continue;
+        if (lane == 0) {
+            L->sel_id[nsel] = cid;
+            L->sel_dist[nsel] = __float_as_uint(L->dp[c]);
+        }
+        nsel++;
+#pragma unroll
+        for (int t = 0; t < NT; t++) {
+            if (t == w) S[t] |= bit;
+            if (t >= w) A[t] &= ~L->kill[c * 4 + t];
+        }
+    }
+    wave_sync();
+    return nsel;
+}
+
+// ---- forward prune of the final frontier of each new point (Alg. 4 step 2)
+template <int DT, int NT>
+__global__ void __launch_bounds__(GP_WPB * 64) forward_prune_gram_kernel(InsertArgs a) {
+    __shared__ GramLds lds[GP_WPB];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const long long i = (long long)blockIdx.x * GP_WPB + wave;
+    if (i >= a.B) return;
+    GramLds* L = &lds[wave];
+    long long xid = a.id_base + i;
+    if (xid >= a.id_skip) xid++;
+    const uint32_t* ids = a.cand_ids + (size_t)i * a.L;
+    const uint32_t* dbits = a.cand_dist + (size_t)i * a.L;
+    int nB = 0;
+    for (int c0 = 0; c0 < a.L; c0 += 64) {
+        const int j = c0 + lane;
+        const bool valid = j < a.L && ids[j] != JX_NONE_ID;  // the frontier is filled from the left
+        nB += __builtin_popcountll(ballot(valid));
+    }
+    if (nB > GP_MAX) return;  // left to the list-based kernel
+    const int nt = nB <= 64 ? 2 : (nB + 31) >> 5;
+    if (nt != NT) return;  // another instantiation's share
+    for (int j = lane; j < nB; j += 64) {
+        L->id[j] = ids[j];
+        L->dp[j] = __uint_as_float(dbits[j]);
+    }
+    wave_sync();
+    const int nsel = gram_prune_wave<DT, NT>(a.ds.recs, (size_t)a.ds.rec_stride, a.ds.nch * 16, L, nB, (uint32_t)xid, true, a.R, a.alpha);
+    uint32_t* row = a.adj + (size_t)xid * a.R;
+    for (int j = lane; j < a.R; j += 64) {
+        const bool on = j < nsel;
+        const uint32_t v = on ? L->sel_id[j] : JX_NONE_ID;
+        row[j] = v;
+        a.keys[(size_t)i * a.R + j] = on ? (((uint64_t)v << 32) | L->sel_dist[j]) : JX_EMPTY_KEY;
+        a.vals[(size_t)i * a.R + j] = on ? (uint32_t)xid : JX_NONE_ID;
+    }
+}
+
+// ---- reverse-edge merge (Alg. 4 step 3): the targets whose row overflows and whose candidates fit 128 slots
+template <int DT, int NT>
+__global__ void __launch_bounds__(GP_WPB * 64) reverse_merge_gram_kernel(InsertArgs a) {
+    __shared__ GramLds lds[GP_WPB];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    GramLds* L = &lds[wave];
+    const long long nseg = *a.nseg;
+    const long long total = a.E ? a.E : a.B * a.R;
+    for (long long s = (long long)blockIdx.x * GP_WPB + wave; s < nseg; s += (long long)gridDim.x * GP_WPB) {
+        const uint32_t head = a.heads[s];
+        if (head & 0x80000000u) continue;  // already merged by another instantiation
+        const long long lo = head;
+        const uint32_t v = (uint32_t)(a.keys[lo] >> 32);
+        if (v == JX_NONE_ID) continue;
+        int m = 0;
+        for (long long c0 = lo; c0 < total; c0 += 64) {
+            const long long j = c0 + lane;
+            const bool same = j < total && (uint32_t)(a.keys[j] >> 32) == v;
+            const uint64_t sm = ballot(same);
+            m += __builtin_popcountll(sm);
+            if (sm != ~0ull) break;
+        }
+        uint32_t* row = a.adj + (size_t)v * a.R;
+        int deg = 0;
+        for (int rb = 0; rb < a.R; rb += 64) {
+            const bool on = rb + lane < a.R && row[rb + lane] != JX_NONE_ID;
+            deg += __builtin_popcountll(ballot(on));
+        }
+        if (a.force_prune) deg = 0;
+        if (!a.force_prune && deg + m <= a.R) continue;  // appended by the list-based kernel
+        const int M = deg + m;
+        const int Mx = M + (DT == JX_F16 ? 1 : 0);
+        if (Mx > GP_MAX) continue;  // left to the list-based kernel
+        const int nt = Mx <= 64 ? 2 : (Mx + 31) >> 5;
+        if (nt != NT) continue;
+        for (int j = lane; j < deg; j += 64) L->id[j] = row[j];
+        for (int j = lane; j < m; j += 64) L->id[deg + j] = a.vals[lo + j];
+        wave_sync();
+        const int nsel = gram_prune_wave<DT, NT>(a.ds.recs, (size_t)a.ds.rec_stride, a.ds.nch * 16, L, M, v, false, a.R, a.alpha);
+        for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? L->sel_id[j] : JX_NONE_ID;
+        // the row has changed, so degree and overflow can no longer be derived from it: mark the segment as done
+        if (lane == 0) const_cast<uint32_t*>(a.heads)[s] = head | 0x80000000u;
+        wave_sync();
+    }
+}
+
+template <int DT>
+static hipError_t launch_forward_gram_dt(const InsertArgs& a, hipStream_t st) {
+    dim3 grid((unsigned)((a.B + GP_WPB - 1) / GP_WPB)), block(GP_WPB * 64);
+    hipLaunchKernelGGL((forward_prune_gram_kernel<DT, 2>), grid, block, 0, st, a);
+    if (a.L > 64) hipLaunchKernelGGL((forward_prune_gram_kernel<DT, 3>), grid, block, 0, st, a);
+    if (a.L > 96) hipLaunchKernelGGL((forward_prune_gram_kernel<DT, 4>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+template <int DT>
+static hipError_t launch_reverse_gram_dt(const InsertArgs& a, hipStream_t st) {
+    long long want = ((a.E ? a.E : a.B * a.R) + GP_WPB - 1) / GP_WPB;
+    dim3 grid((unsigned)(want < 2048 ? (want < 1 ? 1 : want) : 2048)), block(GP_WPB * 64);
+    hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 2>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 3>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 4>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_forward_prune_gram(int dtype, const InsertArgs& a, hipStream_t st) {
+    if (a.B <= 0) return hipSuccess;
+    return dtype == JX_F16 ? launch_forward_gram_dt<JX_F16>(a, st) : launch_forward_gram_dt<JX_F32>(a, st);
+}
+
+hipError_t launch_reverse_merge_gram(int dtype, const InsertArgs& a, hipStream_t st) {
+    return dtype == JX_F16 ? launch_reverse_gram_dt<JX_F16>(a, st) : launch_reverse_gram_dt<JX_F32>(a, st);
+}
+
+}  // namespace jx

@@ -24,7 +24,7 @@ MAX_L, MAX_R, MAX_BF_K = 512, 256, 128
 EXPORTS = [
     "jx_arena_bytes", "jx_create", "jx_destroy", "jx_insert", "jx_quantize", "jx_search", "jx_beam_frontier",
     "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_import_codes", "jx_rotate",
-    "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_deleted_count", "jx_strerror", "jx_last_error",
+    "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_deleted_count", "jx_probe_gather", "jx_strerror", "jx_last_error",
 ]
 
 
@@ -236,6 +236,18 @@ class Index:
         with torch.cuda.device(self.device):
             _check(_lib.jx_deleted_count(self._h, C.byref(n), _stream()))
         return n.value
+
+
+def probe_gather(table: torch.Tensor, rec_bytes: int, ids: torch.Tensor, blocks: int = 4096):
+    """jx_probe_gather: independent gathers of rec_bytes-byte records; returns the checksum words."""
+    assert table.dtype == torch.uint8 and ids.dtype == torch.int32
+    n_rec = table.numel() // rec_bytes
+    assert 0 <= int(ids.min()) and int(ids.max()) < n_rec  # the device does not check
+    sink = torch.empty(blocks * 256, dtype=torch.int32, device=table.device)
+    with torch.cuda.device(table.device):
+        _check(_lib.jx_probe_gather(_ptr(table), C.c_int64(n_rec), C.c_int32(rec_bytes), _ptr(ids), C.c_int64(ids.numel()),
+                                    C.c_int32(blocks), _ptr(sink), _stream()))
+    return sink
 
 
 def ids_to_numpy(t: torch.Tensor):
