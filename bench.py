@@ -203,6 +203,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # What this GPU delivers for dependency-free gathers of records of the kernel's size class from a table of the
+    # index's footprint: the practical ceiling for the gather part of beamSearch (context for the 8 TB/s peak).
+    rec_bytes = d if not rabitq else ((d * sp["bits"] // 8 + 15) // 16 + 1) * 16
+    rec_class = min((64, 128, 256, 512), key=lambda c: abs(c - rec_bytes))
+    tab = torch.randint(0, 255, (n * rec_class,), dtype=torch.uint8, device="cuda")
+    gid = torch.randint(0, n, ((2 << 30) // rec_class,), dtype=torch.int32, device="cuda")
+    jx.probe_gather(tab, rec_class, gid)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(5):
+        jx.probe_gather(tab, rec_class, gid)
+    ev[1].record()
+    torch.cuda.synchronize()
+    gather_gbs = gid.numel() * rec_class / (ev[0].elapsed_time(ev[1]) / 5 * 1e-3) / 1e9
+    del tab, gid
+
     # algorithmic bytes of one beamSearch launch: adjacency rows + gathered records + query records in + results out
     qrec = d if not rabitq else (16 + (2 if sp["bits"] == 4 else args.query_bits) * ((d * sp["bits"] // 8 + 15) // 16) * 16)
     out_k = rerank if rerank else k
@@ -212,7 +228,9 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((wl, n, nq, L_star)),
                 "bytes_per_launch": int(alg_bytes), "kernel_ms": round(beam_ms, 4),
                 "hops_per_query": round(st["hops"] / nq, 1), "dist_evals_per_query": round(st["dist_evals"] / nq, 1),
-                "stage_ms": {k2: round(v, 4) for k2, v in stage.items()}}
+                "stage_ms": {k2: round(v, 4) for k2, v in stage.items()},
+                "gather_ceiling": {"GB/s": round(gather_gbs, 1), "rec_bytes": rec_class, "table_bytes": n * rec_class,
+                                   "what": "jx_probe_gather: independent random gathers, measured in this run"}}
 
     cpu = None
     if args.cpu_queries > 0:

@@ -99,6 +99,36 @@ def test_insert_f32_dyadic_grid_bit_exact(jx):
     assert np.array_equal(adj, oadj)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("n,d,R,L,calls,growth", [
+    (2500, 32, 8, 16, None, 0.25),          # prunes of 9..: one and two 32-row blocks of the Gram-matrix kernels
+    (3000, 64, 40, 64, None, 0.25),         # 41.. candidates: two and three blocks
+    (3000, 64, 64, 128, None, 0.5),         # frontier of 128 = four blocks; merges of 65..128 and beyond
+    (2500, 40, 100, 128, None, 0.25),       # merges of 101..128 (four blocks) and > 128 (list-based kernel); ragged 160/80-byte vectors
+    (2500, 64, 126, 128, None, 0.25),       # binary16: 127 candidates + the pruned vertex fill the 128 rows exactly
+    (2500, 64, 127, 128, None, 0.25),       # binary16: one too many for the extra row -> list-based kernel
+    (2000, 64, 24, 160, [800, 1200], 0.25), # frontier wider than 128: forward prune stays with the list-based kernel
+])
+def test_insert_float_dyadic_grid_gram_classes(jx, dtype, n, d, R, L, calls, growth):
+    """Float builds on a dyadic grid (every distance exact in float32 in any summation order) must equal the
+    oracle's graph bit for bit; the cases walk through every size class of the matrix-core robustPrune and
+    its hand-over to the list-based kernel."""
+    x = datagen.dyadic_grid(n, d, seed=n + R).astype(dtype)
+    dt = jx.F32 if dtype == np.float32 else jx.F16
+    ref = oracle.Index(d, x.dtype, R, L, 1.2, n, batch_growth=growth)
+    g = jx.Index(d, dt, R, L, 1.2, capacity=n, max_batch=n, batch_growth=growth)
+    pos = 0
+    for c in calls or [n]:
+        ref.insert(x[pos:pos + c])
+        g.insert(dev(x[pos:pos + c]))
+        pos += c
+    oadj, odeg, adj, deg = _graphs(ref, g)
+    assert g.size() == (n, ref.entry)
+    assert np.array_equal(deg, odeg)
+    bad = np.nonzero((adj != oadj).any(axis=1))[0]
+    assert bad.size == 0, (bad[:5], adj[bad[:1]], oadj[bad[:1]])
+
+
 def _invariants(adj, deg, n, R):
     for i in range(n):
         row = adj[i, :deg[i]]
