@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--query-bits", type=int, default=0, help="B_q of the integer query (0 = 8 for 4-bit codes, 4 for 1-bit codes)")
     ap.add_argument("--cpu-queries", type=int, default=2000, help="sample size of the cpu_baseline leg (0 = skip)")
     ap.add_argument("--f16", action="store_true", help="store the float workloads (3, 4) as binary16 (App. D of the paper)")
+    ap.add_argument("--delete-frac", type=float, default=0.0,
+                    help="after everything else: mark this fraction of the vertices deleted, consolidate, and report "
+                         "rates, queries/s and recall before / after (Sec. 4.6, Table 2 of the paper)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -269,6 +272,46 @@ def main():
         cfg["quantize_s"] = round(t_quant, 2)
     if stream_log:
         cfg["stream"] = stream_log
+    if args.delete_frac > 0:
+        # batch deletion: random victims; ground truth on the live set from a wider brute force with the victims removed
+        def timed_qps(reps=5):
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(reps):
+                g.search(dq, k, L_star, mode=mode, rerank=rerank)
+            torch.cuda.synchronize()
+            return reps * nq / (time.perf_counter() - t1)
+
+        rng = np.random.Generator(np.random.PCG64(4242))
+        victims = rng.choice(n, int(args.delete_frac * n), replace=False).astype(np.int64)
+        dead = np.zeros(n, bool)
+        dead[victims] = True
+        wide, _ = g.bruteforce(dq, 64)
+        wide = wide.cpu().numpy().view(np.uint32)
+        gt_live = np.stack([row[~dead[row]][:k] for row in wide])
+        qps_before = timed_qps()
+        dv = torch.from_numpy(victims.astype(np.int32)).cuda()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        g.delete(dv)
+        torch.cuda.synchronize()
+        t_mark = time.perf_counter() - t1
+        ids, _ = g.search(dq, k, L_star, mode=mode, rerank=rerank)
+        rec_marked = recall_of(ids, gt_live)
+        qps_marked = timed_qps()
+        t1 = time.perf_counter()
+        g.consolidate()
+        torch.cuda.synchronize()
+        t_cons = time.perf_counter() - t1
+        ids, _ = g.search(dq, k, L_star, mode=mode, rerank=rerank)
+        rec_after = recall_of(ids, gt_live)
+        qps_after = timed_qps()
+        cfg["delete"] = {"fraction": args.delete_frac, "deleted": int(victims.size), "mark_ms": round(t_mark * 1e3, 3),
+                         "consolidate_s": round(t_cons, 3), "consolidate_vertices_per_s": round(n / t_cons, 1),
+                         "recall_at_10": {"before": round(rec, 4), "marked": round(rec_marked, 4), "consolidated": round(rec_after, 4)},
+                         "queries_per_s": {"before": round(qps_before, 1), "marked": round(qps_marked, 1),
+                                           "consolidated": round(qps_after, 1)}}
+        log(f"[bench] delete {cfg['delete']}")
     line = {
         "metric": "queries/sec at recall@10=0.95 (10k-query batch)", "value": round(qps, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),

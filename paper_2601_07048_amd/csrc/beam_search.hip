@@ -28,6 +28,15 @@ namespace jx {
 #ifndef JX_UMAX_EXACT
 #define JX_UMAX_EXACT 8
 #endif
+#ifndef JX_RQ1_LANES
+#define JX_RQ1_LANES 8
+#endif
+#ifndef JX_UMAX_RQ1
+#define JX_UMAX_RQ1 8
+#endif
+#ifndef JX_UMAX_RQ4
+#define JX_UMAX_RQ4 8
+#endif
 #ifndef JX_WPE_EXACT
 #define JX_WPE_EXACT 6
 #endif
@@ -36,7 +45,7 @@ template <int KIND, int T, int CPL, int NREG, int QB>
 __global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu(((KIND <= K_F32 || KIND == K_F16) && NREG <= 2 && CPL <= 2) ? JX_WPE_EXACT : 1, 8)))
 beam_search_kernel(BeamArgs a) {
     constexpr int G = 64 / T;
-    constexpr int UMAX = (KIND == K_RQ1) ? 4 : ((KIND == K_U8) ? JX_UMAX_EXACT : 8);  // 16-byte loads in flight per lane (the 1-bit path keeps its bit planes in registers)
+    constexpr int UMAX = (KIND == K_RQ1) ? JX_UMAX_RQ1 : ((KIND == K_U8) ? JX_UMAX_EXACT : ((KIND == K_RQ4) ? JX_UMAX_RQ4 : 8));  // 16-byte loads in flight per lane (the 1-bit path keeps its bit planes in registers)
     constexpr int U0 = (UMAX / CPL) > 0 ? (UMAX / CPL) : 1;
     constexpr int U = U0 < (64 / G) ? U0 : (64 / G);  // records in flight per lane group
     constexpr int FCAP = NREG * 64;
@@ -299,9 +308,31 @@ static int chunks_per_lane_pref(int kind) {
     return kind == K_RQ1 ? 1 : 2;
 }
 
+// 1-bit records (experiments: JX_RQ1_SHAPE = 16 | 8 | 4 lanes per record of at most 16 chunks)
+static int rq1_lanes_pref() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("JX_RQ1_SHAPE");
+        v = e ? atoi(e) : 0;
+        if (v != 16 && v != 8 && v != 4) v = 0;
+    }
+    return v;
+}
+
 template <int KIND, int QB>
 static hipError_t launch_shape(const BeamArgs& a, hipStream_t st) {
     const int nch = a.ds.nch;
+    if constexpr (KIND == K_RQ1) {
+        if (nch <= 16) {
+            // B_q = 4: 8 lanes x 2 chunks with the four bit planes of both chunks in registers (measured 10 % faster
+            // than 16 x 1 at L = 64..128); B_q = 8 would need 64 plane registers per lane and stays at 16 x 1
+            const int pref = rq1_lanes_pref() ? rq1_lanes_pref() : (QB == 4 ? JX_RQ1_LANES : 16);
+            if (pref == 8) return launch_nreg<KIND, 8, 2, QB>(a, st);
+            if constexpr (QB == 4) {
+                if (pref == 4) return launch_nreg<KIND, 4, 4, QB>(a, st);
+            }
+        }
+    }
     if constexpr (KIND != K_RQ1) {
         if (nch <= 64 && chunks_per_lane_pref(KIND) == 2) {
             if (nch <= 8) return launch_nreg<KIND, 4, 2, QB>(a, st);

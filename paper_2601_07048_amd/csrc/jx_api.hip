@@ -119,7 +119,8 @@ void layout(const jx_params* p, Layout* L) {
     L->vec_bytes = p->dim * elem_bytes(p->dtype);
     L->code_bytes = p->quant_bits ? p->dim * p->quant_bits / 8 : 0;
     L->meta_chunk = (L->code_bytes + 15) / 16;
-    L->code_stride = p->quant_bits ? (L->meta_chunk + 1) * 16 : 0;
+    // records start on 128-byte lines: a gather then touches ceil(record / 128) lines, the fewest any layout allows
+    L->code_stride = p->quant_bits ? ((L->meta_chunk + 1) * 16 + 127) / 128 * 128 : 0;
     int64_t off = 0;
     L->vecs = off;
     off += align256((int64_t)p->capacity * L->vec_bytes);
@@ -440,7 +441,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         h_stats->hops = hs[0];
         h_stats->dist_evals = hs[1];
         h_stats->adj_bytes = hs[0] * 4ull * p.R;
-        h_stats->vec_bytes = hs[1] * (unsigned long long)(mode == JX_EXACT ? idx->vec_bytes : idx->code_stride);
+        h_stats->vec_bytes = hs[1] * (unsigned long long)(mode == JX_EXACT ? idx->vec_bytes : (idx->meta_chunk + 1) * 16);
         h_stats->rerank_bytes = hs[2] * (unsigned long long)idx->vec_bytes;
         h_stats->rotate_ms = tm.acc[0];
         h_stats->prep_ms = tm.acc[1];
@@ -652,6 +653,7 @@ static int encode_range(jx_index* idx, int64_t first, int64_t count, hipStream_t
         e.meta_stride = idx->code_stride;
         e.meta_pad = 8;
         JX_HIP(jx::launch_encode(e, st));
+        JX_HIP(jx::launch_code_sums(e.codes, m, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, idx->quantized, st));
     }
     return JX_OK;
 }
@@ -705,6 +707,7 @@ int jx_import_codes(jx_index* idx, int32_t bits, const float* d_rotation, const 
     JX_HIP(hipMemcpyAsync(idx->d_P, d_rotation, (size_t)p.dim * p.dim * 4, hipMemcpyDeviceToDevice, st));
     JX_HIP(hipMemcpyAsync(idx->d_centroid, d_centroid, (size_t)p.dim * 4, hipMemcpyDeviceToDevice, st));
     JX_HIP(jx::launch_pack_records(idx->d_codes, idx->n, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, d_codes, d_meta, st));
+    JX_HIP(jx::launch_code_sums(idx->d_codes, idx->n, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, bits, st));
     idx->quantized = bits;
     idx->qbits = query_bits;
     idx->rule = JX_RULE_MAXABS;

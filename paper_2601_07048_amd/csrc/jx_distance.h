@@ -26,7 +26,6 @@ struct QueryRegs {
     static constexpr int PLANES = (KIND == K_RQ4) ? 2 : (KIND == K_RQ1 ? QB : 1);
     static constexpr int N = 4 * CPL * PLANES;
     uint32_t w[N];
-    uint32_t cmask[CPL];  // RaBitQ: all-ones for code chunks, 0 for the meta chunk and beyond
     // per-query scalars
     int32_t qq;           // U8: sum q^2
     float qqf;            // F16: sum q^2
@@ -79,8 +78,6 @@ __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const Di
                 q.w[(p * CPL + j) * 4 + 3] = v.w;
             }
         }
-#pragma unroll
-        for (int j = 0; j < CPL; j++) q.cmask[j] = (lig + T * j) < a.meta_chunk ? 0xFFFFFFFFu : 0u;
     }
 }
 
@@ -181,39 +178,36 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
             dist_code = f32_to_ordered(acc);
         } else {
             // RaBitQ estimator, integer-query form (Sec. 5.1): exact integer
-            // <u,q_int> and sum(u), then five float32 operations in a fixed order.
+            // <u,q_int>, sum(u) read from the record (stored at encode time), then
+            // five float32 operations in a fixed order.  The query planes are zero
+            // for the meta chunk and beyond, so no chunk has to be masked.
             uint32_t I = 0, S = 0;
             float m_add = 0.f, m_rescale = 0.f;
             const int mj = a.meta_chunk / T, ml = a.meta_chunk % T;
             writer = (lig == ml);
 #pragma unroll
             for (int j = 0; j < CPL; j++) {
-                uint4 v = data[u][j];
+                const uint4 v = data[u][j];
                 if (j == mj) {
                     m_add = __uint_as_float(v.x);
                     m_rescale = __uint_as_float(v.y);
+                    S = v.z;
                 }
-                v.x &= q.cmask[j];
-                v.y &= q.cmask[j];
-                v.z &= q.cmask[j];
-                v.w &= q.cmask[j];
                 if constexpr (KIND == K_RQ4) {
                     uint32_t ih = 0, il = 0;
                     const uint32_t* qh = &q.w[(0 * CPL + j) * 4];
                     const uint32_t* ql = &q.w[(1 * CPL + j) * 4];
-                    ih = __builtin_amdgcn_udot8(v.x, qh[0], ih, false);
-                    ih = __builtin_amdgcn_udot8(v.y, qh[1], ih, false);
-                    ih = __builtin_amdgcn_udot8(v.z, qh[2], ih, false);
-                    ih = __builtin_amdgcn_udot8(v.w, qh[3], ih, false);
                     il = __builtin_amdgcn_udot8(v.x, ql[0], il, false);
                     il = __builtin_amdgcn_udot8(v.y, ql[1], il, false);
                     il = __builtin_amdgcn_udot8(v.z, ql[2], il, false);
                     il = __builtin_amdgcn_udot8(v.w, ql[3], il, false);
+                    if constexpr (QB == 8) {
+                        ih = __builtin_amdgcn_udot8(v.x, qh[0], ih, false);
+                        ih = __builtin_amdgcn_udot8(v.y, qh[1], ih, false);
+                        ih = __builtin_amdgcn_udot8(v.z, qh[2], ih, false);
+                        ih = __builtin_amdgcn_udot8(v.w, qh[3], ih, false);
+                    }
                     I += (QB == 8) ? (16u * ih + il) : il;
-                    S = __builtin_amdgcn_udot8(v.x, 0x11111111u, S, false);
-                    S = __builtin_amdgcn_udot8(v.y, 0x11111111u, S, false);
-                    S = __builtin_amdgcn_udot8(v.z, 0x11111111u, S, false);
-                    S = __builtin_amdgcn_udot8(v.w, 0x11111111u, S, false);
                 } else {
 #pragma unroll
                     for (int b = 0; b < QB; b++) {
@@ -222,12 +216,9 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
                                        __builtin_popcount(v.z & qp[2]) + __builtin_popcount(v.w & qp[3]);
                         I += cnt << b;
                     }
-                    S += __builtin_popcount(v.x) + __builtin_popcount(v.y) + __builtin_popcount(v.z) +
-                         __builtin_popcount(v.w);
                 }
             }
             I = group_sum<T>(I);
-            S = group_sum<T>(S);
             float t = __fmul_rn((float)I, q.delta);
             float t2 = __fmul_rn(q.lo, (float)S);
             t = __fadd_rn(t, t2);

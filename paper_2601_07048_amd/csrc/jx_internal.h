@@ -112,6 +112,7 @@ hipError_t launch_unpack_records(const uint8_t* recs, long long n, int code_stri
                                  uint8_t* codes, float* meta, hipStream_t st);
 hipError_t launch_pack_records(uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,
                                const uint8_t* codes, const float* meta, hipStream_t st);
+hipError_t launch_code_sums(uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off, int bits, hipStream_t st);
 hipError_t launch_query_prep(const QueryPrepArgs& a, hipStream_t st);
 hipError_t launch_rerank(int dtype, const RerankArgs& a, hipStream_t st);
 hipError_t launch_column_mean(const void* vecs, int dtype, long long n, int d, double* partial, float* mean, hipStream_t st);

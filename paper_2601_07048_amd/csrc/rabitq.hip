@@ -414,6 +414,31 @@ hipError_t launch_pack_records(uint8_t* recs, long long n, int code_stride, int 
     return hipGetLastError();
 }
 
+// Sum of the code units of every record (popcount for 1-bit codes, sum of nibbles for 4-bit codes), stored as a
+// uint32 behind the two floats of the meta chunk: the estimator's sum(u) term then costs the search kernel nothing.
+__global__ void __launch_bounds__(256) code_sums_kernel(uint8_t* recs, long long n, int code_stride, int code_bytes,
+                                                       int meta_off, int bits) {
+    const long long v = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const int lane = lane_id();
+    uint8_t* rec = recs + (size_t)v * code_stride;
+    uint32_t s = 0;
+    for (int b = lane * 4; b < code_bytes; b += 256) {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(rec + b);
+        s += bits == 1 ? (uint32_t)__builtin_popcount(w) : __builtin_amdgcn_udot8(w, 0x11111111u, 0u, false);
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) s += shfl_xor(s, m);
+    if (lane == 0) *reinterpret_cast<uint32_t*>(rec + meta_off + 8) = s;
+}
+
+hipError_t launch_code_sums(uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off, int bits, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(code_sums_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, recs, n, code_stride, code_bytes,
+                       meta_off, bits);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ query records
 
 __global__ void __launch_bounds__(256) query_prep_kernel(QueryPrepArgs a) {

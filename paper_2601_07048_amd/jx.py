@@ -111,7 +111,7 @@ class Index:
         self._h = h
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:  # _lib is gone at interpreter shutdown
             _lib.jx_destroy(self._h)
             self._h = None
 

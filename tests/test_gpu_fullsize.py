@@ -88,6 +88,58 @@ def test_fullsize_build_matches_oracle(jx, big):
     assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
 
 
+def test_fullsize_delete_consolidate_sampled_against_oracle(jx, big):
+    """Mark 10 % of the 1M vertices and consolidate; on sampled vertices the new row must be the oracle's
+    robustPrune of the candidate set assembled from the graph before the call, bit for bit; untouched rows
+    stay; searches return no deleted id and equal the oracle's on the exported graph.  Runs last among the
+    tests that share the index, because it changes it."""
+    x, q, g, adj, deg = big
+    adj0, deg0 = u32(adj), u32(deg)
+    rng = np.random.Generator(np.random.PCG64(4242))
+    victims = rng.choice(N, N // 10, replace=False)
+    dead = np.zeros(N, bool)
+    dead[victims] = True
+    g.delete(dev(victims.astype(np.uint32)))
+    assert g.deleted_count() == victims.size
+    g.consolidate()
+    a1, d1 = g.export_graph()
+    adj1, deg1 = u32(a1), u32(d1)
+    assert (deg1[dead] == 0).all()
+    live_rows = adj1[~dead]
+    assert not dead[live_rows[live_rows != 0xFFFFFFFF]].any()
+    xi = x.astype(np.int64)
+    checked = 0
+    for v in rng.choice(N, 600, replace=False):
+        if dead[v]:
+            continue
+        row = adj0[v, :deg0[v]]
+        if not dead[row].any():
+            assert np.array_equal(adj1[v], adj0[v])
+            continue
+        cand = []
+        for u in row:
+            if not dead[u]:
+                cand.append(int(u))
+            else:
+                cand += [int(w) for w in adj0[u, :deg0[u]] if not dead[w] and w != v]
+        cand = np.array(sorted(set(cand)), np.uint32)
+        dist = ((xi[cand] - xi[v]) ** 2).sum(axis=1).astype(np.float64)
+        want = oracle.robust_prune(int(v), cand, dist, x, R, 1.2)
+        assert adj1[v, :deg1[v]].tolist() == want.tolist(), v
+        checked += 1
+    assert checked > 300
+    n, entry = g.size()
+    assert not dead[entry]
+    ref = oracle.Index(128, np.uint8, R, LB, 1.2, N)
+    ref.set_graph(x, adj1, entry)
+    ref.delete(victims.astype(np.uint32))
+    sample = rng.choice(NQ, 200, replace=False)
+    ids, dist = g.search(dev(q), 10, 96)
+    want = ref.search(q[sample], 10, 96)
+    assert np.array_equal(u32(ids)[sample], want["ids"])
+    assert not dead[u32(ids)].any()
+
+
 def _device_base(workload, n, d):
     dx = torch.empty((n, d), dtype=torch.float32, device="cuda")
     step = 16 * datagen.CHUNK
