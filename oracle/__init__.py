@@ -57,6 +57,7 @@ def lib():
         L.orc_rabitq_est_int.restype = C.c_float
         L.orc_num_threads.restype = C.c_int
         L.orc_index_deleted_count.restype = C.c_int64
+        L.orc_index_compact.restype = C.c_int64
     return _lib
 
 
@@ -266,6 +267,14 @@ class Index:
 
     def consolidate(self, nthreads=None):
         lib().orc_index_consolidate(self._h, C.c_int(_nt(nthreads)))
+
+    def compact(self):
+        """Remove the deleted vertices (after consolidate); returns old id -> new id (NONE for removed)."""
+        m = np.empty(self.n, np.uint32)
+        rc = lib().orc_index_compact(self._h, _p(m))
+        if rc < 0:
+            raise RuntimeError("compact needs a consolidated index")
+        return m
 
     def quantize(self, bits, P, centroid=None, qbits=8, rule=RULE_MAXCOS, nthreads=None):
         P = np.ascontiguousarray(P, dtype=np.float32)

@@ -809,6 +809,52 @@ void orc_index_consolidate(orc_index *x, int nthreads) {
     }
 }
 
+/*
+ * Compact (Sec. 4.6, third phase): physically remove the deleted vertices.  It
+ * may only follow a consolidation: no live row may still name a deleted vertex
+ * (returns -1 otherwise, changing nothing).  Live vertices keep their relative
+ * order: new id = number of live vertices with a smaller old id, so every
+ * (distance, id) comparison -- and with it every search -- is unchanged up to
+ * this renaming.  Vectors, rows, codes and the entry point move along; the
+ * marks are cleared.  old_to_new [n_old] (may be NULL) receives the renaming,
+ * ORC_NONE for removed vertices.  Returns the new number of points.
+ */
+int64_t orc_index_compact(orc_index *x, uint32_t *old_to_new) {
+    const int R = x->R;
+    const size_t vs = (size_t)x->d * esize(x->dtype);
+    const int64_t n = x->n;
+    for (int64_t v = 0; v < n; v++) {
+        if (x->deleted[v]) continue;
+        const uint32_t *row = x->adj + (size_t)v * R;
+        for (int j = 0; j < R && row[j] != ORC_NONE; j++)
+            if (x->deleted[row[j]]) return -1;
+    }
+    uint32_t *map = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(n + 1));
+    int64_t live = 0;
+    for (int64_t v = 0; v < n; v++) map[v] = x->deleted[v] ? ORC_NONE : (uint32_t)live++;
+    for (int64_t v = 0; v < n; v++) {
+        if (x->deleted[v]) continue;
+        const int64_t w = map[v]; /* w <= v: moving in increasing order never overwrites an unread source */
+        memmove((char *)x->base + (size_t)w * vs, (const char *)x->base + (size_t)v * vs, vs);
+        uint32_t *dst = x->adj + (size_t)w * R;
+        const uint32_t *src = x->adj + (size_t)v * R;
+        for (int j = 0; j < R; j++) dst[j] = src[j] == ORC_NONE ? ORC_NONE : map[src[j]];
+        if (x->bits) {
+            memmove(x->codes + (size_t)w * x->code_bytes, x->codes + (size_t)v * x->code_bytes, (size_t)x->code_bytes);
+            x->meta[2 * w] = x->meta[2 * v];
+            x->meta[2 * w + 1] = x->meta[2 * v + 1];
+        }
+    }
+    memset(x->adj + (size_t)live * R, 0xFF, sizeof(uint32_t) * (size_t)(n - live) * R);
+    memset(x->deleted, 0, (size_t)n);
+    if (x->entry != ORC_NONE) x->entry = map[x->entry];
+    if (old_to_new) memcpy(old_to_new, map, sizeof(uint32_t) * (size_t)n);
+    free(map);
+    x->n = live;
+    x->n_deleted = 0;
+    return live;
+}
+
 /* ------------------------------------------------------------------ */
 /* RaBitQ (Sec. 5.1)                                                   */
 /* ------------------------------------------------------------------ */
