@@ -306,11 +306,21 @@ def main():
         ids, _ = g.search(dq, k, L_star, mode=mode, rerank=rerank)
         rec_after = recall_of(ids, gt_live)
         qps_after = timed_qps()
+        t1 = time.perf_counter()
+        ren = g.compact()
+        torch.cuda.synchronize()
+        t_comp = time.perf_counter() - t1
+        ren = ren.cpu().numpy().view(np.uint32)
+        ids, _ = g.search(dq, k, L_star, mode=mode, rerank=rerank)
+        rec_comp = recall_of(ids, ren[gt_live])
+        qps_comp = timed_qps()
         cfg["delete"] = {"fraction": args.delete_frac, "deleted": int(victims.size), "mark_ms": round(t_mark * 1e3, 3),
                          "consolidate_s": round(t_cons, 3), "consolidate_vertices_per_s": round(n / t_cons, 1),
-                         "recall_at_10": {"before": round(rec, 4), "marked": round(rec_marked, 4), "consolidated": round(rec_after, 4)},
+                         "compact_s": round(t_comp, 3),
+                         "recall_at_10": {"before": round(rec, 4), "marked": round(rec_marked, 4), "consolidated": round(rec_after, 4),
+                                          "compacted": round(rec_comp, 4)},
                          "queries_per_s": {"before": round(qps_before, 1), "marked": round(qps_marked, 1),
-                                           "consolidated": round(qps_after, 1)}}
+                                           "consolidated": round(qps_after, 1), "compacted": round(qps_comp, 1)}}
         log(f"[bench] delete {cfg['delete']}")
     line = {
         "metric": "queries/sec at recall@10=0.95 (10k-query batch)", "value": round(qps, 1), "unit": "queries/s",

@@ -177,8 +177,8 @@ int jx_beam_frontier(jx_index* idx, const void* d_queries, int64_t nq, int32_t L
 int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, uint32_t* d_out_ids,
                   float* d_out_dist, void* stream);
 
-/* Batch deletion (Sec. 4.6; the two-step scheme of FreshDiskANN that the
- * paper adopts).
+/* Batch deletion (Sec. 4.6 and 6.5: mark, consolidate, compact; the scheme of
+ * FreshDiskANN that the paper adopts).
  *
  * jx_delete marks the n vertices d_ids[n] (device) as deleted: an in-place,
  * asynchronous flag update.  Ids >= the number of points and ids already
@@ -194,16 +194,28 @@ int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, u
  * its row becomes robustPrune (Alg. 3, the index's alpha and R) of that set;
  * all rows are computed from the graph as it stood at the call.  The rows of
  * deleted vertices are then emptied.  If the entry point is deleted, the
- * live vertex nearest to it (distance, then id) takes its place.  Ids are
- * never reused and the vector store is not compacted; deleted vertices stay
- * marked.  Synchronises with the stream (it needs counts on the host).
+ * live vertex nearest to it (distance, then id) takes its place.  Ids do
+ * not change and deleted vertices stay marked (jx_compact removes them).
+ * Synchronises with the stream (it needs counts on the host).
  * JX_ECAPACITY if one vertex has more than max_batch * R candidates
  * (max_batch >= R always suffices).
  *
  * jx_deleted_count returns the number of vertices marked so far
- * (synchronises with the stream). */
+ * (synchronises with the stream).
+ *
+ * jx_compact (third phase) removes the deleted vertices physically: live
+ * vertices keep their relative order (new id = number of live vertices with
+ * a smaller old id), vectors, rows, RaBitQ records and the entry point move
+ * along, the freed tail of the arena becomes insertable again and the marks
+ * are cleared.  Because the renaming preserves the id order, every search
+ * returns the renamed ids of what it returned before.  d_old_to_new (device,
+ * [points before the call], may be NULL) receives the renaming, JX_NONE for
+ * removed vertices.  JX_ESTATE, and nothing changed, if a live vertex still
+ * points to a deleted one (jx_consolidate has not run since the last
+ * jx_delete).  Synchronises with the stream. */
 int jx_delete(jx_index* idx, const uint32_t* d_ids, int64_t n, void* stream);
 int jx_consolidate(jx_index* idx, void* stream);
+int jx_compact(jx_index* idx, uint32_t* d_old_to_new, void* stream);
 int jx_deleted_count(jx_index* idx, int64_t* n_deleted, void* stream);
 
 /* Calibration aid for the roofline of beamSearch (Sec. 6.6 prices the kernel

@@ -236,4 +236,105 @@ hipError_t launch_nearest_live(const void* vecs, int dtype, long long n, int d, 
     return launch_argmin(dist, n, out_id, st);
 }
 
+// ---- compaction (third phase of Sec. 4.6): order-preserving renaming of the live vertices ----
+
+// flag[v] = 1 for live vertices (scanned into the renaming afterwards); err is set if a live row names a deleted vertex
+__global__ void __launch_bounds__(256) compact_flags_kernel(const uint32_t* adj, int R, long long n, const uint8_t* deleted,
+                                                           uint32_t* flag, uint32_t* err) {
+    const long long v = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v > n) return;
+    const int lane = lane_id();
+    if (v == n) {  // one slot past the end receives the total
+        if (lane == 0) flag[n] = 0u;
+        return;
+    }
+    const bool live = deleted[v] == 0;
+    if (lane == 0) flag[v] = live ? 1u : 0u;
+    if (!live) return;
+    bool bad = false;
+    for (int j = lane; j < R; j += 64) {
+        const uint32_t u = adj[(size_t)v * R + j];
+        if (u != JX_NONE_ID && deleted[u]) bad = true;
+    }
+    if (bad) atomicOr(err, 1u);
+}
+
+// adj[i] = map[adj[i]] in place; the public renaming gets NONE for removed vertices
+__global__ void compact_rename_kernel(uint32_t* adj, long long n_entries, const uint32_t* map, const uint8_t* deleted, long long n,
+                                      uint32_t* public_map) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_entries) {
+        const uint32_t u = adj[i];
+        if (u != JX_NONE_ID) adj[i] = map[u];
+    }
+    if (public_map && i < n) public_map[i] = deleted[i] ? JX_NONE_ID : map[i];
+}
+
+// live records of vertices [c0, c1) -> staging, packed in order; UNIT = uint4 or uint32_t
+template <typename UNIT>
+__global__ void __launch_bounds__(256) compact_gather_kernel(const uint8_t* base, int rec_bytes, long long c0, long long c1,
+                                                            const uint32_t* map, const uint8_t* deleted, uint8_t* staging) {
+    const long long v = c0 + (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= c1 || deleted[v]) return;
+    const int lane = lane_id();
+    const size_t slot = (size_t)(map[v] - map[c0]);
+    const UNIT* src = reinterpret_cast<const UNIT*>(base + (size_t)v * rec_bytes);
+    UNIT* dst = reinterpret_cast<UNIT*>(staging + slot * rec_bytes);
+    for (int b = lane; b < rec_bytes / (int)sizeof(UNIT); b += 64) dst[b] = src[b];
+}
+
+// staging -> base[map[c0] ...]; the number of records is read on the device (map[c1] - map[c0])
+template <typename UNIT>
+__global__ void __launch_bounds__(256) compact_scatter_kernel(uint8_t* base, int rec_bytes, long long c0, long long c1,
+                                                             const uint32_t* map, const uint8_t* staging) {
+    const size_t units = (size_t)(map[c1] - map[c0]) * (size_t)(rec_bytes / (int)sizeof(UNIT));
+    UNIT* dst = reinterpret_cast<UNIT*>(base + (size_t)map[c0] * rec_bytes);
+    const UNIT* src = reinterpret_cast<const UNIT*>(staging);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < units; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_compact_flags(const uint32_t* adj, int R, long long n, const uint8_t* deleted, uint32_t* flag, uint32_t* err,
+                                hipStream_t st) {
+    hipLaunchKernelGGL(compact_flags_kernel, dim3((unsigned)((n + 1 + 3) / 4)), dim3(256), 0, st, adj, R, n, deleted, flag, err);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact_rename(uint32_t* adj, int R, long long n, const uint32_t* map, const uint8_t* deleted,
+                                 uint32_t* public_map, hipStream_t st) {
+    const long long ne = n * R;
+    hipLaunchKernelGGL(compact_rename_kernel, dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, st, adj, ne, map, deleted, n,
+                       public_map);
+    return hipGetLastError();
+}
+
+// Moves the live records of one array to their new places, slice by slice through the staging buffer: the
+// destination of a slice ends where its sources begin at the latest, and its own sources are all in the staging
+// buffer before the first of them is overwritten.
+template <typename UNIT>
+static void compact_records_units(uint8_t* base, int rec_bytes, long long n, const uint32_t* map, const uint8_t* deleted,
+                                  uint8_t* staging, long long slice, hipStream_t st) {
+    for (long long c0 = 0; c0 < n; c0 += slice) {
+        const long long c1 = c0 + slice < n ? c0 + slice : n;
+        hipLaunchKernelGGL(compact_gather_kernel<UNIT>, dim3((unsigned)((c1 - c0 + 3) / 4)), dim3(256), 0, st, base, rec_bytes, c0,
+                           c1, map, deleted, staging);
+        hipLaunchKernelGGL(compact_scatter_kernel<UNIT>, dim3(2048), dim3(256), 0, st, base, rec_bytes, c0, c1, map, staging);
+    }
+}
+
+// Moves the live records of one array to their new places, slice by slice through the staging buffer: the
+// destination of a slice ends where its sources begin at the latest, and its own sources are all in the staging
+// buffer before the first of them is overwritten.
+hipError_t launch_compact_records(uint8_t* base, int rec_bytes, long long n, const uint32_t* map, const uint8_t* deleted,
+                                  uint8_t* staging, long long staging_bytes, hipStream_t st) {
+    if (rec_bytes % 4) return hipErrorInvalidValue;
+    long long slice = staging_bytes / rec_bytes;
+    if (slice < 1) return hipErrorInvalidValue;
+    if (slice > (1LL << 24)) slice = 1LL << 24;  // keeps the gather grid within range
+    if (rec_bytes % 16 == 0)
+        compact_records_units<uint4>(base, rec_bytes, n, map, deleted, staging, slice, st);
+    else
+        compact_records_units<uint32_t>(base, rec_bytes, n, map, deleted, staging, slice, st);
+    return hipGetLastError();
+}
+
 }  // namespace jx

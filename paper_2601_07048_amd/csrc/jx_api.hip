@@ -885,6 +885,46 @@ int jx_consolidate(jx_index* idx, void* stream) {
     return JX_OK;
 }
 
+int jx_compact(jx_index* idx, uint32_t* d_old_to_new, void* stream) {
+    if (!idx) return fail(JX_EINVAL, "index is NULL");
+    hipStream_t st = as_stream(stream);
+    const int64_t n = idx->n;
+    if (n == 0) return JX_OK;
+    const jx_params& p = idx->p;
+    InsertWork w;
+    insert_work(&p, p.max_batch, &w);
+    if (w.total > idx->work_bytes) return fail(JX_ECAPACITY, "workspace too small");
+    uint8_t* W = idx->d_work;
+    uint32_t* map = (uint32_t*)(W + w.dist);           // [n + 1]: live vertices before v; [n] = live in total
+    uint32_t* err = (uint32_t*)(W + w.counters) + 40;
+    uint8_t* staging = W;                               // everything in front of the renaming
+    const int64_t staging_bytes = w.dist;
+    JX_HIP(jx::launch_fill_u32(err, 1, 0u, st));
+    JX_HIP(jx::launch_compact_flags(idx->d_adj, p.R, n, idx->d_deleted, map, err, st));
+    uint32_t herr = 0;
+    JX_HIP(hipMemcpyAsync(&herr, err, 4, hipMemcpyDeviceToHost, st));
+    JX_HIP(hipStreamSynchronize(st));
+    if (herr) return fail(JX_ESTATE, "a live vertex still points to a deleted one: call jx_consolidate first");
+    JX_HIP(jx::launch_scan_u32(map, n + 1, st));
+    JX_HIP(jx::launch_compact_rename(idx->d_adj, p.R, n, map, idx->d_deleted, d_old_to_new, st));
+    JX_HIP(jx::launch_compact_records(idx->d_vecs, idx->vec_bytes, n, map, idx->d_deleted, staging, staging_bytes, st));
+    JX_HIP(jx::launch_compact_records((uint8_t*)idx->d_adj, p.R * 4, n, map, idx->d_deleted, staging, staging_bytes, st));
+    if (idx->quantized)
+        JX_HIP(jx::launch_compact_records(idx->d_codes, idx->code_stride, n, map, idx->d_deleted, staging, staging_bytes, st));
+    uint32_t live = 0, new_entry = JX_NONE;
+    JX_HIP(hipMemcpyAsync(&live, map + n, 4, hipMemcpyDeviceToHost, st));
+    if (idx->entry != JX_NONE) JX_HIP(hipMemcpyAsync(&new_entry, map + idx->entry, 4, hipMemcpyDeviceToHost, st));
+    JX_HIP(hipStreamSynchronize(st));
+    if (live > (uint64_t)n) return fail(JX_EHIP, "compaction counted %u live vertices of %lld", live, (long long)n);
+    if (live < (uint64_t)n) JX_HIP(jx::launch_fill_u32(idx->d_adj + (size_t)live * p.R, (n - live) * p.R, JX_NONE, st));
+    JX_HIP(jx::launch_fill_u32((uint32_t*)idx->d_deleted, (n + 3) / 4, 0u, st));
+    JX_HIP(jx::launch_fill_u32((uint32_t*)(idx->d_stats + 8), 2, 0u, st));
+    idx->n = live;
+    idx->entry = live ? new_entry : JX_NONE;
+    idx->any_delete = 0;
+    return JX_OK;
+}
+
 int jx_probe_gather(const void* d_table, int64_t n_rec, int32_t rec_bytes, const uint32_t* d_ids, int64_t n_ids,
                     int32_t blocks, uint32_t* d_sink, void* stream) {
     if (!d_table || !d_ids || !d_sink) return fail(JX_EINVAL, "NULL argument");

@@ -140,6 +140,13 @@ hipError_t launch_clear_deleted_rows(uint32_t* adj, int R, long long n, const ui
 hipError_t launch_nearest_live(const void* vecs, int dtype, long long n, int d, uint32_t target, const uint8_t* deleted,
                                double* dist, uint32_t* out_id, hipStream_t st);
 
+hipError_t launch_compact_flags(const uint32_t* adj, int R, long long n, const uint8_t* deleted, uint32_t* flag, uint32_t* err,
+                                hipStream_t st);
+hipError_t launch_compact_rename(uint32_t* adj, int R, long long n, const uint32_t* map, const uint8_t* deleted,
+                                 uint32_t* public_map, hipStream_t st);
+hipError_t launch_compact_records(uint8_t* base, int rec_bytes, long long n, const uint32_t* map, const uint8_t* deleted,
+                                  uint8_t* staging, long long staging_bytes, hipStream_t st);
+
 // ---- brute force ------------------------------------------------------------
 struct BfArgs {
     const void* base;

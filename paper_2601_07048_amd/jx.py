@@ -24,7 +24,7 @@ MAX_L, MAX_R, MAX_BF_K = 512, 256, 128
 EXPORTS = [
     "jx_arena_bytes", "jx_create", "jx_destroy", "jx_insert", "jx_quantize", "jx_search", "jx_beam_frontier",
     "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_import_codes", "jx_rotate",
-    "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_deleted_count", "jx_probe_gather", "jx_strerror", "jx_last_error",
+    "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_compact", "jx_deleted_count", "jx_probe_gather", "jx_strerror", "jx_last_error",
 ]
 
 
@@ -230,6 +230,14 @@ class Index:
     def consolidate(self):
         with torch.cuda.device(self.device):
             _check(_lib.jx_consolidate(self._h, _stream()))
+
+    def compact(self, want_map=True):
+        """jx_compact; returns old id -> new id (int32 tensor, -1 = NONE for removed vertices) if asked."""
+        n_old, _ = self.size()
+        m = torch.empty(n_old, dtype=torch.int32, device=self.device) if want_map else None
+        with torch.cuda.device(self.device):
+            _check(_lib.jx_compact(self._h, _ptr(m), _stream()))
+        return m
 
     def deleted_count(self):
         n = C.c_int64()

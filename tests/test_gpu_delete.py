@@ -254,3 +254,75 @@ def test_consolidate_capacity_error(jx):
     # nothing was changed
     adj, _ = g.export_graph()
     assert np.array_equal(u32(adj), ref.graph()[0])
+
+
+@pytest.mark.parametrize("n,d,R,L,frac,quant", [
+    (600, 32, 8, 16, 0.1, 0),
+    (3000, 128, 32, 64, 0.3, 0),
+    (2500, 128, 70, 130, 0.2, 0),
+    (3000, 64, 13, 32, 0.25, 0),      # row of 52 bytes: moved in 4-byte units
+])
+def test_compact_u8_bit_exact(jx, n, d, R, L, frac, quant):
+    x = random_data(n, d, np.uint8, seed=5 * n + R)
+    q = random_data(200, d, np.uint8, seed=n + 3)
+    ref, g = _pair(jx, x, R, L)
+    rng = np.random.default_rng(n + 2)
+    dele = np.unique(np.concatenate([rng.choice(n, int(frac * n), replace=False), [ref.entry]])).astype(np.uint32)
+    ref.delete(dele)
+    g.delete(dev(dele))
+    with pytest.raises(jx.JxError) as e:
+        g.compact()
+    assert e.value.code == -3
+    ref.consolidate()
+    g.consolidate()
+    before = u32(g.search(dev(q), 10, L)[0])
+    want_map = ref.compact()
+    got_map = u32(g.compact())
+    assert np.array_equal(got_map, want_map)
+    assert g.size() == (ref.n, ref.entry) and g.deleted_count() == 0
+    _same_graph(ref, g)
+    oi = _same_search(ref, g, q, 10, L)
+    assert np.array_equal(oi, want_map[before])      # a renaming, nothing else
+    bi, bd = g.bruteforce(dev(q[:20]), 5)             # the vectors moved with their ids
+    oi2, od2 = oracle.bruteforce(x[np.setdiff1d(np.arange(n), dele)], q[:20], 5)
+    assert np.array_equal(u32(bi), oi2)
+    # the freed tail takes new points
+    extra = random_data(400, d, np.uint8, seed=n + 9)
+    ref.insert(extra)
+    g.insert(dev(extra))
+    _same_graph(ref, g)
+    _same_search(ref, g, q, 10, L)
+
+
+def test_compact_without_deletions_is_identity(jx):
+    x = random_data(1000, 32, np.uint8, seed=77)
+    ref, g = _pair(jx, x, 8, 16)
+    m = u32(g.compact())
+    assert np.array_equal(m, np.arange(1000))
+    _same_graph(ref, g)
+
+
+def test_compact_rabitq_records_move(jx):
+    """Quantised float index: after delete / consolidate / compact the estimated-distance search with re-rank
+    returns the renamed ids of what it returned before, with identical distances."""
+    from paper_2601_07048_amd import datagen
+    n, d, R, L = 3000, 128, 32, 64
+    x = random_data(n, d, np.float32, seed=61)
+    q = random_data(150, d, np.float32, seed=62)
+    g = jx.Index(d, jx.F32, R, L, 1.2, capacity=n, max_batch=n, quant_bits=4)
+    g.insert(dev(x))
+    g.quantize(4, dev(datagen.random_orthogonal(d, seed=7).astype(np.float32)))
+    dele = np.random.default_rng(8).choice(n, 600, replace=False).astype(np.uint32)
+    g.delete(dev(dele))
+    g.consolidate()
+    b_ex = g.search(dev(q), 10, L)
+    b_rq = g.search(dev(q), 10, L, mode=jx.RABITQ)
+    b_rr = g.search(dev(q), 10, L, mode=jx.RABITQ, rerank=40)
+    m = u32(g.compact())
+    assert g.size()[0] == n - 600
+    for (bi, bd), kw in ((b_ex, {}), (b_rq, dict(mode=jx.RABITQ)), (b_rr, dict(mode=jx.RABITQ, rerank=40))):
+        ai, ad = g.search(dev(q), 10, L, **kw)
+        assert np.array_equal(u32(ai), m[u32(bi)])
+        assert np.array_equal(ad.cpu().numpy(), bd.cpu().numpy())
+    codes, meta, _ = g.export_codes()
+    assert codes.shape[0] == n - 600
