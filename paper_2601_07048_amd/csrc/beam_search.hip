@@ -57,14 +57,17 @@ beam_search_kernel(BeamArgs a) {
     if (qi >= a.nq) return;  // whole wavefront leaves; there is no block-level barrier below
 
     const int H = a.hash_slots;
-    const size_t per_wave = (size_t)FCAP * 8 + 64 * 8 + 64 * 4 + (size_t)H * 4;
+    const int tag_bits = a.tag_bits;  // > 0: 16-bit entries (slot and tag together name the id exactly)
+    const uint32_t id_mask = tag_bits ? ((1u << (tag_bits + 31 - __builtin_clz((uint32_t)H))) - 1u) : 0u;
+    const size_t per_wave = (size_t)FCAP * 8 + 64 * 8 + 64 * 4 + (size_t)H * (tag_bits ? 2 : 4);
     unsigned char* my = smem + per_wave * wave;
     uint64_t* fr = reinterpret_cast<uint64_t*>(my);
     uint64_t* cand_key = fr + FCAP;
     uint32_t* cand_id = reinterpret_cast<uint32_t*>(cand_key + 64);
     uint32_t* tab = cand_id + 64;
 
-    for (int i = lane; i < H; i += 64) tab[i] = JX_NONE_ID;
+    uint16_t* tab16 = reinterpret_cast<uint16_t*>(tab);
+    for (int i = lane; i < (tag_bits ? H / 2 : H); i += 64) tab[i] = JX_NONE_ID;
     for (int i = lane; i < FCAP; i += 64) fr[i] = JX_EMPTY_KEY;
 
     QueryRegs<KIND, CPL, QB> q;
@@ -84,7 +87,12 @@ beam_search_kernel(BeamArgs a) {
     // seed: the entry vertex
     if (lane == 0) {
         cand_id[0] = a.entry;
-        tab[__umulhi(a.entry * 0x9E3779B1u, (uint32_t)H)] = a.entry;
+        if (tag_bits) {
+            const uint32_t h = (a.entry * 0x9E3779B1u) & id_mask;
+            tab16[h >> tag_bits] = (uint16_t)(h & ((1u << tag_bits) - 1u));
+        } else {
+            tab[__umulhi(a.entry * 0x9E3779B1u, (uint32_t)H)] = a.entry;
+        }
     }
     wave_sync();
     eval_batch<KIND, T, CPL, QB, 1>(q, a.ds, 0, 1, cand_id, cand_key, g, lig);
@@ -160,9 +168,18 @@ beam_search_kernel(BeamArgs a) {
             bool is_new = false;
             // ---- 3. visited filter
             if (v != JX_NONE_ID) {
-                uint32_t h = __umulhi(v * 0x9E3779B1u, (uint32_t)H);
-                is_new = tab[h] != v;
-                if (is_new) tab[h] = v;
+                if (tag_bits) {
+                    // ids below 2^b, b = log2(H) + tag_bits: multiplying by an odd constant permutes them, so the
+                    // slot (high bits) and the tag (low bits) of the product identify the id
+                    const uint32_t h = (v * 0x9E3779B1u) & id_mask;
+                    const uint16_t tag = (uint16_t)(h & ((1u << tag_bits) - 1u));
+                    is_new = tab16[h >> tag_bits] != tag;
+                    if (is_new) tab16[h >> tag_bits] = tag;
+                } else {
+                    uint32_t h = __umulhi(v * 0x9E3779B1u, (uint32_t)H);
+                    is_new = tab[h] != v;
+                    if (is_new) tab[h] = v;
+                }
             }
             uint64_t nm = ballot(is_new);
             if (ballot(v != JX_NONE_ID) == 0ull) break;  // rows are filled from the left
@@ -278,7 +295,7 @@ static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st) {
     dim3 grid((unsigned)((a.nq + JX_BEAM_WPB - 1) / JX_BEAM_WPB)), block(JX_BEAM_WPB * 64);
 #define JX_LAUNCH(NR)                                                                                   \
     {                                                                                                   \
-        size_t sh = ((size_t)(NR) * 64 * 8 + 64 * 8 + 64 * 4 + (size_t)H * 4) * JX_BEAM_WPB;            \
+        size_t sh = ((size_t)(NR) * 64 * 8 + 64 * 8 + 64 * 4 + (size_t)H * (a.tag_bits ? 2 : 4)) * JX_BEAM_WPB; \
         auto kern = beam_search_kernel<KIND, T, CPL, NR, QB>;                                           \
         if (sh > 48 * 1024) {                                                                           \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh); \
