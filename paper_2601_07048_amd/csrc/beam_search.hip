@@ -58,7 +58,7 @@ beam_search_kernel(BeamArgs a) {
 
     const int H = a.hash_slots;
     const int tag_bits = a.tag_bits;  // > 0: 16-bit entries (slot and tag together name the id exactly)
-    const uint32_t id_mask = tag_bits ? ((1u << (tag_bits + 31 - __builtin_clz((uint32_t)H))) - 1u) : 0u;
+    const uint32_t id_mask = tag_bits ? ((1u << (tag_bits + 30 - __builtin_clz((uint32_t)H))) - 1u) : 0u;  // H / 2 sets
     const size_t per_wave = (size_t)FCAP * 8 + 64 * 8 + 64 * 4 + (size_t)H * (tag_bits ? 2 : 4);
     unsigned char* my = smem + per_wave * wave;
     uint64_t* fr = reinterpret_cast<uint64_t*>(my);
@@ -66,7 +66,6 @@ beam_search_kernel(BeamArgs a) {
     uint32_t* cand_id = reinterpret_cast<uint32_t*>(cand_key + 64);
     uint32_t* tab = cand_id + 64;
 
-    uint16_t* tab16 = reinterpret_cast<uint16_t*>(tab);
     for (int i = lane; i < (tag_bits ? H / 2 : H); i += 64) tab[i] = JX_NONE_ID;
     for (int i = lane; i < FCAP; i += 64) fr[i] = JX_EMPTY_KEY;
 
@@ -89,7 +88,7 @@ beam_search_kernel(BeamArgs a) {
         cand_id[0] = a.entry;
         if (tag_bits) {
             const uint32_t h = (a.entry * 0x9E3779B1u) & id_mask;
-            tab16[h >> tag_bits] = (uint16_t)(h & ((1u << tag_bits) - 1u));
+            tab[h >> tag_bits] = 0xFFFF0000u | (h & ((1u << tag_bits) - 1u));
         } else {
             tab[__umulhi(a.entry * 0x9E3779B1u, (uint32_t)H)] = a.entry;
         }
@@ -169,12 +168,14 @@ beam_search_kernel(BeamArgs a) {
             // ---- 3. visited filter
             if (v != JX_NONE_ID) {
                 if (tag_bits) {
-                    // ids below 2^b, b = log2(H) + tag_bits: multiplying by an odd constant permutes them, so the
-                    // slot (high bits) and the tag (low bits) of the product identify the id
+                    // ids below 2^b, b = log2(sets) + tag_bits: multiplying by an odd constant permutes them, so the
+                    // set (high bits) and the tag (low bits) of the product identify the id.  Two tags per set in one
+                    // 32-bit word, most recent first: one LDS read finds both, one write installs the new one
                     const uint32_t h = (v * 0x9E3779B1u) & id_mask;
-                    const uint16_t tag = (uint16_t)(h & ((1u << tag_bits) - 1u));
-                    is_new = tab16[h >> tag_bits] != tag;
-                    if (is_new) tab16[h >> tag_bits] = tag;
+                    const uint32_t tag = h & ((1u << tag_bits) - 1u);
+                    const uint32_t w = tab[h >> tag_bits];
+                    is_new = (w & 0xFFFFu) != tag && (w >> 16) != tag;
+                    if (is_new) tab[h >> tag_bits] = (w << 16) | tag;
                 } else {
                     uint32_t h = __umulhi(v * 0x9E3779B1u, (uint32_t)H);
                     is_new = tab[h] != v;

@@ -193,7 +193,7 @@ void visited_table_for(int L, int64_t n, int* slots, int* tag_bits) {
     *tag_bits = 0;
     if (mode16 && (h & (h - 1)) == 0) {
         int h16 = forced ? h : 2 * h, lg = 0;
-        while ((1 << lg) < h16) lg++;
+        while ((2 << lg) < h16) lg++;  // log2 of the number of sets (two entries each)
         int tb = id_bits - lg;
         if (tb < 1) tb = 1;
         if (tb <= 15) {

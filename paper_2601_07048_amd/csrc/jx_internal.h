@@ -31,8 +31,9 @@ struct BeamArgs {
     int L;
     uint32_t entry;
     int hash_slots;        // visited-table size (any value >= 64; slot = high word of hash * size)
-    int tag_bits;          // 0: 32-bit entries hold the id.  > 0: hash_slots is a power of two, every id is below
-                           // hash_slots << tag_bits, and 16-bit entries hold the low tag_bits of the permuted id (<= 15)
+    int tag_bits;          // 0: 32-bit entries hold the id.  > 0: hash_slots is a power of two, the table has hash_slots / 2
+                           // sets of two 16-bit entries, every id is below (hash_slots / 2) << tag_bits, and an entry holds
+                           // the low tag_bits (<= 15) of the permuted id
     uint32_t* out_ids;     // [nq][out_k]
     float* out_dist;       // [nq][out_k]
     int out_k;
