@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of one timed launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command
 # (profiles/beam_search_u8_N1M_L96.md); reported only when the run has the same shape.
-MEASURED_TRAFFIC = {(2, 1_000_000, 10_000, 96): 3.683e9 + 8.31e6}
+MEASURED_TRAFFIC = {(2, 1_000_000, 10_000, 96): 2.737e9 + 7.07e6}
 
 SPEC = {
     2: dict(d=128, u8=True, bits=0, sweep=[16, 24, 32, 48, 64, 96, 128, 256], kernel="beam_search_kernel<u8>",
