@@ -39,6 +39,11 @@ SPEC = {
     4: dict(d=1536, u8=False, bits=1, sweep=[64, 96, 128, 192, 256, 384, 512], kernel="beam_search_kernel<1-bit RaBitQ>",
             text="d=1536 float32 unit-norm 512-component mixture, 1-bit RaBitQ codes (B_q=4), exact fp32 re-rank of 40, k=10"),
 }
+SPEC[6] = dict(d=96, u8=False, bits=0, sweep=[16, 24, 32, 48, 64, 96, 128, 256], kernel="beam_search_kernel<f32>",
+               text="d=96 float32 unit-norm 256-component anisotropic mixture (Deep-like), search k=10 exact fp32 L2")
+SPEC[7] = dict(d=200, u8=False, bits=0, sweep=[16, 24, 32, 48, 64, 96, 128, 256], kernel="beam_search_kernel<f32>", mips=True,
+               text="d=200 float32 embeddings of varying norm (Text2Image-like), inner-product search through one extra "
+                    "dimension (204 stored), k=10 exact fp32 L2 on the augmented vectors")
 SPEC[5] = dict(SPEC[2], sweep=[128], text="streaming: batches of 100,000 inserts, a 10,000-query batch at L=128 every 1M; " + SPEC[2]["text"])
 
 
@@ -51,7 +56,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5])
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7])
     ap.add_argument("--n", type=int, default=1_000_000)
     ap.add_argument("--nq", type=int, default=10_000)
     ap.add_argument("--recall", type=float, default=0.95)
@@ -97,6 +102,15 @@ def main():
     for s0 in range(0, n, step):
         m = min(step, n - s0)
         dx[s0:s0 + m] = torch.from_numpy(datagen.base(gen_wl, m, start=s0)).cuda().to(tdt)
+    if sp.get("mips"):
+        # inner-product data: one extra coordinate (padded to a multiple of 4) makes it an L2 problem
+        assert not f16, "--f16 is not offered for the inner-product workload"
+        norms = jx.mips_augment(dx, want_norms=True)
+        big_m = float(norms.max()) * (1 + 1e-6)
+        d = (d + 1 + 3) // 4 * 4
+        dx = jx.mips_augment(dx, big_m, dim_out=d)
+        dq = jx.mips_augment(dq, big_m, is_query=True, dim_out=d)
+        q = dq.cpu().numpy()
     if f16:
         dq = dq.half()
         q = q.astype(np.float16)
@@ -208,7 +222,8 @@ def main():
 
     # What this GPU delivers for dependency-free gathers of records of the kernel's size class from a table of the
     # index's footprint: the practical ceiling for the gather part of beamSearch (context for the 8 TB/s peak).
-    rec_bytes = d if not rabitq else ((d * sp["bits"] // 8 + 15) // 16 + 1) * 16
+    esize = 1 if sp["u8"] else (2 if f16 else 4)
+    rec_bytes = d * esize if not rabitq else ((d * sp["bits"] // 8 + 15) // 16 + 1) * 16
     rec_class = min((64, 128, 256, 512), key=lambda c: abs(c - rec_bytes))
     tab = torch.randint(0, 255, (n * rec_class,), dtype=torch.uint8, device="cuda")
     gid = torch.randint(0, n, ((2 << 30) // rec_class,), dtype=torch.int32, device="cuda")
@@ -223,7 +238,7 @@ def main():
     del tab, gid
 
     # algorithmic bytes of one beamSearch launch: adjacency rows + gathered records + query records in + results out
-    qrec = d if not rabitq else (16 + (2 if sp["bits"] == 4 else args.query_bits) * ((d * sp["bits"] // 8 + 15) // 16) * 16)
+    qrec = d * esize if not rabitq else (16 + (2 if sp["bits"] == 4 else args.query_bits) * ((d * sp["bits"] // 8 + 15) // 16) * 16)
     out_k = rerank if rerank else k
     alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * qrec + nq * out_k * 8
     achieved = alg_bytes / (beam_ms * 1e-3) / 1e9
@@ -326,7 +341,7 @@ def main():
         "metric": "queries/sec at recall@10=0.95 (10k-query batch)", "value": round(qps, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8" if sp["u8"] else ("u4+f32" if sp["bits"] == 4 else "u1+f32"), "data": "synthetic",
+        "dtype": "u8" if sp["u8"] else ({4: "u4+f32", 1: "u1+f32", 0: "f16" if f16 else "f32"}[sp["bits"]]), "data": "synthetic",
         "config": cfg, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

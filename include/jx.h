@@ -218,6 +218,20 @@ int jx_consolidate(jx_index* idx, void* stream);
 int jx_compact(jx_index* idx, uint32_t* d_old_to_new, void* stream);
 int jx_deleted_count(jx_index* idx, int64_t* n_deleted, void* stream);
 
+/* Maximum-inner-product data as squared-L2 data (Sec. 6.3, the Text2Image
+ * set: one extra dimension restores a metric space for graph construction).
+ * For n float32 rows d_in [n][dim]:
+ *   d_norms [n] (may be NULL) receives |x| (accumulated in double);
+ *   d_out [n][dim_out] (may be NULL; dim_out >= dim + 1) receives the row,
+ *   then sqrt(max(max_norm^2 - |x|^2, 0)) for base rows (is_query = 0) or 0
+ *   for query rows (is_query != 0), then zeros up to dim_out (choose dim_out
+ *   as the next multiple of 4 for a JX_F32 index).
+ * With max_norm >= every base norm, |x' - q'|^2 = max_norm^2 + |q|^2 - 2<x,q>,
+ * so nearest neighbours in the augmented space are the largest inner
+ * products.  Both buffers may be requested in one call. */
+int jx_mips_augment(const float* d_in, int64_t n, int32_t dim, float max_norm, int32_t is_query, float* d_out,
+                    int32_t dim_out, float* d_norms, void* stream);
+
 /* Calibration aid for the roofline of beamSearch (Sec. 6.6 prices the kernel
  * against memory bandwidth): reads the n_ids records d_ids[i] (all < n_rec;
  * not checked on the device -- the caller guarantees it) of a table of

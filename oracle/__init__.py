@@ -107,6 +107,19 @@ def bruteforce(base, queries, k, nthreads=None):
     return ids, dist
 
 
+def mips_augment(x, max_norm, is_query=False, dim_out=None):
+    """Inner-product search as L2 search (Sec. 6.3): append sqrt(M^2 - |x|^2) to base rows, 0 to query rows,
+    then zero padding up to dim_out.  Everything in float64, rounded to float32 at the end."""
+    x = np.asarray(x, dtype=np.float64)
+    n, d = x.shape
+    dim_out = dim_out or d + 1
+    out = np.zeros((n, dim_out), np.float64)
+    out[:, :d] = x
+    if not is_query:
+        out[:, d] = np.sqrt(np.maximum(float(max_norm) ** 2 - (x * x).sum(axis=1), 0.0))
+    return out.astype(np.float32)
+
+
 # ---------------------------------------------------------------- beamSearch
 def beam_search(adj, base, query, L, start, filter=FILTER_EXACT, V_cap=0):
     """One query on a caller-supplied graph.  Returns dict(F_ids, F_dist, nF,

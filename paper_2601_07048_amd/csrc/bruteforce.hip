@@ -261,6 +261,41 @@ hipError_t launch_row_degrees(const uint32_t* adj, long long n, int R, uint32_t*
     return hipGetLastError();
 }
 
+// Maximum-inner-product search as L2 search (Sec. 6.3, Text2Image): one extra coordinate sqrt(M^2 - |x|^2) for base
+// vectors (M >= every |x|), 0 for queries; then |x' - q'|^2 = M^2 + |q|^2 - 2<x,q>.  One wavefront per row, squared
+// norm accumulated in double; dim_out >= dim + 1, the rest is zero padding.
+__global__ void __launch_bounds__(256) mips_augment_kernel(const float* in, long long n, int dim, float max_norm, int is_query,
+                                                          float* out, int dim_out, float* norm_out) {
+    const long long i = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= n) return;
+    const int lane = threadIdx.x & 63;
+    const float* x = in + (size_t)i * dim;
+    float* y = out ? out + (size_t)i * dim_out : nullptr;
+    double s = 0.0;
+    for (int j = lane; j < dim; j += 64) {
+        const float v = x[j];
+        s += (double)v * (double)v;
+        if (y) y[j] = v;
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) s += __shfl_xor(s, m, 64);
+    if (norm_out && lane == 0) norm_out[i] = (float)sqrt(s);
+    if (!y) return;
+    if (lane == 0) {
+        const double rest = (double)max_norm * (double)max_norm - s;
+        y[dim] = is_query ? 0.f : (float)sqrt(rest > 0.0 ? rest : 0.0);
+    }
+    for (int j = dim + 1 + lane; j < dim_out; j += 64) y[j] = 0.f;
+}
+
+hipError_t launch_mips_augment(const float* in, long long n, int dim, float max_norm, int is_query, float* out, int dim_out,
+                               float* norm_out, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(mips_augment_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, in, n, dim, max_norm, is_query, out,
+                       dim_out, norm_out);
+    return hipGetLastError();
+}
+
 // Calibration: independent gathers of whole records in a given id order, T = rec_bytes / 16 lanes per record,
 // eight 16-byte loads in flight per lane; nothing depends on a loaded value except the final checksum.
 template <int T>

@@ -940,6 +940,18 @@ int jx_compact(jx_index* idx, uint32_t* d_old_to_new, void* stream) {
     return JX_OK;
 }
 
+int jx_mips_augment(const float* d_in, int64_t n, int32_t dim, float max_norm, int32_t is_query, float* d_out,
+                    int32_t dim_out, float* d_norms, void* stream) {
+    if (n < 0) return fail(JX_EINVAL, "n < 0");
+    if (n == 0) return JX_OK;
+    if (!d_in || (!d_out && !d_norms)) return fail(JX_EINVAL, "NULL argument");
+    if (dim < 1) return fail(JX_EINVAL, "dim must be positive");
+    if (d_out && dim_out < dim + 1) return fail(JX_EINVAL, "dim_out must be at least dim + 1");
+    if (d_out && !(max_norm >= 0.0f)) return fail(JX_EINVAL, "max_norm must be non-negative");
+    JX_HIP(jx::launch_mips_augment(d_in, n, dim, max_norm, is_query, d_out, dim_out, d_norms, as_stream(stream)));
+    return JX_OK;
+}
+
 int jx_probe_gather(const void* d_table, int64_t n_rec, int32_t rec_bytes, const uint32_t* d_ids, int64_t n_ids,
                     int32_t blocks, uint32_t* d_sink, void* stream) {
     if (!d_table || !d_ids || !d_sink) return fail(JX_EINVAL, "NULL argument");

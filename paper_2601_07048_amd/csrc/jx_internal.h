@@ -167,6 +167,8 @@ hipError_t launch_bruteforce(const BfArgs& a, hipStream_t st);
 
 // ---- small utilities ----------------------------------------------------------
 hipError_t launch_fill_u32(uint32_t* p, long long n, uint32_t v, hipStream_t st);
+hipError_t launch_mips_augment(const float* in, long long n, int dim, float max_norm, int is_query, float* out, int dim_out,
+                               float* norm_out, hipStream_t st);
 hipError_t launch_gather_probe(const uint8_t* table, int rec_bytes, const uint32_t* ids, long long n_ids, int blocks,
                                uint32_t* sink, hipStream_t st);
 hipError_t launch_row_degrees(const uint32_t* adj, long long n, int R, uint32_t* deg, hipStream_t st);

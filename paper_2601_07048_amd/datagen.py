@@ -33,6 +33,10 @@ _SPEC = {
     2: dict(d=128, dtype=np.uint8, comps=256, kind="u8", centre_mean=64.0, centre_std=24.0, sigma=18.0, decay=1.25),
     3: dict(d=960, dtype=np.float32, comps=128, kind="aniso", centre_std=1.0, sigma=0.3, decay=1.0, normalise=False),
     4: dict(d=1536, dtype=np.float32, comps=512, kind="aniso", centre_std=0.25, sigma=0.3, decay=1.0, normalise=True),
+    # 6: unit-norm 96-d descriptors with a decaying spectrum (Deep-like); 7: 200-d embeddings of varying norm,
+    # searched by inner product (Text2Image-like)
+    6: dict(d=96, dtype=np.float32, comps=256, kind="aniso", centre_std=0.25, sigma=0.3, decay=1.0, normalise=True),
+    7: dict(d=200, dtype=np.float32, comps=256, kind="aniso", centre_std=0.5, sigma=0.3, decay=1.0, normalise=False),
 }
 _SPEC[5] = _SPEC[2]
 

@@ -24,7 +24,7 @@ MAX_L, MAX_R, MAX_BF_K = 512, 256, 128
 EXPORTS = [
     "jx_arena_bytes", "jx_create", "jx_destroy", "jx_insert", "jx_quantize", "jx_search", "jx_beam_frontier",
     "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_import_codes", "jx_rotate",
-    "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_compact", "jx_deleted_count", "jx_probe_gather", "jx_strerror", "jx_last_error",
+    "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_compact", "jx_deleted_count", "jx_probe_gather", "jx_mips_augment", "jx_strerror", "jx_last_error",
 ]
 
 
@@ -244,6 +244,20 @@ class Index:
         with torch.cuda.device(self.device):
             _check(_lib.jx_deleted_count(self._h, C.byref(n), _stream()))
         return n.value
+
+
+def mips_augment(x: torch.Tensor, max_norm: float = 0.0, is_query: bool = False, dim_out: int = 0, want_norms: bool = False):
+    """jx_mips_augment.  Returns the augmented rows (if dim_out > 0) and / or the row norms."""
+    assert x.dtype == torch.float32 and x.is_contiguous()
+    n, dim = x.shape
+    out = torch.empty((n, dim_out), dtype=torch.float32, device=x.device) if dim_out else None
+    norms = torch.empty(n, dtype=torch.float32, device=x.device) if want_norms else None
+    with torch.cuda.device(x.device):
+        _check(_lib.jx_mips_augment(_ptr(x), C.c_int64(n), C.c_int32(dim), C.c_float(max_norm), C.c_int32(int(is_query)),
+                                    _ptr(out), C.c_int32(dim_out), _ptr(norms), _stream()))
+    if out is not None and norms is not None:
+        return out, norms
+    return out if out is not None else norms
 
 
 def probe_gather(table: torch.Tensor, rec_bytes: int, ids: torch.Tensor, blocks: int = 4096):

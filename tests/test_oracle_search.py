@@ -202,3 +202,22 @@ def test_recall_definition():
     t = np.array([[1, 2, 3, 4]], np.uint32)
     f = np.array([[4, 9, 1, 7]], np.uint32)
     assert oracle.recall_at_k(f, t) == 0.5
+
+
+def test_mips_augment_is_inner_product_search():
+    """Sec. 6.3: with one extra coordinate the L2 order of the augmented vectors is the inner-product order of the
+    originals, and the distance has the closed form M^2 + |q|^2 - 2 <x, q>."""
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((400, 20)) * rng.uniform(0.2, 3.0, (400, 1))).astype(np.float32)
+    q = rng.standard_normal((30, 20)).astype(np.float32)
+    M = float(np.linalg.norm(x.astype(np.float64), axis=1).max())
+    xa = oracle.mips_augment(x, M, dim_out=24)
+    qa = oracle.mips_augment(q, M, is_query=True, dim_out=24)
+    assert xa.shape == (400, 24) and (xa[:, 21:] == 0).all() and (qa[:, 20:] == 0).all()
+    assert np.array_equal(xa[:, :20], x) and xa[:, 20].min() >= 0 and np.isclose(xa[:, 20].min(), 0, atol=2e-3)
+    ip = x.astype(np.float64) @ q.astype(np.float64).T
+    ids, dist = oracle.bruteforce(xa, qa, 10)
+    want = np.argsort(-ip, axis=0, kind="stable")[:10].T
+    assert np.array_equal(ids, want)
+    closed = M * M + (q.astype(np.float64) ** 2).sum(axis=1)[:, None] - 2 * np.take_along_axis(ip.T, want, axis=1)
+    assert np.allclose(dist, closed, rtol=1e-5)
