@@ -44,6 +44,8 @@ SPEC[6] = dict(d=96, u8=False, bits=0, sweep=[16, 24, 32, 48, 64, 96, 128, 256],
 SPEC[7] = dict(d=200, u8=False, bits=0, sweep=[16, 24, 32, 48, 64, 96, 128, 256], kernel="beam_search_kernel<f32>", mips=True,
                text="d=200 float32 embeddings of varying norm (Text2Image-like), inner-product search through one extra "
                     "dimension (204 stored), k=10 exact fp32 L2 on the augmented vectors")
+SPEC[8] = dict(d=128, u8=True, bits=4, sweep=[48, 64, 96, 128, 192, 256], kernel="beam_search_kernel<4-bit RaBitQ>",
+               text="workload 2's uint8 data searched on 4-bit RaBitQ codes (B_q=8) with exact re-rank of 40, k=10")
 SPEC[5] = dict(SPEC[2], sweep=[128], text="streaming: batches of 100,000 inserts, a 10,000-query batch at L=128 every 1M; " + SPEC[2]["text"])
 
 
@@ -56,7 +58,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7])
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7, 8])
     ap.add_argument("--n", type=int, default=1_000_000)
     ap.add_argument("--nq", type=int, default=10_000)
     ap.add_argument("--recall", type=float, default=0.95)
@@ -89,7 +91,7 @@ def main():
         args.query_bits = 4 if sp["bits"] == 1 else 8
     mode = jx.RABITQ if rabitq else jx.EXACT
     rerank = 4 * k if rabitq else 0
-    gen_wl = 2 if wl == 5 else wl
+    gen_wl = 2 if wl in (5, 8) else wl
 
     t0 = time.time()
     q = datagen.queries(gen_wl, nq)
@@ -163,7 +165,7 @@ def main():
 
     t_quant = None
     if rabitq:
-        P = torch.from_numpy(datagen.rotation(wl)).cuda()
+        P = torch.from_numpy(datagen.rotation(gen_wl)).cuda()
         torch.cuda.synchronize()
         t0 = time.time()
         g.quantize(sp["bits"], P, None, query_bits=args.query_bits)
@@ -259,7 +261,7 @@ def main():
         oix.set_graph(dx.cpu().numpy(), adj.cpu().numpy().view(np.uint32), g.size()[1])
         if rabitq:
             codes, meta, cen = [t.cpu().numpy() for t in g.export_codes()]
-            oix.set_codes(sp["bits"], datagen.rotation(wl), cen, codes, meta, qbits=args.query_bits)
+            oix.set_codes(sp["bits"], datagen.rotation(gen_wl), cen, codes, meta, qbits=args.query_bits)
         m = min(args.cpu_queries, nq)
         oix.search(q[:32], k, L_star, mode=1 if rabitq else 0, rerank=rerank)  # touch
         t0 = time.perf_counter()
@@ -341,7 +343,7 @@ def main():
         "metric": "queries/sec at recall@10=0.95 (10k-query batch)", "value": round(qps, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8" if sp["u8"] else ({4: "u4+f32", 1: "u1+f32", 0: "f16" if f16 else "f32"}[sp["bits"]]), "data": "synthetic",
+        "dtype": ("u4+u8" if rabitq else "u8") if sp["u8"] else ({4: "u4+f32", 1: "u1+f32", 0: "f16" if f16 else "f32"}[sp["bits"]]), "data": "synthetic",
         "config": cfg, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

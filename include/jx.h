@@ -131,7 +131,8 @@ int jx_destroy(jx_index* idx);
 int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream);
 
 /*
- * RaBitQ quantisation of the current base set (Sec. 5.1), float32 or binary16 data.
+ * RaBitQ quantisation of the current base set (Sec. 5.1); any storage type (uint8 and
+ * binary16 values enter the rotation as float32, exactly).
  * bits: 1 or 4 (must equal params.quant_bits).  d_rotation: orthogonal matrix P,
  * float32 [dim][dim] row-major, applied as r = P (v - c).  d_centroid: c
  * (float32 [dim]) or NULL = mean of the current base set.  query_bits: width

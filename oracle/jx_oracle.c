@@ -1115,7 +1115,6 @@ void orc_rabitq_unpack(const uint8_t *code, int bits, int d, uint8_t *out) {
  */
 int orc_index_quantize(orc_index *x, int bits, int qbits, int rule, const float *P, const float *centroid,
                        int nthreads) {
-    if (x->dtype == ORC_U8) return -1;
     const int d = x->d;
     free(x->P);
     free(x->c);
@@ -1142,9 +1141,9 @@ int orc_index_quantize(orc_index *x, int bits, int qbits, int rule, const float 
     float *r = (float *)malloc(sizeof(float) * (size_t)x->n * d + 16);
     const float *src = (const float *)x->base;
     float *tmp = NULL;
-    if (x->dtype == ORC_F16) { /* binary16 -> float32 is exact */
+    if (x->dtype != ORC_F32) { /* binary16 -> float32 and uint8 -> float32 are exact */
         tmp = (float *)malloc(sizeof(float) * (size_t)x->n * d + 16);
-        for (size_t i = 0; i < (size_t)x->n * d; i++) tmp[i] = (float)half_to_double(((const uint16_t *)x->base)[i]);
+        for (size_t i = 0; i < (size_t)x->n * d; i++) tmp[i] = (float)elem(x->dtype, x->base, i);
         src = tmp;
     }
     orc_rabitq_rotate(src, x->n, d, x->P, x->c, r, NULL, nthreads);
@@ -1223,9 +1222,9 @@ int orc_index_search(const orc_index *x, const void *queries, int64_t nq, int k,
             ctx.query = q;
             if (mode == 1) {
                 float m4[4];
-                if (x->dtype == ORC_F16) {
+                if (x->dtype != ORC_F32) {
                     float *qf = (float *)malloc(sizeof(float) * (size_t)d);
-                    for (int j = 0; j < d; j++) qf[j] = (float)half_to_double(((const uint16_t *)q)[j]);
+                    for (int j = 0; j < d; j++) qf[j] = (float)elem(x->dtype, q, (size_t)j);
                     orc_rabitq_rotate(qf, 1, d, x->P, x->c, qr, NULL, 1);
                     free(qf);
                 } else {

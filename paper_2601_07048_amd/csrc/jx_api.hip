@@ -59,7 +59,6 @@ int check_params(const jx_params* p) {
     if ((int64_t)p->max_batch * p->R >= 0x7FFFFFFFLL) return fail(JX_EINVAL, "max_batch * R must stay below 2^31");
     if (p->quant_bits != 0 && p->quant_bits != 1 && p->quant_bits != 4)
         return fail(JX_EINVAL, "quant_bits must be 0, 1 or 4");
-    if (p->quant_bits && p->dtype == JX_U8) return fail(JX_EINVAL, "RaBitQ needs float data (float32 or binary16)");
     if (p->quant_bits && p->dim % 32) return fail(JX_EINVAL, "RaBitQ needs dim to be a multiple of 32");
     if (!(p->batch_growth >= 0.0f) || p->batch_growth > 1.0f) return fail(JX_EINVAL, "batch_growth must be in [0, 1]");
     return JX_OK;
@@ -394,7 +393,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
             const int64_t m = nq - q0 < p.max_batch ? nq - q0 : p.max_batch;
             const uint8_t* qs = (const uint8_t*)d_queries + (size_t)q0 * idx->vec_bytes;
             tm.begin();
-            JX_HIP(jx::launch_rotate(qs, p.dtype == JX_F16, m, p.dim, idx->d_P, idx->d_centroid, (float*)(W + qw.rot), st));
+            JX_HIP(jx::launch_rotate(qs, p.dtype, m, p.dim, idx->d_P, idx->d_centroid, (float*)(W + qw.rot), st));
             tm.end(0);
             jx::QueryPrepArgs qp;
             memset(&qp, 0, sizeof qp);
@@ -652,7 +651,7 @@ static int encode_range(jx_index* idx, int64_t first, int64_t count, hipStream_t
     for (int64_t s0 = 0; s0 < count; s0 += slice) {
         const int64_t m = count - s0 < slice ? count - s0 : slice;
         const uint8_t* src = idx->d_vecs + (size_t)(first + s0) * idx->vec_bytes;
-        JX_HIP(jx::launch_rotate(src, p.dtype == JX_F16, m, p.dim, idx->d_P, idx->d_centroid, rot, st));
+        JX_HIP(jx::launch_rotate(src, p.dtype, m, p.dim, idx->d_P, idx->d_centroid, rot, st));
         jx::EncodeArgs e;
         memset(&e, 0, sizeof e);
         e.rot = rot;
@@ -735,7 +734,7 @@ int jx_rotate(jx_index* idx, const float* d_in, int64_t n, float* d_out, void* s
     if (n < 0) return fail(JX_EINVAL, "n < 0");
     if (n == 0) return JX_OK;
     if (!d_in || !d_out) return fail(JX_EINVAL, "NULL argument");
-    JX_HIP(jx::launch_rotate(d_in, false, n, idx->p.dim, idx->d_P, idx->d_centroid, d_out, as_stream(stream)));
+    JX_HIP(jx::launch_rotate(d_in, JX_F32, n, idx->p.dim, idx->d_P, idx->d_centroid, d_out, as_stream(stream)));
     return JX_OK;
 }
 

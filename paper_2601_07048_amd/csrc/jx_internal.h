@@ -108,7 +108,7 @@ struct RerankArgs {
     unsigned long long* stats;  // [2] += number of vectors read
 };
 
-hipError_t launch_rotate(const void* in, bool in_f16, long long n, int d, const float* P, const float* c, float* out,
+hipError_t launch_rotate(const void* in, int in_dtype, long long n, int d, const float* P, const float* c, float* out,
                          hipStream_t st);
 hipError_t launch_encode(const EncodeArgs& a, hipStream_t st);
 hipError_t launch_unpack_records(const uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,

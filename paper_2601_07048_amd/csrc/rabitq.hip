@@ -21,7 +21,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define GK 32
 #define GLD 36  // padded LDS row (floats)
 
-template <bool IN_F16>
+// IN: storage type of the input rows (JX_F32, JX_F16, JX_U8); all three convert to float32 exactly
+template <int IN>
 __global__ void __launch_bounds__(256) rotate_gemm_kernel(const void* __restrict__ in_v, long long n, int d,
                                                           const float* __restrict__ P, const float* __restrict__ c,
                                                           float* __restrict__ out) {
@@ -48,9 +49,12 @@ __global__ void __launch_bounds__(256) rotate_gemm_kernel(const void* __restrict
             if (k0 + c4 < d) {
                 if (m0 + row < n) {
                     float4 v;
-                    if (IN_F16) {
+                    if (IN == JX_F16) {
                         const _Float16* hp = reinterpret_cast<const _Float16*>(in_v) + (size_t)(m0 + row) * d + k0 + c4;
                         v = make_float4((float)hp[0], (float)hp[1], (float)hp[2], (float)hp[3]);
+                    } else if (IN == JX_U8) {
+                        const uint8_t* bp = reinterpret_cast<const uint8_t*>(in_v) + (size_t)(m0 + row) * d + k0 + c4;
+                        v = make_float4((float)bp[0], (float)bp[1], (float)bp[2], (float)bp[3]);
                     } else {
                         v = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(in_v) + (size_t)(m0 + row) * d + k0 + c4);
                     }
@@ -95,14 +99,16 @@ __global__ void __launch_bounds__(256) rotate_gemm_kernel(const void* __restrict
             }
 }
 
-hipError_t launch_rotate(const void* in, bool in_f16, long long n, int d, const float* P, const float* c, float* out,
+hipError_t launch_rotate(const void* in, int in_dtype, long long n, int d, const float* P, const float* c, float* out,
                          hipStream_t st) {
     if (n <= 0) return hipSuccess;
     dim3 grid((unsigned)((d + GT - 1) / GT), (unsigned)((n + GT - 1) / GT));
-    if (in_f16)
-        hipLaunchKernelGGL(rotate_gemm_kernel<true>, grid, dim3(256), 0, st, in, n, d, P, c, out);
+    if (in_dtype == JX_F16)
+        hipLaunchKernelGGL(rotate_gemm_kernel<JX_F16>, grid, dim3(256), 0, st, in, n, d, P, c, out);
+    else if (in_dtype == JX_U8)
+        hipLaunchKernelGGL(rotate_gemm_kernel<JX_U8>, grid, dim3(256), 0, st, in, n, d, P, c, out);
     else
-        hipLaunchKernelGGL(rotate_gemm_kernel<false>, grid, dim3(256), 0, st, in, n, d, P, c, out);
+        hipLaunchKernelGGL(rotate_gemm_kernel<JX_F32>, grid, dim3(256), 0, st, in, n, d, P, c, out);
     return hipGetLastError();
 }
 

@@ -7,7 +7,7 @@ import torch
 
 import oracle
 from paper_2601_07048_amd import datagen
-from gpu_common import dev, u32, oracle_index, gpu_index_from_oracle
+from gpu_common import dev, u32, oracle_index, gpu_index_from_oracle, random_data
 
 pytestmark = pytest.mark.gpu
 
@@ -247,4 +247,42 @@ def test_rabitq_argument_errors(jx):
     with pytest.raises(jx.JxError):
         g.search(dev(x[:4]), 5, 8, mode=jx.RABITQ, rerank=3)  # rerank < k
     with pytest.raises(jx.JxError):
-        jx.Index(d, jx.U8, 8, 16, 1.2, capacity=n, quant_bits=4)  # RaBitQ needs float32 data
+        jx.Index(48, jx.U8, 8, 16, 1.2, capacity=n, quant_bits=4)  # RaBitQ needs dim % 32 == 0
+
+
+def test_rabitq_on_uint8_data(jx):
+    """4-bit codes of uint8 vectors (the 2x compression case of Sec. 5.1).  uint8 -> float32 is exact, so an index
+    on the same values held as float32 must give identical codes, and with injected oracle codes and an exact
+    rotation the estimated-distance frontier equals the oracle's bit for bit; re-rank distances are exact integers."""
+    n, d, R, L = 3000, 128, 32, 64
+    x = random_data(n, d, np.uint8, seed=17)
+    q = random_data(100, d, np.uint8, seed=18)
+    ix = oracle_index(x, R, L)
+    P = datagen.random_orthogonal(d, seed=4).astype(np.float32)
+    g = gpu_index_from_oracle(jx, x, ix, R, L, quant_bits=4)
+    g.quantize(4, dev(P))
+    gf = gpu_index_from_oracle(jx, x.astype(np.float32), ix, R, L, quant_bits=4)
+    gf.quantize(4, dev(P))
+    c8, m8, cen8 = [t.cpu().numpy() for t in g.export_codes()]
+    cf, mf, cenf = [t.cpu().numpy() for t in gf.export_codes()]
+    assert np.array_equal(c8, cf) and np.array_equal(m8, mf) and np.array_equal(cen8, cenf)
+    # end to end against the oracle (its rotation is in double: recall, not bits)
+    ix.quantize(4, P)
+    gt = oracle.bruteforce(x, q, 10)[0]
+    ids, dist = g.search(dev(q), 10, L, mode=jx.RABITQ, rerank=40)
+    want = ix.search(q, 10, L, mode=1, rerank=40)
+    r_g, r_o = oracle.recall_at_k(u32(ids), gt), oracle.recall_at_k(want["ids"], gt)
+    assert abs(r_g - r_o) <= 0.005 and r_g > 0.6
+    same = (u32(ids) == want["ids"]).all(axis=1)
+    assert same.mean() > 0.95
+    assert np.array_equal(dist.cpu().numpy().astype(np.float64)[same], want["dist"][same])  # exact integers
+    # injected codes + signed permutation + zero centroid: bit-exact frontier
+    Pp = _signed_permutation(d, 6)
+    zero = np.zeros(d, np.float32)
+    ix.quantize(4, Pp, centroid=zero)
+    oc, om, _ = ix.codes()
+    g.import_codes(4, dev(Pp), dev(zero), dev(oc), dev(om))
+    ref = ix.search(q, 1, 50, mode=1, want_frontier=True)
+    fi, fd = g.beam_frontier(dev(q), 50, mode=jx.RABITQ)
+    assert np.array_equal(u32(fi), ref["F_ids"])
+    assert np.array_equal(fd.cpu().numpy().astype(np.float64), ref["F_dist"])

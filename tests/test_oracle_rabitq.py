@@ -225,3 +225,28 @@ def test_quantized_search_and_rerank():
             keys = list(zip(rr["dist"][i].tolist(), rr["ids"][i].tolist()))
             assert keys == sorted(keys)
             assert rr["dist"][i, 0] == oracle.l2sq(q[i], x[rr["ids"][i, 0]])
+
+
+def test_rabitq_on_uint8_equals_the_same_values_as_float32():
+    """uint8 -> float32 is exact: an index on uint8 vectors must give the codes, the two floats and the search
+    results of an index on the same values stored as float32 (whose path is pinned above)."""
+    from paper_2601_07048_amd import datagen
+    n, d = 2000, 64
+    rng = np.random.default_rng(12)
+    x = rng.integers(0, 256, (n, d), dtype=np.uint8)
+    q = rng.integers(0, 256, (50, d), dtype=np.uint8)
+    a = oracle.Index(d, np.uint8, 16, 32, 1.2, n)
+    a.insert(x)
+    adj, _ = a.graph()
+    b = oracle.Index(d, np.float32, 16, 32, 1.2, n)
+    b.set_graph(x.astype(np.float32), adj, a.entry)
+    P = datagen.random_orthogonal(d, seed=2).astype(np.float32)
+    for bits in (1, 4):
+        a.quantize(bits, P)
+        b.quantize(bits, P)
+        ca, ma, cena = a.codes()
+        cb, mb, cenb = b.codes()
+        assert np.array_equal(ca, cb) and np.array_equal(ma, mb) and np.array_equal(cena, cenb)
+        ra = a.search(q, 5, 32, mode=1, rerank=20)
+        rb = b.search(q.astype(np.float32), 5, 32, mode=1, rerank=20)
+        assert np.array_equal(ra["ids"], rb["ids"]) and np.array_equal(ra["dist"], rb["dist"])
