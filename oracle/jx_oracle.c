@@ -141,22 +141,16 @@ typedef struct orc_dist_ctx {
     float q_lo, q_delta, q_add, q_sumq;
 } orc_dist_ctx;
 
+/* Code packing for m in {1, 2, 4, 8} bits: coordinate i occupies bits [i*m, (i+1)*m) of the little-endian bit
+ * string (m = 1: bit i%8 of byte i/8; m = 4: low nibble for even i, high nibble for odd i; m = 8: byte i). */
 static int code_get(const uint8_t *code, int bits, int i) {
-    /* bits==1: coordinate i is bit (i%8) of byte i/8.
-       bits==4: coordinate i is the low (i even) or high (i odd) nibble of byte i/2. */
-    if (bits == 1) return (code[i >> 3] >> (i & 7)) & 1;
-    return (i & 1) ? (code[i >> 1] >> 4) : (code[i >> 1] & 15);
+    const int per = 8 / bits; /* coordinates per byte */
+    return (code[i / per] >> ((i % per) * bits)) & ((1 << bits) - 1);
 }
 
 static void code_set(uint8_t *code, int bits, int i, int u) {
-    if (bits == 1) {
-        if (u) code[i >> 3] |= (uint8_t)(1u << (i & 7));
-    } else {
-        if (i & 1)
-            code[i >> 1] |= (uint8_t)(u << 4);
-        else
-            code[i >> 1] |= (uint8_t)u;
-    }
+    const int per = 8 / bits;
+    code[i / per] |= (uint8_t)(u << ((i % per) * bits));
 }
 
 /* Sec. 5.1, integer-query form of the estimator.  <u,q'> is approximated by

@@ -43,14 +43,15 @@ def test_rotate_matches_numpy():
     assert np.array_equal(r32, r64.astype(np.float32))
 
 
-@pytest.mark.parametrize("bits,rule", [(1, 0), (4, oracle.RULE_MAXCOS), (4, oracle.RULE_MAXABS)])
+@pytest.mark.parametrize("bits,rule", [(1, 0), (4, oracle.RULE_MAXCOS), (4, oracle.RULE_MAXABS), (2, oracle.RULE_MAXCOS),
+                                       (2, oracle.RULE_MAXABS), (8, oracle.RULE_MAXCOS), (8, oracle.RULE_MAXABS)])
 def test_on_grid_vector_estimate_is_exact(bits, rule):
     """If r lies exactly on a ray through a grid point the code is parallel to
     r, and est = ||r||^2 + ||q'||^2 - 2<r,q'> must hold exactly: this checks the
     signs and constants of all four metadata terms (c_b in particular)."""
     rng = np.random.default_rng(2)
-    d = 64
     half = 1 << (bits - 1)
+    d = max(64, 2 * half)
     lev = rng.integers(0, half, d)
     lev[:half] = np.arange(half)  # every level present
     sgn = rng.choice([-1.0, 1.0], d)
@@ -69,7 +70,7 @@ def test_on_grid_vector_estimate_is_exact(bits, rule):
 
 def test_zero_vector_is_degenerate_but_finite():
     r = np.zeros((1, 16), np.float32)
-    for bits in (1, 4):
+    for bits in (1, 2, 4, 8):
         codes, meta, _ = oracle.rabitq_encode(r, bits)
         assert meta[0].tolist() == [0.0, 0.0]
         u = oracle.rabitq_unpack(codes[0], bits, 16)
@@ -90,7 +91,8 @@ def _pairs(d, n, seed, bits, rule):
     return v, q, r32, q64, codes, meta, cos
 
 
-@pytest.mark.parametrize("bits,rule", [(1, 0), (4, oracle.RULE_MAXCOS), (4, oracle.RULE_MAXABS)])
+@pytest.mark.parametrize("bits,rule", [(1, 0), (4, oracle.RULE_MAXCOS), (4, oracle.RULE_MAXABS), (2, oracle.RULE_MAXCOS),
+                                       (8, oracle.RULE_MAXABS)])
 def test_estimator_unbiased_and_error_law(bits, rule):
     """est - true = -2 ||r|| tan(theta) ||q_perp|| Z with Z one coordinate of a
     uniform unit vector of R^(d-1) (mean 0, variance 1/(d-1)): the normalised
@@ -157,7 +159,7 @@ def test_sweep_is_optimal():
         assert abs(u @ o / np.linalg.norm(u) / np.linalg.norm(o) - cos_a[i]) < 1e-12
 
 
-@pytest.mark.parametrize("bits", [1, 4])
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
 @pytest.mark.parametrize("qbits", [4, 8])
 def test_integer_query_form(bits, qbits):
     """|<u,q'> - (delta <u,q_int> + lo sum u)| <= delta/2 * sum u, and the
