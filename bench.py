@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--L", type=int, default=0, help="force the beam width (0 = smallest with recall >= target)")
     ap.add_argument("--query-bits", type=int, default=0, help="B_q of the integer query (0 = 8 for 4-bit codes, 4 for 1-bit codes)")
     ap.add_argument("--cpu-queries", type=int, default=2000, help="sample size of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--bits", type=int, default=0, choices=[0, 1, 2, 4, 8],
+                    help="RaBitQ code width for the quantised workloads (0 = the workload's own: 4, 4, 1 for 3, 8, 4)")
     ap.add_argument("--f16", action="store_true", help="store the float workloads (3, 4) as binary16 (App. D of the paper)")
     ap.add_argument("--delete-frac", type=float, default=0.0,
                     help="after everything else: mark this fraction of the vertices deleted, consolidate, and report "
@@ -86,9 +88,12 @@ def main():
     sp = SPEC[wl]
     R, L_build, alpha, k, d = 64, 128, 1.2, 10, sp["d"]
     n, nq = args.n, args.nq
+    if args.bits and sp["bits"]:
+        sp = dict(sp, bits=args.bits, kernel=f"beam_search_kernel<{args.bits}-bit RaBitQ>",
+                  text=sp["text"].replace("4-bit", f"{args.bits}-bit").replace("1-bit", f"{args.bits}-bit"))
     rabitq = sp["bits"] > 0
     if not args.query_bits:
-        args.query_bits = 4 if sp["bits"] == 1 else 8
+        args.query_bits = 4 if sp["bits"] in (1, 2) else 8
     mode = jx.RABITQ if rabitq else jx.EXACT
     rerank = 4 * k if rabitq else 0
     gen_wl = 2 if wl in (5, 8) else wl
@@ -225,7 +230,9 @@ def main():
     # What this GPU delivers for dependency-free gathers of records of the kernel's size class from a table of the
     # index's footprint: the practical ceiling for the gather part of beamSearch (context for the 8 TB/s peak).
     esize = 1 if sp["u8"] else (2 if f16 else 4)
-    rec_bytes = d * esize if not rabitq else ((d * sp["bits"] // 8 + 15) // 16 + 1) * 16
+    fam, ncp = (1 if sp["bits"] <= 2 else 4), (2 if sp["bits"] in (2, 8) else 1)
+    code_chunks = ncp * ((d * fam // 8 + 15) // 16)      # 2- and 8-bit codes are two planes, each in whole chunks
+    rec_bytes = d * esize if not rabitq else (code_chunks + 1) * 16
     rec_class = min((64, 128, 256, 512), key=lambda c: abs(c - rec_bytes))
     tab = torch.randint(0, 255, (n * rec_class,), dtype=torch.uint8, device="cuda")
     gid = torch.randint(0, n, ((2 << 30) // rec_class,), dtype=torch.int32, device="cuda")
@@ -240,7 +247,7 @@ def main():
     del tab, gid
 
     # algorithmic bytes of one beamSearch launch: adjacency rows + gathered records + query records in + results out
-    qrec = d * esize if not rabitq else (16 + (2 if sp["bits"] == 4 else args.query_bits) * ((d * sp["bits"] // 8 + 15) // 16) * 16)
+    qrec = d * esize if not rabitq else (16 + (2 if fam == 4 else args.query_bits) * (code_chunks // ncp) * 16)
     out_k = rerank if rerank else k
     alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * qrec + nq * out_k * 8
     achieved = alg_bytes / (beam_ms * 1e-3) / 1e9
@@ -343,7 +350,7 @@ def main():
         "metric": "queries/sec at recall@10=0.95 (10k-query batch)", "value": round(qps, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("u4+u8" if rabitq else "u8") if sp["u8"] else ({4: "u4+f32", 1: "u1+f32", 0: "f16" if f16 else "f32"}[sp["bits"]]), "data": "synthetic",
+        "dtype": ("u4+u8" if rabitq else "u8") if sp["u8"] else ({0: "f16" if f16 else "f32"}.get(sp["bits"], f"u{sp['bits']}+f32")), "data": "synthetic",
         "config": cfg, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

@@ -51,7 +51,7 @@ extern "C" {
 /* rule that picks the m-bit code for m > 1 (Sec. 5.1 says only "simple scalar
  * quantization") */
 #define JX_RULE_MAXCOS 0 /* the grid point whose direction is closest to r ("extended" codes): exact sweep
-                           over the breakpoints of the grid scale; 4-bit codes, dim <= 1170 */
+                           over the breakpoints of the grid scale; 2- and 4-bit codes with dim * (2^(m-1) - 1) <= 8192 */
 #define JX_RULE_MAXABS 1 /* grid scale t = (2^(m-1) - 1/2) / max_i |r_i| */
 
 /* error codes */
@@ -79,7 +79,7 @@ typedef struct {
     int64_t max_batch; /* largest number of points linked by one internal batch
                           and largest number of queries processed at once
                           (larger query batches are processed in slices) */
-    int32_t quant_bits; /* 0: never quantised; 1 or 4: reserve room for RaBitQ codes */
+    int32_t quant_bits; /* 0: never quantised; 1, 2, 4 or 8: reserve room for RaBitQ codes of that width */
     float batch_growth; /* an internal insert batch holds at most max(1, floor(batch_growth * #linked))
                            points; 0 selects the default 0.25 */
 } jx_params;
@@ -133,14 +133,18 @@ int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream);
 /*
  * RaBitQ quantisation of the current base set (Sec. 5.1); any storage type (uint8 and
  * binary16 values enter the rotation as float32, exactly).
- * bits: 1 or 4 (must equal params.quant_bits).  d_rotation: orthogonal matrix P,
+ * bits: 1, 2, 4 or 8 (must equal params.quant_bits).  d_rotation: orthogonal matrix P,
  * float32 [dim][dim] row-major, applied as r = P (v - c).  d_centroid: c
  * (float32 [dim]) or NULL = mean of the current base set.  query_bits: width
  * B_q of the integer query (4 or 8).  rule: JX_RULE_MAXCOS or JX_RULE_MAXABS
  * (ignored for 1-bit codes).
- * Per vector the record is  dim*bits/8 code bytes, zero padding to a multiple
- * of 16, then data_add = ||r||^2 and data_rescale = -2||r||^2/<xbar,r> as two
- * floats, then padding to a multiple of 16 bytes.  The matrix, centroid and
+ * Per vector the arena holds the dim*bits/8 code bytes (2- and 8-bit codes
+ * split into a low and a high plane of 1-bit / 4-bit fields), zero padding to
+ * 16-byte chunks, then data_add = ||r||^2 and data_rescale = -2||r||^2/<xbar,r>
+ * as two floats and the code sum as uint32, the record padded to a multiple
+ * of 128 bytes.  jx_export_codes / jx_import_codes always speak the natural
+ * packing: coordinate i in bits [i*bits, (i+1)*bits) of the little-endian
+ * bit string.  The matrix, centroid and
  * parameters are copied into the arena and frozen; later inserts are encoded
  * with them.  dim must be a multiple of 32.
  */

@@ -32,7 +32,7 @@ inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 
 struct Layout {
     int64_t vecs, adj, codes, P, centroid, stats, deleted, work, work_bytes, total;
-    int vec_bytes, code_bytes, meta_chunk, code_stride;
+    int vec_bytes, code_bytes, meta_chunk, code_stride, plane_chunks, plane_shift;
 };
 
 int elem_bytes(int dtype) { return dtype == JX_U8 ? 1 : (dtype == JX_F16 ? 2 : 4); }
@@ -57,8 +57,8 @@ int check_params(const jx_params* p) {
     if (p->capacity < 1 || p->capacity > 0x7FFFFFFELL) return fail(JX_EINVAL, "capacity out of range");
     if (p->max_batch < 1) return fail(JX_EINVAL, "max_batch must be positive");
     if ((int64_t)p->max_batch * p->R >= 0x7FFFFFFFLL) return fail(JX_EINVAL, "max_batch * R must stay below 2^31");
-    if (p->quant_bits != 0 && p->quant_bits != 1 && p->quant_bits != 4)
-        return fail(JX_EINVAL, "quant_bits must be 0, 1 or 4");
+    if (p->quant_bits != 0 && p->quant_bits != 1 && p->quant_bits != 2 && p->quant_bits != 4 && p->quant_bits != 8)
+        return fail(JX_EINVAL, "quant_bits must be 0, 1, 2, 4 or 8");
     if (p->quant_bits && p->dim % 32) return fail(JX_EINVAL, "RaBitQ needs dim to be a multiple of 32");
     if (!(p->batch_growth >= 0.0f) || p->batch_growth > 1.0f) return fail(JX_EINVAL, "batch_growth must be in [0, 1]");
     return JX_OK;
@@ -96,11 +96,11 @@ struct QueryWork {
     int plane_stride, qrec_stride_max;
 };
 
-int64_t query_work(const jx_params* p, int64_t B, int meta_chunk, QueryWork* w) {
+int64_t query_work(const jx_params* p, int64_t B, int plane_chunks, QueryWork* w) {
     int64_t off = 0;
     auto take = [&](int64_t bytes) { int64_t o = off; off += align256(bytes); return o; };
-    w->plane_stride = meta_chunk * 16;
-    w->qrec_stride_max = 16 + (p->quant_bits == 4 ? 2 : 8) * w->plane_stride;
+    w->plane_stride = plane_chunks * 16;
+    w->qrec_stride_max = 16 + (p->quant_bits >= 4 ? 2 : 8) * w->plane_stride;
     if (!p->quant_bits) {
         w->rot = w->qrecs = w->fr_ids = w->fr_dist = 0;
         w->total = 0;
@@ -116,8 +116,14 @@ int64_t query_work(const jx_params* p, int64_t B, int meta_chunk, QueryWork* w) 
 
 void layout(const jx_params* p, Layout* L) {
     L->vec_bytes = p->dim * elem_bytes(p->dtype);
+    // 1- and 4-bit codes are one plane; 2- and 8-bit codes are stored as a low and a high plane of the 1-bit /
+    // 4-bit kind (u = lo + 2 hi, u = lo + 16 hi), each padded to whole 16-byte chunks
     L->code_bytes = p->quant_bits ? p->dim * p->quant_bits / 8 : 0;
-    L->meta_chunk = (L->code_bytes + 15) / 16;
+    const int fam = p->quant_bits <= 2 ? 1 : 4;
+    const int ncp = (p->quant_bits == 2 || p->quant_bits == 8) ? 2 : 1;
+    L->plane_chunks = p->quant_bits ? (p->dim * fam / 8 + 15) / 16 : 0;
+    L->plane_shift = ncp == 2 ? fam : 0;
+    L->meta_chunk = ncp * L->plane_chunks;
     // records start on 128-byte lines: a gather then touches ceil(record / 128) lines, the fewest any layout allows
     L->code_stride = p->quant_bits ? ((L->meta_chunk + 1) * 16 + 127) / 128 * 128 : 0;
     int64_t off = 0;
@@ -140,7 +146,7 @@ void layout(const jx_params* p, Layout* L) {
     InsertWork iw;
     int64_t ins = insert_work(p, B, &iw);
     QueryWork qw;
-    int64_t qry = query_work(p, B, L->meta_chunk, &qw);
+    int64_t qry = query_work(p, B, L->plane_chunks, &qw);
     int64_t qnt = align256((int64_t)512 * p->dim * 8) + align256((int64_t)p->dim * 4 * 1024);  // centroid + >= 1024 rotated rows
     if (p->quant_bits && qnt > qry) qry = qnt;
     int64_t w = ins > qry ? ins : qry;
@@ -256,6 +262,8 @@ int jx_create(const jx_params* p, void* d_arena, int64_t arena_bytes, void* stre
     x->work_bytes = L.work_bytes;
     x->code_bytes = L.code_bytes;
     x->meta_chunk = L.meta_chunk;
+    x->plane_chunks = L.plane_chunks;
+    x->plane_shift = L.plane_shift;
     x->code_stride = L.code_stride;
     hipError_t e = jx::launch_fill_u32(x->d_adj, (long long)p->capacity * p->R, JX_NONE, as_stream(stream));
     if (e == hipSuccess) e = jx::launch_fill_u32((uint32_t*)x->d_stats, 64, 0u, as_stream(stream));
@@ -385,9 +393,9 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         tm.end(2);
     } else {
         QueryWork qw;
-        query_work(&p, p.max_batch, idx->meta_chunk, &qw);
+        query_work(&p, p.max_batch, idx->plane_chunks, &qw);
         uint8_t* W = idx->d_work;
-        const int nplanes = idx->quantized == 4 ? 2 : idx->qbits;
+        const int nplanes = idx->quantized >= 4 ? 2 : idx->qbits;
         const int qrec_stride = 16 + nplanes * qw.plane_stride;
         for (int64_t q0 = 0; q0 < nq; q0 += p.max_batch) {
             const int64_t m = nq - q0 < p.max_batch ? nq - q0 : p.max_batch;
@@ -416,6 +424,8 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
             a.ds.qrecs = W + qw.qrecs;
             a.ds.qrec_stride = qrec_stride;
             a.ds.qplane_stride = qw.plane_stride;
+            a.ds.plane_chunks = idx->plane_chunks;
+            a.ds.plane_shift = idx->plane_shift;
             a.nq = m;
             if (rerank) {
                 a.out_ids = (uint32_t*)(W + qw.fr_ids);
@@ -427,7 +437,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
                 a.out_k = out_k;
             }
             tm.begin();
-            JX_HIP(jx::launch_beam_search(idx->quantized == 4 ? 2 : 3, idx->qbits, a, st));
+            JX_HIP(jx::launch_beam_search(idx->quantized >= 4 ? 2 : 3, idx->qbits, a, st));
             tm.end(2);
             if (rerank) {
                 jx::RerankArgs r;
@@ -668,6 +678,8 @@ static int encode_range(jx_index* idx, int64_t first, int64_t count, hipStream_t
         e.meta_pad = 8;
         JX_HIP(jx::launch_encode(e, st));
         JX_HIP(jx::launch_code_sums(e.codes, m, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, idx->quantized, st));
+        if (idx->plane_shift)
+            JX_HIP(jx::launch_planarize(e.codes, m, idx->code_stride, idx->code_bytes, idx->plane_chunks * 16, idx->quantized, st));
     }
     return JX_OK;
 }
@@ -680,8 +692,8 @@ int jx_quantize(jx_index* idx, int32_t bits, const float* d_rotation, const floa
     if (bits != p.quant_bits) return fail(JX_EINVAL, "bits must equal params.quant_bits (%d)", p.quant_bits);
     if (query_bits != 4 && query_bits != 8) return fail(JX_EINVAL, "query_bits must be 4 or 8");
     if (rule != JX_RULE_MAXABS && rule != JX_RULE_MAXCOS) return fail(JX_EINVAL, "unknown code rule");
-    if (rule == JX_RULE_MAXCOS && bits == 4 && p.dim * 7 > 8192)
-        return fail(JX_EINVAL, "JX_RULE_MAXCOS supports dim <= 1170; use JX_RULE_MAXABS");
+    if (rule == JX_RULE_MAXCOS && bits > 1 && (bits == 8 || p.dim * ((1 << (bits - 1)) - 1) > 8192))
+        return fail(JX_EINVAL, "JX_RULE_MAXCOS supports 2- and 4-bit codes with dim * (2^(bits-1) - 1) <= 8192; use JX_RULE_MAXABS");
     if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
     hipStream_t st = as_stream(stream);
     JX_HIP(hipMemcpyAsync(idx->d_P, d_rotation, (size_t)p.dim * p.dim * 4, hipMemcpyDeviceToDevice, st));
@@ -703,7 +715,7 @@ int jx_export_codes(jx_index* idx, uint8_t* d_codes, float* d_meta, float* d_cen
     if (!idx->quantized) return fail(JX_ESTATE, "index is not quantised");
     hipStream_t st = as_stream(stream);
     JX_HIP(jx::launch_unpack_records(idx->d_codes, idx->n, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, d_codes,
-                                     d_meta, st));
+                                     d_meta, idx->plane_shift ? idx->quantized : 0, idx->plane_chunks * 16, st));
     if (d_centroid)
         JX_HIP(hipMemcpyAsync(d_centroid, idx->d_centroid, (size_t)idx->p.dim * 4, hipMemcpyDeviceToDevice, st));
     return JX_OK;
@@ -722,6 +734,8 @@ int jx_import_codes(jx_index* idx, int32_t bits, const float* d_rotation, const 
     JX_HIP(hipMemcpyAsync(idx->d_centroid, d_centroid, (size_t)p.dim * 4, hipMemcpyDeviceToDevice, st));
     JX_HIP(jx::launch_pack_records(idx->d_codes, idx->n, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, d_codes, d_meta, st));
     JX_HIP(jx::launch_code_sums(idx->d_codes, idx->n, idx->code_stride, idx->code_bytes, idx->meta_chunk * 16, bits, st));
+    if (idx->plane_shift)
+        JX_HIP(jx::launch_planarize(idx->d_codes, idx->n, idx->code_stride, idx->code_bytes, idx->plane_chunks * 16, bits, st));
     idx->quantized = bits;
     idx->qbits = query_bits;
     idx->rule = JX_RULE_MAXABS;

@@ -26,6 +26,7 @@ struct QueryRegs {
     static constexpr int PLANES = (KIND == K_RQ4) ? 2 : (KIND == K_RQ1 ? QB : 1);
     static constexpr int N = 4 * CPL * PLANES;
     uint32_t w[N];
+    uint32_t ps[CPL];     // RaBitQ: left shift of this chunk slot's integer dot product (high code plane)
     // per-query scalars
     int32_t qq;           // U8: sum q^2
     float qqf;            // F16: sum q^2
@@ -60,6 +61,8 @@ __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const Di
         }
     } else {
         constexpr int PL = QueryRegs<KIND, CPL, QB>::PLANES;
+#pragma unroll
+        for (int j = 0; j < CPL; j++) q.ps[j] = (lig + T * j) >= a.plane_chunks ? (uint32_t)a.plane_shift : 0u;
         const float* hdr = reinterpret_cast<const float*>(base);
         q.lo = hdr[0];
         q.delta = hdr[1];
@@ -71,7 +74,9 @@ __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const Di
             for (int j = 0; j < CPL; j++) {
                 int ch = lig + T * j;
                 uint4 v = make_uint4(0, 0, 0, 0);
-                if (ch < a.meta_chunk) v = load16(base + 16 + (size_t)p * a.qplane_stride + (size_t)ch * 16);
+                // the high code plane meets the same query planes as the low one
+                const int qch = ch >= a.plane_chunks ? ch - a.plane_chunks : ch;
+                if (ch < a.meta_chunk) v = load16(base + 16 + (size_t)p * a.qplane_stride + (size_t)qch * 16);
                 q.w[(p * CPL + j) * 4 + 0] = v.x;
                 q.w[(p * CPL + j) * 4 + 1] = v.y;
                 q.w[(p * CPL + j) * 4 + 2] = v.z;
@@ -207,14 +212,14 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
                         ih = __builtin_amdgcn_udot8(v.z, qh[2], ih, false);
                         ih = __builtin_amdgcn_udot8(v.w, qh[3], ih, false);
                     }
-                    I += (QB == 8) ? (16u * ih + il) : il;
+                    I += ((QB == 8) ? (16u * ih + il) : il) << q.ps[j];
                 } else {
 #pragma unroll
                     for (int b = 0; b < QB; b++) {
                         const uint32_t* qp = &q.w[(b * CPL + j) * 4];
                         uint32_t cnt = __builtin_popcount(v.x & qp[0]) + __builtin_popcount(v.y & qp[1]) +
                                        __builtin_popcount(v.z & qp[2]) + __builtin_popcount(v.w & qp[3]);
-                        I += cnt << b;
+                        I += cnt << (b + q.ps[j]);
                     }
                 }
             }

@@ -20,6 +20,9 @@ struct DistSrc {
     const uint8_t* qrecs;  // per-query records
     long long qrec_stride;
     int qplane_stride;     // RaBitQ: bytes between the query's planes
+    int plane_chunks;      // RaBitQ: chunks per code plane (= meta_chunk for 1- and 4-bit codes, meta_chunk / 2 for
+                           // 2- and 8-bit codes, which are stored as a low and a high plane)
+    int plane_shift;       // RaBitQ: log2 of the weight of the high plane (1 for 2-bit, 4 for 8-bit codes, else 0)
 };
 
 struct BeamArgs {
@@ -112,7 +115,8 @@ hipError_t launch_rotate(const void* in, int in_dtype, long long n, int d, const
                          hipStream_t st);
 hipError_t launch_encode(const EncodeArgs& a, hipStream_t st);
 hipError_t launch_unpack_records(const uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,
-                                 uint8_t* codes, float* meta, hipStream_t st);
+                                 uint8_t* codes, float* meta, int planar_bits, int plane_bytes, hipStream_t st);
+hipError_t launch_planarize(uint8_t* recs, long long n, int code_stride, int code_bytes, int plane_bytes, int bits, hipStream_t st);
 hipError_t launch_pack_records(uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,
                                const uint8_t* codes, const float* meta, hipStream_t st);
 hipError_t launch_code_sums(uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off, int bits, hipStream_t st);
@@ -198,6 +202,8 @@ struct jx_index {
     int quantized;    // 0 or bits
     int qbits, rule;
     int code_bytes;   // dim*bits/8
-    int meta_chunk;   // = ceil(code_bytes/16)
+    int meta_chunk;   // chunks of code planes in front of the meta chunk
+    int plane_chunks; // chunks per code plane
+    int plane_shift;  // log2 weight of the high plane (2- and 8-bit codes), else 0
     int code_stride;  // (meta_chunk+1)*16
 };

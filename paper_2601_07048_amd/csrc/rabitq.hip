@@ -159,23 +159,23 @@ __global__ void __launch_bounds__(256) encode_kernel(EncodeArgs a) {
         amax = wave_max_f32(amax);
         const float t = amax > 0.f ? __fdiv_rn((float)half - 0.5f, amax) : 0.f;
         const double cb = ((double)(1 << a.bits) - 1.0) * 0.5;
-        // 8 consecutive coordinates per lane -> one dword of nibbles (bits == 4)
-        for (int c0 = 0; c0 < a.d; c0 += 512) {
-            const int i0 = c0 + lane * 8;
+        // 32 / bits consecutive coordinates per lane -> one dword (field i % per of dword i / per)
+        const int per = 32 / a.bits;
+        for (int c0 = 0; c0 < a.d; c0 += 64 * per) {
+            const int i0 = c0 + lane * per;
             if (i0 < a.d) {
                 uint32_t w = 0;
-#pragma unroll
-                for (int j = 0; j < 8; j++) {
+                for (int j = 0; j < per; j++) {
                     const float x = r[i0 + j];
                     float lvf = floorf(__fmul_rn(t, fabsf(x)));
                     int lv = (int)lvf;
                     lv = lv > half - 1 ? half - 1 : (lv < 0 ? 0 : lv);
                     const int u = x >= 0.0f ? half + lv : half - 1 - lv;
-                    w |= (uint32_t)u << (4 * j);
+                    w |= (uint32_t)u << (a.bits * j);
                     l2 += (double)x * (double)x;
                     ip += ((double)u - cb) * (double)x;
                 }
-                *reinterpret_cast<uint32_t*>(code + i0 / 2) = w;
+                *reinterpret_cast<uint32_t*>(code + (size_t)i0 * a.bits / 8) = w;
             }
         }
     }
@@ -332,23 +332,23 @@ __global__ void __launch_bounds__(256) encode_maxcos_kernel(EncodeArgs a) {
     }
     __syncthreads();
     const double bt = s_best_t;
-    // ---- codes: 8 consecutive coordinates per thread -> one dword
+    // ---- codes: 32 / bits consecutive coordinates per thread -> one dword
     const double cb = ((double)(1 << a.bits) - 1.0) * 0.5;
+    const int per = 32 / a.bits;
     double ip = 0.0;
-    for (int i0 = tid * 8; i0 < a.d; i0 += 2048) {
+    for (int i0 = tid * per; i0 < a.d; i0 += 256 * per) {
         uint32_t w = 0;
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
+        for (int j = 0; j < per; j++) {
             const float x = r[i0 + j];
             const double ax = fabs((double)x);
             int lv = 0;
             if (ax > 0.0)
                 while (lv + 1 < half && (double)(lv + 1) / ax <= bt) lv++;
             const int u = x >= 0.0f ? half + lv : half - 1 - lv;
-            w |= (uint32_t)u << (4 * j);
+            w |= (uint32_t)u << (a.bits * j);
             ip += ((double)u - cb) * (double)x;
         }
-        *reinterpret_cast<uint32_t*>(code + i0 / 2) = w;
+        *reinterpret_cast<uint32_t*>(code + (size_t)i0 * a.bits / 8) = w;
     }
     const double tip = block_scan_incl(ip, ws, tid);
     if (tid == 255) s_ip = tip;
@@ -365,7 +365,7 @@ __global__ void __launch_bounds__(256) encode_maxcos_kernel(EncodeArgs a) {
 hipError_t launch_encode(const EncodeArgs& a, hipStream_t st) {
     if (a.n <= 0) return hipSuccess;
     if (a.bits > 1 && a.rule == JX_RULE_MAXCOS) {
-        if (a.bits != 4 || a.d * ((1 << (a.bits - 1)) - 1) > MC_CAP) return hipErrorInvalidValue;
+        if ((a.bits != 4 && a.bits != 2) || a.d * ((1 << (a.bits - 1)) - 1) > MC_CAP) return hipErrorInvalidValue;
         const size_t sh = (size_t)MC_CAP * (8 + 2);
         hipError_t e = hipFuncSetAttribute((const void*)encode_maxcos_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
         if (e != hipSuccess) return e;
@@ -376,23 +376,111 @@ hipError_t launch_encode(const EncodeArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
+// 2-bit and 8-bit codes are searched as two planes of the 1-bit / 4-bit provider: u = lo + 2^f hi with f = 1 / 4.
+// Natural packing (field i % per of dword i / per) <-> planes ([lo plane][hi plane], each plane_bytes long, a plane
+// packed as 1-bit / 4-bit codes are).  Two natural dwords make one dword of each plane.
+__device__ __forceinline__ uint32_t even_bits(uint32_t x) {  // bits 0,2,4,.. -> bits 0..15
+    x &= 0x55555555u;
+    x = (x | (x >> 1)) & 0x33333333u;
+    x = (x | (x >> 2)) & 0x0F0F0F0Fu;
+    x = (x | (x >> 4)) & 0x00FF00FFu;
+    x = (x | (x >> 8)) & 0x0000FFFFu;
+    return x;
+}
+__device__ __forceinline__ uint32_t spread_bits(uint32_t x) {  // bits 0..15 -> bits 0,2,4,..
+    x &= 0x0000FFFFu;
+    x = (x | (x << 8)) & 0x00FF00FFu;
+    x = (x | (x << 4)) & 0x0F0F0F0Fu;
+    x = (x | (x << 2)) & 0x33333333u;
+    x = (x | (x << 1)) & 0x55555555u;
+    return x;
+}
+__device__ __forceinline__ uint32_t low_nibbles(uint32_t x) {  // low nibble of each byte -> bits 0..15
+    x &= 0x0F0F0F0Fu;
+    x = (x | (x >> 4)) & 0x00FF00FFu;
+    x = (x | (x >> 8)) & 0x0000FFFFu;
+    return x;
+}
+__device__ __forceinline__ uint32_t spread_nibbles(uint32_t x) {  // nibbles 0..3 -> low nibble of bytes 0..3
+    x &= 0x0000FFFFu;
+    x = (x | (x << 8)) & 0x00FF00FFu;
+    x = (x | (x << 4)) & 0x0F0F0F0Fu;
+    return x;
+}
+__device__ __forceinline__ void split_pair(int bits, uint32_t n0, uint32_t n1, uint32_t* lo, uint32_t* hi) {
+    if (bits == 2) {
+        *lo = even_bits(n0) | (even_bits(n1) << 16);
+        *hi = even_bits(n0 >> 1) | (even_bits(n1 >> 1) << 16);
+    } else {
+        *lo = low_nibbles(n0) | (low_nibbles(n1) << 16);
+        *hi = low_nibbles(n0 >> 4) | (low_nibbles(n1 >> 4) << 16);
+    }
+}
+__device__ __forceinline__ void join_pair(int bits, uint32_t lo, uint32_t hi, uint32_t* n0, uint32_t* n1) {
+    if (bits == 2) {
+        *n0 = spread_bits(lo) | (spread_bits(hi) << 1);
+        *n1 = spread_bits(lo >> 16) | (spread_bits(hi >> 16) << 1);
+    } else {
+        *n0 = spread_nibbles(lo) | (spread_nibbles(hi) << 4);
+        *n1 = spread_nibbles(lo >> 16) | (spread_nibbles(hi >> 16) << 4);
+    }
+}
+
+// in place: natural codes at the start of each record -> two planes; one wavefront per record, staged in LDS
+__global__ void __launch_bounds__(256) planarize_kernel(uint8_t* recs, long long n, int code_stride, int code_bytes, int plane_bytes,
+                                                       int bits) {
+    extern __shared__ __align__(16) uint32_t stage[];  // 4 x code_bytes / 4
+    const long long v = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const int lane = lane_id();
+    uint32_t* mine = stage + (size_t)(threadIdx.x >> 6) * (code_bytes / 4);
+    uint32_t* rec = reinterpret_cast<uint32_t*>(recs + (size_t)v * code_stride);
+    const int nd = code_bytes / 4;  // natural dwords (even: dim % 32 == 0)
+    for (int k = lane; k < nd; k += 64) mine[k] = rec[k];
+    wave_sync();
+    for (int k = lane; k < plane_bytes / 4; k += 64) {  // dword k of each plane, zero beyond the codes
+        uint32_t lo = 0, hi = 0;
+        if (2 * k + 1 < nd) split_pair(bits, mine[2 * k], mine[2 * k + 1], &lo, &hi);
+        rec[k] = lo;
+        rec[plane_bytes / 4 + k] = hi;
+    }
+}
+
+hipError_t launch_planarize(uint8_t* recs, long long n, int code_stride, int code_bytes, int plane_bytes, int bits, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(planarize_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), (size_t)4 * code_bytes, st, recs, n, code_stride,
+                       code_bytes, plane_bytes, bits);
+    return hipGetLastError();
+}
+
 // records -> unpadded codes + meta
 __global__ void __launch_bounds__(256) unpack_records_kernel(const uint8_t* recs, long long n, int code_stride, int code_bytes,
-                                                            int meta_off, uint8_t* codes, float* meta) {
+                                                            int meta_off, uint8_t* codes, float* meta, int planar_bits,
+                                                            int plane_bytes) {
     const long long v = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (v >= n) return;
     const int lane = lane_id();
     const uint8_t* rec = recs + (size_t)v * code_stride;
+    if (planar_bits) {  // two planes -> natural packing
+        const uint32_t* pl = reinterpret_cast<const uint32_t*>(rec);
+        uint32_t* out = reinterpret_cast<uint32_t*>(codes + (size_t)v * code_bytes);
+        for (int k = lane; 2 * k + 1 < code_bytes / 4; k += 64) {
+            uint32_t n0, n1;
+            join_pair(planar_bits, pl[k], pl[plane_bytes / 4 + k], &n0, &n1);
+            out[2 * k] = n0;
+            out[2 * k + 1] = n1;
+        }
+    } else
     for (int b = lane * 4; b < code_bytes; b += 256)
         *reinterpret_cast<uint32_t*>(codes + (size_t)v * code_bytes + b) = *reinterpret_cast<const uint32_t*>(rec + b);
     if (lane < 2) meta[2 * v + lane] = reinterpret_cast<const float*>(rec + meta_off)[lane];
 }
 
 hipError_t launch_unpack_records(const uint8_t* recs, long long n, int code_stride, int code_bytes, int meta_off,
-                                 uint8_t* codes, float* meta, hipStream_t st) {
+                                 uint8_t* codes, float* meta, int planar_bits, int plane_bytes, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(unpack_records_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, recs, n, code_stride, code_bytes,
-                       meta_off, codes, meta);
+                       meta_off, codes, meta, planar_bits, plane_bytes);
     return hipGetLastError();
 }
 
@@ -420,7 +508,7 @@ hipError_t launch_pack_records(uint8_t* recs, long long n, int code_stride, int 
     return hipGetLastError();
 }
 
-// Sum of the code units of every record (popcount for 1-bit codes, sum of nibbles for 4-bit codes), stored as a
+// Sum of the code units of every record (codes in their natural packing: fields of `bits` bits), stored as a
 // uint32 behind the two floats of the meta chunk: the estimator's sum(u) term then costs the search kernel nothing.
 __global__ void __launch_bounds__(256) code_sums_kernel(uint8_t* recs, long long n, int code_stride, int code_bytes,
                                                        int meta_off, int bits) {
@@ -431,7 +519,14 @@ __global__ void __launch_bounds__(256) code_sums_kernel(uint8_t* recs, long long
     uint32_t s = 0;
     for (int b = lane * 4; b < code_bytes; b += 256) {
         const uint32_t w = *reinterpret_cast<const uint32_t*>(rec + b);
-        s += bits == 1 ? (uint32_t)__builtin_popcount(w) : __builtin_amdgcn_udot8(w, 0x11111111u, 0u, false);
+        if (bits == 1)
+            s += (uint32_t)__builtin_popcount(w);
+        else if (bits == 2)
+            s += (uint32_t)__builtin_popcount(w & 0x55555555u) + 2u * (uint32_t)__builtin_popcount(w & 0xAAAAAAAAu);
+        else if (bits == 4)
+            s += __builtin_amdgcn_udot8(w, 0x11111111u, 0u, false);
+        else
+            s += __builtin_amdgcn_udot4(w, 0x01010101u, 0u, false);
     }
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) s += shfl_xor(s, m);
@@ -476,9 +571,10 @@ __global__ void __launch_bounds__(256) query_prep_kernel(QueryPrepArgs a) {
         hdr[2] = (float)s2;
         hdr[3] = (float)(cb * s);
     }
-    const int nplanes = a.bits == 4 ? 2 : a.qbits;
+    const bool nib = a.bits >= 4;  // 4- and 8-bit codes: nibble planes; 1- and 2-bit codes: bit planes
+    const int nplanes = nib ? 2 : a.qbits;
     // zero the padding of each plane (planes are whole 16-byte chunks)
-    const int written = a.bits == 4 ? a.d / 2 : a.d / 8;
+    const int written = nib ? a.d / 2 : a.d / 8;
     for (int p = 0; p < nplanes; p++)
         for (int b = written + lane * 4; b < a.plane_stride; b += 256)
             *reinterpret_cast<uint32_t*>(rec + 16 + (size_t)p * a.plane_stride + b) = 0u;
@@ -489,7 +585,7 @@ __global__ void __launch_bounds__(256) query_prep_kernel(QueryPrepArgs a) {
         t = t < 0.f ? 0.f : (t > levels ? levels : t);
         return (uint32_t)t;
     };
-    if (a.bits == 4) {
+    if (nib) {
         // nibble planes: dword k holds coordinates 8k..8k+7; plane 0 = high nibbles, plane 1 = low nibbles
         for (int c0 = 0; c0 < a.d; c0 += 512) {
             const int i0 = c0 + lane * 8;

@@ -54,7 +54,8 @@ def test_rotation_gemm(jx, d, n):
     assert np.array_equal(got, x @ Q.T)
 
 
-@pytest.mark.parametrize("bits,d", [(1, 1536), (4, 960), (1, 96), (4, 32), (4, 1536), (1, 960)])
+@pytest.mark.parametrize("bits,d", [(1, 1536), (4, 960), (1, 96), (4, 32), (4, 1536), (1, 960), (2, 960), (2, 32), (2, 1536),
+                                    (8, 96), (8, 960), (8, 1536)])
 def test_encoder_on_injected_rotated_vectors(jx, bits, d):
     """Encoder stage alone: fed with the oracle's float32 rotated vectors it must
     emit the oracle's codes bit for bit (the decisions are float32 on both
@@ -74,6 +75,25 @@ def test_encoder_on_injected_rotated_vectors(jx, bits, d):
     ec, em, cen = g.export_codes()
     assert np.array_equal(ec.cpu().numpy(), wc) and np.allclose(em.cpu().numpy(), wm, rtol=2e-7, atol=0)
     assert (cen.cpu().numpy() == 0).all()
+
+
+@pytest.mark.parametrize("d", [960, 96, 1536])
+def test_max_cosine_encoder_two_bit(jx, d):
+    """The same sweep for 2-bit codes (one breakpoint per coordinate)."""
+    n = 300
+    r32 = (_clustered(n, d, 78 + d) * np.float32(2.3)).astype(np.float32)
+    r32[3] = 0.0
+    r32[7] = np.float32(0.5)
+    r32[9, ::2] = r32[9, 1::2]
+    g = jx.Index(d, jx.F32, 8, 8, 1.2, capacity=n, quant_bits=2)
+    g.import_graph(dev(r32), dev(np.full((n, 8), jx.NONE, np.uint32)), 0)
+    g.quantize(2, dev(np.eye(d, dtype=np.float32)), dev(np.zeros(d, np.float32)), rule=jx.RULE_MAXCOS)
+    codes, meta = g.encode_rotated(dev(r32))
+    wc, wm, _ = oracle.rabitq_encode(r32, 2, oracle.RULE_MAXCOS)
+    assert np.array_equal(codes.cpu().numpy(), wc)
+    assert np.allclose(meta.cpu().numpy(), wm, rtol=2e-7, atol=0)
+    ec, em, _ = g.export_codes()   # through the two-plane record and back
+    assert np.array_equal(ec.cpu().numpy(), wc)
 
 
 @pytest.mark.parametrize("d", [960, 96, 32, 1152])
@@ -122,7 +142,8 @@ def _quantized_pair(jx, x, P, bits, qbits, R=24, L=48, centroid=None, inject=Fal
     return ix, g
 
 
-@pytest.mark.parametrize("bits,qbits,d", [(4, 8, 960), (1, 8, 1536), (4, 4, 128), (1, 4, 256), (1, 8, 96), (4, 8, 1536)])
+@pytest.mark.parametrize("bits,qbits,d", [(4, 8, 960), (1, 8, 1536), (4, 4, 128), (1, 4, 256), (1, 8, 96), (4, 8, 1536),
+                                          (2, 4, 960), (2, 8, 96), (2, 4, 1536), (8, 8, 96), (8, 8, 960), (8, 4, 1536)])
 def test_estimated_beam_bit_exact_on_injected_codes(jx, bits, qbits, d):
     """beamSearch + estimator stage: oracle codes injected, rotation a signed
     permutation and c = 0 (so both sides see identical rotated queries).  The
@@ -248,6 +269,12 @@ def test_rabitq_argument_errors(jx):
         g.search(dev(x[:4]), 5, 8, mode=jx.RABITQ, rerank=3)  # rerank < k
     with pytest.raises(jx.JxError):
         jx.Index(48, jx.U8, 8, 16, 1.2, capacity=n, quant_bits=4)  # RaBitQ needs dim % 32 == 0
+    with pytest.raises(jx.JxError):
+        jx.Index(d, jx.F32, 8, 16, 1.2, capacity=n, quant_bits=3)  # widths are 1, 2, 4, 8
+    g8 = jx.Index(d, jx.F32, 8, 16, 1.2, capacity=n, quant_bits=8)
+    g8.import_graph(dev(x), dev(np.full((n, 8), jx.NONE, np.uint32)), 0)
+    with pytest.raises(jx.JxError):
+        g8.quantize(8, P, rule=jx.RULE_MAXCOS)  # the breakpoint sweep is offered for 2- and 4-bit codes
 
 
 def test_rabitq_on_uint8_data(jx):
@@ -286,3 +313,34 @@ def test_rabitq_on_uint8_data(jx):
     fi, fd = g.beam_frontier(dev(q), 50, mode=jx.RABITQ)
     assert np.array_equal(u32(fi), ref["F_ids"])
     assert np.array_equal(fd.cpu().numpy().astype(np.float64), ref["F_dist"])
+
+
+@pytest.mark.parametrize("bits,d,n", [(2, 960, 3000), (8, 960, 3000), (2, 1536, 2000), (8, 128, 3000)])
+def test_quantize_end_to_end_other_widths(jx, bits, d, n):
+    """2- and 8-bit codes, whole path (rotation on the GPU in float32, oracle in double): codes at most one level
+    apart on rare coordinates, re-ranked recall within 0.005 of the oracle's, estimates close where ranks agree."""
+    wl = 3 if d == 960 else (4 if d == 1536 else 1)
+    x = datagen.base(wl, n)
+    q = datagen.queries(wl, 200)
+    P = datagen.rotation(wl)
+    ix, g = _quantized_pair(jx, x, P, bits, 8, R=32, L=64, rule=1)
+    wc, wm, wcen = ix.codes()
+    gc, gm, gcen = [t.cpu().numpy() for t in g.export_codes()]
+    assert gc.shape == wc.shape == (n, d * bits // 8)
+    U = np.stack([oracle.rabitq_unpack(wc[i], bits, d) for i in range(0, n, 7)]).astype(int)
+    G = np.stack([oracle.rabitq_unpack(gc[i], bits, d) for i in range(0, n, 7)]).astype(int)
+    diff = U != G
+    assert diff.mean() < (2e-3 if bits == 2 else 2e-2) and (np.abs(U - G)[diff] <= 1).all()
+    gt = oracle.bruteforce(x, q, 10)[0]
+    rr = ix.search(q, 10, 64, mode=1, rerank=40)
+    gi, _ = g.search(dev(q), 10, 64, mode=jx.RABITQ, rerank=40)
+    r_gpu, r_ref = oracle.recall_at_k(u32(gi), gt), oracle.recall_at_k(rr["ids"], gt)
+    assert abs(r_gpu - r_ref) <= 0.005, (r_gpu, r_ref)
+    ref = ix.search(q, 10, 64, mode=1, want_frontier=True)
+    ids, dist = g.beam_frontier(dev(q), 64, mode=jx.RABITQ)
+    ids, dist = u32(ids), dist.cpu().numpy().astype(np.float64)
+    m = ids == ref["F_ids"]
+    assert m.mean() > 0.8
+    # a code that differs by one (coarse) level moves that vector's estimate; everything else agrees to rounding
+    err = np.abs(dist[m] - ref["F_dist"][m]) / np.abs(ref["F_dist"]).mean()
+    assert np.quantile(err, 0.98) < 1e-3 and err.max() < 0.05, (np.quantile(err, 0.98), err.max())
