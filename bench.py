@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--recall", type=float, default=0.95)
     ap.add_argument("--L", type=int, default=0, help="force the beam width (0 = smallest with recall >= target)")
     ap.add_argument("--query-bits", type=int, default=0, help="B_q of the integer query (0 = 8 for 4-bit codes, 4 for 1-bit codes)")
-    ap.add_argument("--cpu-queries", type=int, default=2000, help="sample size of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--cpu-queries", type=int, default=10000, help="sample size of the cpu_baseline leg (0 = skip)")
     ap.add_argument("--bits", type=int, default=0, choices=[0, 1, 2, 4, 8],
                     help="RaBitQ code width for the quantised workloads (0 = the workload's own: 4, 4, 1 for 3, 8, 4)")
     ap.add_argument("--f16", action="store_true", help="store the float workloads (3, 4) as binary16 (App. D of the paper)")
@@ -278,14 +278,14 @@ def main():
         # the oracle's batch insertion on a bounded prefix of the same base set (uint8 workloads)
         ins = None
         if sp["u8"]:
-            pre = min(n, 50_000)
+            pre = min(n, 200_000)
             oins = oracle.Index(d, np.uint8, R, L_build, alpha, pre)
             t0 = time.perf_counter()
             oins.insert(dx[:pre].cpu().numpy())
             ins = round(pre / (time.perf_counter() - t0), 1)
             del oins
         cpu = {"value": round(m / dt, 1), "unit": "queries/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "inserts_per_s": ins, "insert_sample": "first 50,000 base vectors inserted into an empty index" if ins else None,
+               "inserts_per_s": ins, "insert_sample": f"first {min(n, 200_000):,} base vectors inserted into an empty index" if ins else None,
                "sample": f"first {m} of the {nq} queries, same graph" + (" and codes" if rabitq else "") +
                          f", same L={L_star}; fraction of result ids identical to the GPU's: {agree:.4f}"}
 
