@@ -341,6 +341,317 @@ __global__ void __launch_bounds__(GP_WPB * 64) reverse_merge_gram_kernel(InsertA
     }
 }
 
+
+// ---- more than 128 candidates: the same contraction, one block row of tiles at a time --------------------------
+// Eight 32-row blocks make 36 upper-triangle tiles, too many accumulators for one pass, and only the bit masks of
+// the relation have to survive a tile.  So the wavefront walks the block rows: for block row bi it accumulates the
+// tiles (bi, bi .. nb-1) over the whole vector length, turns them into mask words, and moves on; a block is read
+// (nb - bi) + 1 times instead of once, still far less than the list-based form reads.  G_jj (and G_jp for
+// binary16) are needed for columns of later blocks, so a first pass over the vectors computes them with plain
+// fused multiply-adds.
+// Beyond 256 candidates only a prefix is taken: Alg. 3 visits candidates in (distance, id) order and stops at R
+// selections, and what happens to a candidate depends on earlier ones only.  The pool is the existing neighbours
+// plus the closest new candidates (the new list arrives sorted) up to 256 rows; if the walk selects R neighbours
+// before it meets a pool member beyond the last included new candidate, the excluded ones could not have mattered
+// and the result is exact.  Otherwise the segment is left to the list-based kernel.
+#define GB_MAX 256
+#define GB_NB 8
+
+struct GramBigLds {
+    uint64_t key[GB_MAX];
+    uint32_t id[GB_MAX];
+    float dp[GB_MAX];
+    float nrm[GB_MAX];
+    uint32_t kill[GB_MAX * GB_NB];
+    uint32_t kb[GB_MAX * GB_NB];
+    uint32_t sel_id[GB_MAX];
+    uint16_t order[GB_MAX];
+};
+
+// L->id[0..M): n_fixed existing neighbours, then new candidates whose (distance bits << 32 | ...) keys are
+// new_keys[0..M-n_fixed), ascending.  truncated: further new candidates exist beyond the pool.  Returns the number
+// selected, or -1 if the pool did not suffice.
+template <int DT>
+__device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride, int vec_bytes, GramBigLds* L, int M, uint32_t p,
+                                              int R, float alpha, int n_fixed, const uint64_t* new_keys, bool truncated) {
+    const int lane = lane_id(), col = lane & 31, half = lane >> 5;
+    const int nb = (M + 31) >> 5;
+    const uint8_t* pp = recs + (size_t)p * stride;
+    // ---- pass 1: d(p, j) and G_jj.  float32: rows centred at p, so both are the same number
+    float npp = 0.f;
+    if constexpr (DT == JX_F16) {
+        for (int p0 = half * 64; p0 < vec_bytes; p0 += 128)
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                const int o = p0 + s * 16;
+                if (o < vec_bytes) {
+                    const uint4 x = load16(pp + o);
+                    npp = hdot2(x.x, x.x, npp);
+                    npp = hdot2(x.y, x.y, npp);
+                    npp = hdot2(x.z, x.z, npp);
+                    npp = hdot2(x.w, x.w, npp);
+                }
+            }
+        npp += shfl_xor(npp, 32);
+    }
+    for (int b = 0; b < nb; b++) {
+        const int i = b * 32 + col;
+        const uint8_t* rp = recs + (size_t)(i < M ? L->id[i] : p) * stride;
+        float nn = 0.f, np = 0.f;
+        for (int p0 = half * 64; p0 < vec_bytes; p0 += 128)
+#pragma unroll
+            for (int s = 0; s < 4; s++) {
+                const int o = p0 + s * 16;
+                if (o < vec_bytes) {
+                    const uint4 x = load16(rp + o), c = load16(pp + o);
+                    if constexpr (DT == JX_F32) {
+                        const float d0 = __uint_as_float(x.x) - __uint_as_float(c.x), d1 = __uint_as_float(x.y) - __uint_as_float(c.y);
+                        const float d2 = __uint_as_float(x.z) - __uint_as_float(c.z), d3 = __uint_as_float(x.w) - __uint_as_float(c.w);
+                        nn = fmaf(d0, d0, nn);
+                        nn = fmaf(d1, d1, nn);
+                        nn = fmaf(d2, d2, nn);
+                        nn = fmaf(d3, d3, nn);
+                    } else {
+                        nn = hdot2(x.x, x.x, nn);
+                        nn = hdot2(x.y, x.y, nn);
+                        nn = hdot2(x.z, x.z, nn);
+                        nn = hdot2(x.w, x.w, nn);
+                        np = hdot2(x.x, c.x, np);
+                        np = hdot2(x.y, c.y, np);
+                        np = hdot2(x.z, c.z, np);
+                        np = hdot2(x.w, c.w, np);
+                    }
+                }
+            }
+        nn += shfl_xor(nn, 32);
+        np += shfl_xor(np, 32);
+        if (half == 0) {
+            L->nrm[i] = i < M ? nn : 0.f;
+            float d = nn;
+            if constexpr (DT == JX_F16) d = fmaxf(npp + nn - 2.f * np, 0.f);
+            // a new candidate keeps the distance it was sorted by
+            if (i >= n_fixed && i < M) d = __uint_as_float((uint32_t)(new_keys[i - n_fixed] & 0xFFFFFFFFull));
+            L->dp[i] = d;
+            if (i < M) L->key[i] = ((uint64_t)__float_as_uint(d) << 32) | L->id[i];
+        }
+    }
+    wave_sync();
+    for (int j = lane; j < M; j += 64) {
+        const uint64_t k = L->key[j];
+        int rank = 0;
+        for (int t = 0; t < M; t++) {
+            const uint64_t o = L->key[t];
+            rank += (o < k || (o == k && t < j)) ? 1 : 0;
+        }
+        L->order[rank] = (uint16_t)j;
+    }
+    // ---- pass 2: block rows of the Gram matrix -> mask words
+    for (int bi = 0; bi < nb; bi++) {
+        f32x16_t acc[GB_NB];
+#pragma unroll
+        for (int t = 0; t < GB_NB; t++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[t][e] = 0.f;
+        const uint8_t* rp[GB_NB];
+        bool rv[GB_NB];
+#pragma unroll
+        for (int t = 0; t < GB_NB; t++) {
+            const int i = (bi + t) * 32 + col;
+            rv[t] = i < M;
+            rp[t] = recs + (size_t)(i < M ? L->id[i] : p) * stride;
+        }
+        for (int p0 = 0; p0 < vec_bytes; p0 += 128) {
+            const int off = p0 + half * 64;
+            if constexpr (DT == JX_F32) {
+                float c[16], fa[16];
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    const int o = off + s * 16;
+                    uint4 x = make_uint4(0, 0, 0, 0), y = x;
+                    if (o < vec_bytes) {
+                        x = load16(pp + o);
+                        y = load16(rp[0] + o);
+                    }
+                    c[4 * s + 0] = __uint_as_float(x.x);
+                    c[4 * s + 1] = __uint_as_float(x.y);
+                    c[4 * s + 2] = __uint_as_float(x.z);
+                    c[4 * s + 3] = __uint_as_float(x.w);
+                    fa[4 * s + 0] = __uint_as_float(y.x) - c[4 * s + 0];
+                    fa[4 * s + 1] = __uint_as_float(y.y) - c[4 * s + 1];
+                    fa[4 * s + 2] = __uint_as_float(y.z) - c[4 * s + 2];
+                    fa[4 * s + 3] = __uint_as_float(y.w) - c[4 * s + 3];
+                }
+#pragma unroll
+                for (int t = 0; t < GB_NB; t++) {
+                    if (bi + t >= nb) break;  // uniform
+                    float fb[16];
+                    if (t == 0) {
+#pragma unroll
+                        for (int e = 0; e < 16; e++) fb[e] = fa[e];
+                    } else {
+#pragma unroll
+                        for (int s = 0; s < 4; s++) {
+                            const int o = off + s * 16;
+                            uint4 y = make_uint4(0, 0, 0, 0);
+                            if (o < vec_bytes) y = load16(rp[t] + o);  // rows beyond M point at p and centre to zero
+                            fb[4 * s + 0] = __uint_as_float(y.x) - c[4 * s + 0];
+                            fb[4 * s + 1] = __uint_as_float(y.y) - c[4 * s + 1];
+                            fb[4 * s + 2] = __uint_as_float(y.z) - c[4 * s + 2];
+                            fb[4 * s + 3] = __uint_as_float(y.w) - c[4 * s + 3];
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 16; e++) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[e], fb[e], acc[t], 0, 0, 0);
+                }
+            } else {
+                uint4 fa[4];
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    const int o = off + s * 16;
+                    fa[s] = make_uint4(0, 0, 0, 0);
+                    if (rv[0] && o < vec_bytes) fa[s] = load16(rp[0] + o);
+                }
+#pragma unroll
+                for (int t = 0; t < GB_NB; t++) {
+                    if (bi + t >= nb) break;  // uniform
+                    uint4 fb[4];
+#pragma unroll
+                    for (int s = 0; s < 4; s++) {
+                        const int o = off + s * 16;
+                        fb[s] = fa[s];
+                        if (t > 0) {
+                            fb[s] = make_uint4(0, 0, 0, 0);
+                            if (rv[t] && o < vec_bytes) fb[s] = load16(rp[t] + o);
+                        }
+                    }
+#pragma unroll
+                    for (int s = 0; s < 4; s++)
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, fa[s]),
+                                                                        __builtin_bit_cast(f16x8_t, fb[s]), acc[t], 0, 0, 0);
+                }
+            }
+        }
+        // masks of this block row
+#pragma unroll
+        for (int t = 0; t < GB_NB; t++) {
+            if (bi + t >= nb) break;
+            const int bj = bi + t;
+            const int j = bj * 32 + col;
+            const float nj = L->nrm[j], dpj = L->dp[j];
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const int r0 = bi * 32 + 8 * (e >> 2) + (e & 3);
+                const int i = r0 + 4 * half;
+                const float ni = L->nrm[i], dpi = L->dp[i];
+                const float dij = fmaxf((ni + nj) - 2.f * acc[t][e], 0.f);
+                const float ad = __fmul_rn(alpha, dij);
+                const bool ok = i < M && j < M && i != j;
+                const uint64_t m1 = ballot(ok && ad <= dpj);
+                if (lane == 0) {
+                    L->kill[r0 * GB_NB + bj] = (uint32_t)m1;
+                    L->kill[(r0 + 4) * GB_NB + bj] = (uint32_t)(m1 >> 32);
+                }
+                if (t > 0) {
+                    const uint64_t m2 = ballot(ok && ad <= dpi);
+                    if (lane == 0) {
+                        L->kb[r0 * GB_NB + bj] = (uint32_t)m2;
+                        L->kb[(r0 + 4) * GB_NB + bj] = (uint32_t)(m2 >> 32);
+                    }
+                }
+            }
+        }
+    }
+    wave_sync();
+    // ---- Alg. 3 on 256-bit masks
+    const uint64_t tau = truncated ? L->key[M - 1] : JX_EMPTY_KEY;  // the last new candidate of the pool
+    uint32_t A[GB_NB], S[GB_NB];
+#pragma unroll
+    for (int t = 0; t < GB_NB; t++) {
+        const int rem = M - 32 * t;
+        A[t] = rem >= 32 ? 0xFFFFFFFFu : (rem <= 0 ? 0u : ((1u << rem) - 1u));
+        S[t] = 0u;
+    }
+    int nsel = 0;
+    bool short_pool = truncated;  // cleared when R neighbours are found inside the prefix
+    for (int r = 0; r < M; r++) {
+        if (nsel >= R) {
+            short_pool = false;
+            break;
+        }
+        const int c = L->order[r];
+        if (truncated && L->key[c] > tau) break;  // beyond the prefix with room left: excluded candidates would matter
+        const int w = c >> 5;
+        const uint32_t bit = 1u << (c & 31);
+        uint32_t aw = 0u;
+#pragma unroll
+        for (int t = 0; t < GB_NB; t++)
+            if (t == w) aw = A[t];
+        if (!(aw & bit)) continue;
+        const uint32_t cid = L->id[c];
+        if (cid == p) continue;
+        bool gone = false;
+#pragma unroll
+        for (int t = 1; t < GB_NB; t++)
+            if (t > w && t < nb) gone = gone || (L->kb[c * GB_NB + t] & S[t]) != 0u;
+        if (gone) continue;
+        if (lane == 0) L->sel_id[nsel] = cid;
+        nsel++;
+#pragma unroll
+        for (int t = 0; t < GB_NB; t++) {
+            if (t == w) S[t] |= bit;
+            if (t >= w && t < nb) A[t] &= ~L->kill[c * GB_NB + t];
+        }
+    }
+    wave_sync();
+    if (nsel >= R) short_pool = false;
+    return short_pool ? -1 : nsel;
+}
+
+template <int DT>
+__global__ void __launch_bounds__(GP_WPB * 64) reverse_merge_gram_big_kernel(InsertArgs a) {
+    extern __shared__ __align__(16) unsigned char gb_dyn[];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    GramBigLds* L = reinterpret_cast<GramBigLds*>(gb_dyn) + wave;
+    const long long nseg = *a.nseg;
+    const long long total = a.E ? a.E : a.B * a.R;
+    for (long long s = (long long)blockIdx.x * GP_WPB + wave; s < nseg; s += (long long)gridDim.x * GP_WPB) {
+        const uint32_t head = a.heads[s];
+        if (head & 0x80000000u) continue;
+        const long long lo = head;
+        const uint32_t v = (uint32_t)(a.keys[lo] >> 32);
+        if (v == JX_NONE_ID) continue;
+        int m = 0;
+        for (long long c0 = lo; c0 < total; c0 += 64) {
+            const long long j = c0 + lane;
+            const bool same = j < total && (uint32_t)(a.keys[j] >> 32) == v;
+            const uint64_t sm = ballot(same);
+            m += __builtin_popcountll(sm);
+            if (sm != ~0ull) break;
+        }
+        uint32_t* row = a.adj + (size_t)v * a.R;
+        int deg = 0;
+        for (int rb = 0; rb < a.R; rb += 64) {
+            const bool on = rb + lane < a.R && row[rb + lane] != JX_NONE_ID;
+            deg += __builtin_popcountll(ballot(on));
+        }
+        if (a.force_prune) deg = 0;
+        if (!a.force_prune && deg + m <= a.R) continue;
+        if (deg + m + (DT == JX_F16 ? 1 : 0) <= GP_MAX) continue;  // the one-pass kernels' share
+        if (deg > GB_MAX - 64) continue;                             // too little room for new candidates: list-based kernel
+        const int mp = m < GB_MAX - deg ? m : GB_MAX - deg;          // new candidates in the pool (the closest ones)
+        const int M = deg + mp;
+        for (int j = lane; j < deg; j += 64) L->id[j] = row[j];
+        for (int j = lane; j < mp; j += 64) L->id[deg + j] = a.vals[lo + j];
+        wave_sync();
+        const int nsel = gram_prune_big<DT>(a.ds.recs, (size_t)a.ds.rec_stride, a.ds.nch * 16, L, M, v, a.R, a.alpha, deg, a.keys + lo,
+                                            mp < m);
+        if (nsel < 0) continue;  // the prefix did not yield R neighbours: left to the list-based kernel
+        for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? L->sel_id[j] : JX_NONE_ID;
+        if (lane == 0) const_cast<uint32_t*>(a.heads)[s] = head | 0x80000000u;
+        wave_sync();
+    }
+}
+
 template <int DT>
 static hipError_t launch_forward_gram_dt(const InsertArgs& a, hipStream_t st) {
     dim3 grid((unsigned)((a.B + GP_WPB - 1) / GP_WPB)), block(GP_WPB * 64);
@@ -357,6 +668,12 @@ static hipError_t launch_reverse_gram_dt(const InsertArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 2>), grid, block, 0, st, a);
     hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 3>), grid, block, 0, st, a);
     hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 4>), grid, block, 0, st, a);
+    {   // 129 .. 256 candidates: few and long, 4 wavefronts per workgroup with 27 KB of LDS each
+        const size_t sh = sizeof(GramBigLds) * GP_WPB;
+        hipError_t e = hipFuncSetAttribute((const void*)reverse_merge_gram_big_kernel<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((reverse_merge_gram_big_kernel<DT>), dim3(grid.x < 1024 ? grid.x : 1024), block, sh, st, a);
+    }
     return hipGetLastError();
 }
 

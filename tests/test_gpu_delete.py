@@ -166,6 +166,31 @@ def test_consolidate_float_dyadic_bit_exact(jx, dtype):
     _same_search(ref, g, q, 10, L)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_consolidate_float_large_candidate_sets_bit_exact(jx, dtype):
+    """Half of the vertices deleted with R = 40: candidate sets of several hundred, beyond the 256 rows of the
+    matrix-core prune, which then works on the closest prefix (exact whenever R neighbours are found inside it)
+    or hands the vertex to the list-based kernel.  Dyadic grid: the result must equal the oracle's bit for bit."""
+    from paper_2601_07048_amd import datagen
+    n, d, R, L = 3000, 64, 40, 80
+    x = datagen.dyadic_grid(n, d, seed=21).astype(dtype)
+    ref, g = _pair(jx, x, R, L)
+    rng = np.random.default_rng(9)
+    dele = rng.choice(n, n // 2, replace=False).astype(np.uint32)
+    ref.delete(dele)
+    g.delete(dev(dele))
+    adj0, deg0 = ref.graph()
+    dead = np.zeros(n, bool)
+    dead[dele] = True
+    sizes = [sum(int((~dead[adj0[u, :deg0[u]]]).sum()) if dead[u] else 1 for u in adj0[v, :deg0[v]]) for v in range(0, n, 50)
+             if not dead[v]]
+    assert max(sizes) > 300  # the case this test is about
+    ref.consolidate()
+    g.consolidate()
+    assert g.size() == (n, ref.entry)
+    _same_graph(ref, g)
+
+
 def test_consolidate_float_quality(jx):
     """Generic float data: rounding differs, so compare what must hold: no edge
     to or from a deleted vertex, rows nearly equal, recall against brute force

@@ -108,6 +108,7 @@ def test_insert_f32_dyadic_grid_bit_exact(jx):
     (2500, 64, 126, 128, None, 0.25),       # binary16: 127 candidates + the pruned vertex fill the 128 rows exactly
     (2500, 64, 127, 128, None, 0.25),       # binary16: one too many for the extra row -> list-based kernel
     (2000, 64, 24, 160, [800, 1200], 0.25), # frontier wider than 128: forward prune stays with the list-based kernel
+    (6000, 32, 12, 24, [10, 5990], 1.0),    # doubling batches, small R: hubs collect hundreds of new edges (prefix pools)
 ])
 def test_insert_float_dyadic_grid_gram_classes(jx, dtype, n, d, R, L, calls, growth):
     """Float builds on a dyadic grid (every distance exact in float32 in any summation order) must equal the
