@@ -172,7 +172,15 @@ int gram_mode(int dtype) {
         const char* e = getenv("JX_GRAM");
         on = (e && atoi(e) == 0) ? 0 : 1;
     }
-    if (!on || dtype == JX_U8) return 0;
+    if (!on) return 0;
+    if (dtype == JX_U8) {
+        static int u8 = -1;
+        if (u8 < 0) {
+            const char* e = getenv("JX_GRAM_U8");
+            u8 = (e && atoi(e) == 1) ? 1 : 0;
+        }
+        return u8 ? 3 : 0;
+    }
     return dtype == JX_F16 ? 2 : 1;
 }
 

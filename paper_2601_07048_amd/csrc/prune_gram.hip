@@ -34,6 +34,36 @@ namespace jx {
 
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef int gi32x16_t __attribute__((ext_vector_type(16)));
+typedef int gi32x4_t __attribute__((ext_vector_type(4)));
+
+// accumulator of a tile: float32, or int32 for uint8 vectors (v_mfma_i32_32x32x32_i8 on the values shifted by -128:
+// distances are translation invariant and everything stays an exact integer)
+template <int DT> struct GAcc { typedef f32x16_t type; };
+template <> struct GAcc<JX_U8> { typedef gi32x16_t type; };
+
+__device__ __forceinline__ uint4 shift128(uint4 x) {
+    x.x ^= 0x80808080u;
+    x.y ^= 0x80808080u;
+    x.z ^= 0x80808080u;
+    x.w ^= 0x80808080u;
+    return x;
+}
+// d(i,j) from G_ii, G_jj (held as raw bits in the float arrays) and G_ij, as the float the alpha test uses
+template <int DT, typename A>
+__device__ __forceinline__ float gram_dist(float ni, float nj, A gij) {
+    if constexpr (DT == JX_U8)
+        return (float)(uint32_t)(__float_as_int(ni) + __float_as_int(nj) - 2 * (int)gij);
+    else
+        return fmaxf((ni + nj) - 2.f * (float)gij, 0.f);
+}
+template <int DT, typename A>
+__device__ __forceinline__ float gram_store(A g) {
+    if constexpr (DT == JX_U8)
+        return __int_as_float((int)g);
+    else
+        return (float)g;
+}
 
 #define GP_WPB 4
 #define GP_MAX 128
@@ -61,7 +91,7 @@ __device__ __forceinline__ int gram_prune_wave(const uint8_t* recs, size_t strid
                                                bool have_dp, int R, float alpha) {
     constexpr int NTILE = NT * (NT + 1) / 2;
     const int lane = lane_id(), col = lane & 31, half = lane >> 5;
-    const bool extra = (DT == JX_F16) && !have_dp;
+    const bool extra = (DT != JX_F32) && !have_dp;
     const int Mx = M + (extra ? 1 : 0);
     const uint8_t* rp[NT];
     bool rv[NT];
@@ -73,15 +103,34 @@ __device__ __forceinline__ int gram_prune_wave(const uint8_t* recs, size_t strid
         const uint32_t id = i < M ? L->id[i] : p;
         rp[b] = recs + (size_t)id * stride;
     }
-    f32x16_t acc[NTILE];
+    typename GAcc<DT>::type acc[NTILE];
 #pragma unroll
     for (int t = 0; t < NTILE; t++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) acc[t][e] = 0.f;
+        for (int e = 0; e < 16; e++) acc[t][e] = 0;
 
     for (int p0 = 0; p0 < vec_bytes; p0 += 128) {
         const int off = p0 + half * 64;
-        if constexpr (DT == JX_F32) {
+        if constexpr (DT == JX_U8) {
+            uint4 f[NT][4];
+#pragma unroll
+            for (int b = 0; b < NT; b++)
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    const int o = off + s * 16;
+                    f[b][s] = make_uint4(0, 0, 0, 0);  // rows and bytes beyond the data: zero after the shift
+                    if (rv[b] && o < vec_bytes) f[b][s] = shift128(load16(rp[b] + o));
+                }
+#pragma unroll
+            for (int s = 0; s < 4; s++)
+#pragma unroll
+                for (int bi = 0; bi < NT; bi++)
+#pragma unroll
+                    for (int bj = bi; bj < NT; bj++)
+                        acc[gp_tile(NT, bi, bj)] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                            __builtin_bit_cast(gi32x4_t, f[bi][s]), __builtin_bit_cast(gi32x4_t, f[bj][s]),
+                            acc[gp_tile(NT, bi, bj)], 0, 0, 0);
+        } else if constexpr (DT == JX_F32) {
             float f[NT][16];
             float c[16];
 #pragma unroll
@@ -145,7 +194,7 @@ __device__ __forceinline__ int gram_prune_wave(const uint8_t* recs, size_t strid
             float dv = 0.f;
 #pragma unroll
             for (int e = 0; e < 16; e++)
-                if (e == ecol) dv = acc[gp_tile(NT, b, b)][e];
+                if (e == ecol) dv = gram_store<DT>(acc[gp_tile(NT, b, b)][e]);
             if (half == hcol) L->nrm[b * 32 + col] = dv;
         }
     }
@@ -158,7 +207,8 @@ __device__ __forceinline__ int gram_prune_wave(const uint8_t* recs, size_t strid
             for (int bj = bi; bj < NT; bj++)
                 if (bj == bv && col == cv) {
 #pragma unroll
-                    for (int e = 0; e < 16; e++) L->gv[bi * 32 + 8 * (e >> 2) + 4 * half + (e & 3)] = acc[gp_tile(NT, bi, bj)][e];
+                    for (int e = 0; e < 16; e++)
+                        L->gv[bi * 32 + 8 * (e >> 2) + 4 * half + (e & 3)] = gram_store<DT>(acc[gp_tile(NT, bi, bj)][e]);
                 }
     }
     wave_sync();
@@ -167,8 +217,10 @@ __device__ __forceinline__ int gram_prune_wave(const uint8_t* recs, size_t strid
             float d;
             if constexpr (DT == JX_F32)
                 d = L->nrm[j];
+            else if constexpr (DT == JX_U8)
+                d = gram_dist<DT>(L->nrm[M], L->nrm[j], __float_as_int(L->gv[j]));
             else
-                d = fmaxf(L->nrm[M] + L->nrm[j] - 2.f * L->gv[j], 0.f);
+                d = gram_dist<DT>(L->nrm[M], L->nrm[j], L->gv[j]);
             L->dp[j] = d;
             L->key[j] = ((uint64_t)__float_as_uint(d) << 32) | L->id[j];
         }
@@ -200,7 +252,7 @@ __device__ __forceinline__ int gram_prune_wave(const uint8_t* recs, size_t strid
                 const int i = r0 + 4 * half;
                 const float ni = L->nrm[i];
                 const float dpi = L->dp[i < M ? i : 0];
-                const float dij = fmaxf((ni + nj) - 2.f * acc[gp_tile(NT, bi, bj)][e], 0.f);
+                const float dij = gram_dist<DT>(ni, nj, acc[gp_tile(NT, bi, bj)][e]);
                 const float ad = __fmul_rn(alpha, dij);
                 const bool ok = i < M && j < M && i != j;
                 const uint64_t m1 = ballot(ok && ad <= dpj);
@@ -326,7 +378,7 @@ __global__ void __launch_bounds__(GP_WPB * 64) reverse_merge_gram_kernel(InsertA
         if (a.force_prune) deg = 0;
         if (!a.force_prune && deg + m <= a.R) continue;  // appended by the list-based kernel
         const int M = deg + m;
-        const int Mx = M + (DT == JX_F16 ? 1 : 0);
+        const int Mx = M + (DT != JX_F32 ? 1 : 0);
         if (Mx > GP_MAX) continue;  // left to the list-based kernel
         const int nt = Mx <= 64 ? 2 : (Mx + 31) >> 5;
         if (nt != NT) continue;
@@ -379,31 +431,42 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
     const uint8_t* pp = recs + (size_t)p * stride;
     // ---- pass 1: d(p, j) and G_jj.  float32: rows centred at p, so both are the same number
     float npp = 0.f;
-    if constexpr (DT == JX_F16) {
+    int ipp = 0;
+    if constexpr (DT != JX_F32) {
         for (int p0 = half * 64; p0 < vec_bytes; p0 += 128)
 #pragma unroll
             for (int s = 0; s < 4; s++) {
                 const int o = p0 + s * 16;
                 if (o < vec_bytes) {
-                    const uint4 x = load16(pp + o);
-                    npp = hdot2(x.x, x.x, npp);
-                    npp = hdot2(x.y, x.y, npp);
-                    npp = hdot2(x.z, x.z, npp);
-                    npp = hdot2(x.w, x.w, npp);
+                    if constexpr (DT == JX_F16) {
+                        const uint4 x = load16(pp + o);
+                        npp = hdot2(x.x, x.x, npp);
+                        npp = hdot2(x.y, x.y, npp);
+                        npp = hdot2(x.z, x.z, npp);
+                        npp = hdot2(x.w, x.w, npp);
+                    } else {
+                        const uint4 x = shift128(load16(pp + o));
+                        ipp = __builtin_amdgcn_sdot4((int)x.x, (int)x.x, ipp, false);
+                        ipp = __builtin_amdgcn_sdot4((int)x.y, (int)x.y, ipp, false);
+                        ipp = __builtin_amdgcn_sdot4((int)x.z, (int)x.z, ipp, false);
+                        ipp = __builtin_amdgcn_sdot4((int)x.w, (int)x.w, ipp, false);
+                    }
                 }
             }
         npp += shfl_xor(npp, 32);
+        ipp += shfl_xor(ipp, 32);
     }
     for (int b = 0; b < nb; b++) {
         const int i = b * 32 + col;
         const uint8_t* rp = recs + (size_t)(i < M ? L->id[i] : p) * stride;
         float nn = 0.f, np = 0.f;
+        int inn = 0, inp = 0;
         for (int p0 = half * 64; p0 < vec_bytes; p0 += 128)
 #pragma unroll
             for (int s = 0; s < 4; s++) {
                 const int o = p0 + s * 16;
                 if (o < vec_bytes) {
-                    const uint4 x = load16(rp + o), c = load16(pp + o);
+                    uint4 x = load16(rp + o), c = load16(pp + o);
                     if constexpr (DT == JX_F32) {
                         const float d0 = __uint_as_float(x.x) - __uint_as_float(c.x), d1 = __uint_as_float(x.y) - __uint_as_float(c.y);
                         const float d2 = __uint_as_float(x.z) - __uint_as_float(c.z), d3 = __uint_as_float(x.w) - __uint_as_float(c.w);
@@ -411,7 +474,7 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
                         nn = fmaf(d1, d1, nn);
                         nn = fmaf(d2, d2, nn);
                         nn = fmaf(d3, d3, nn);
-                    } else {
+                    } else if constexpr (DT == JX_F16) {
                         nn = hdot2(x.x, x.x, nn);
                         nn = hdot2(x.y, x.y, nn);
                         nn = hdot2(x.z, x.z, nn);
@@ -420,15 +483,32 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
                         np = hdot2(x.y, c.y, np);
                         np = hdot2(x.z, c.z, np);
                         np = hdot2(x.w, c.w, np);
+                    } else {
+                        x = shift128(x);
+                        c = shift128(c);
+                        inn = __builtin_amdgcn_sdot4((int)x.x, (int)x.x, inn, false);
+                        inn = __builtin_amdgcn_sdot4((int)x.y, (int)x.y, inn, false);
+                        inn = __builtin_amdgcn_sdot4((int)x.z, (int)x.z, inn, false);
+                        inn = __builtin_amdgcn_sdot4((int)x.w, (int)x.w, inn, false);
+                        inp = __builtin_amdgcn_sdot4((int)x.x, (int)c.x, inp, false);
+                        inp = __builtin_amdgcn_sdot4((int)x.y, (int)c.y, inp, false);
+                        inp = __builtin_amdgcn_sdot4((int)x.z, (int)c.z, inp, false);
+                        inp = __builtin_amdgcn_sdot4((int)x.w, (int)c.w, inp, false);
                     }
                 }
             }
         nn += shfl_xor(nn, 32);
         np += shfl_xor(np, 32);
+        inn += shfl_xor(inn, 32);
+        inp += shfl_xor(inp, 32);
         if (half == 0) {
-            L->nrm[i] = i < M ? nn : 0.f;
-            float d = nn;
+            float d = nn, nstore = nn;
             if constexpr (DT == JX_F16) d = fmaxf(npp + nn - 2.f * np, 0.f);
+            if constexpr (DT == JX_U8) {
+                d = (float)(uint32_t)(ipp + inn - 2 * inp);
+                nstore = __int_as_float(inn);
+            }
+            L->nrm[i] = i < M ? nstore : 0.f;
             // a new candidate keeps the distance it was sorted by
             if (i >= n_fixed && i < M) d = __uint_as_float((uint32_t)(new_keys[i - n_fixed] & 0xFFFFFFFFull));
             L->dp[i] = d;
@@ -447,11 +527,11 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
     }
     // ---- pass 2: block rows of the Gram matrix -> mask words
     for (int bi = 0; bi < nb; bi++) {
-        f32x16_t acc[GB_NB];
+        typename GAcc<DT>::type acc[GB_NB];
 #pragma unroll
         for (int t = 0; t < GB_NB; t++)
 #pragma unroll
-            for (int e = 0; e < 16; e++) acc[t][e] = 0.f;
+            for (int e = 0; e < 16; e++) acc[t][e] = 0;
         const uint8_t* rp[GB_NB];
         bool rv[GB_NB];
 #pragma unroll
@@ -509,7 +589,7 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
                 for (int s = 0; s < 4; s++) {
                     const int o = off + s * 16;
                     fa[s] = make_uint4(0, 0, 0, 0);
-                    if (rv[0] && o < vec_bytes) fa[s] = load16(rp[0] + o);
+                    if (rv[0] && o < vec_bytes) fa[s] = DT == JX_U8 ? shift128(load16(rp[0] + o)) : load16(rp[0] + o);
                 }
 #pragma unroll
                 for (int t = 0; t < GB_NB; t++) {
@@ -521,13 +601,18 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
                         fb[s] = fa[s];
                         if (t > 0) {
                             fb[s] = make_uint4(0, 0, 0, 0);
-                            if (rv[t] && o < vec_bytes) fb[s] = load16(rp[t] + o);
+                            if (rv[t] && o < vec_bytes) fb[s] = DT == JX_U8 ? shift128(load16(rp[t] + o)) : load16(rp[t] + o);
                         }
                     }
 #pragma unroll
-                    for (int s = 0; s < 4; s++)
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, fa[s]),
-                                                                        __builtin_bit_cast(f16x8_t, fb[s]), acc[t], 0, 0, 0);
+                    for (int s = 0; s < 4; s++) {
+                        if constexpr (DT == JX_U8)
+                            acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(gi32x4_t, fa[s]),
+                                                                           __builtin_bit_cast(gi32x4_t, fb[s]), acc[t], 0, 0, 0);
+                        else
+                            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, fa[s]),
+                                                                            __builtin_bit_cast(f16x8_t, fb[s]), acc[t], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -543,7 +628,7 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
                 const int r0 = bi * 32 + 8 * (e >> 2) + (e & 3);
                 const int i = r0 + 4 * half;
                 const float ni = L->nrm[i], dpi = L->dp[i];
-                const float dij = fmaxf((ni + nj) - 2.f * acc[t][e], 0.f);
+                const float dij = gram_dist<DT>(ni, nj, acc[t][e]);
                 const float ad = __fmul_rn(alpha, dij);
                 const bool ok = i < M && j < M && i != j;
                 const uint64_t m1 = ballot(ok && ad <= dpj);
@@ -636,7 +721,7 @@ __global__ void __launch_bounds__(GP_WPB * 64) reverse_merge_gram_big_kernel(Ins
         }
         if (a.force_prune) deg = 0;
         if (!a.force_prune && deg + m <= a.R) continue;
-        if (deg + m + (DT == JX_F16 ? 1 : 0) <= GP_MAX) continue;  // the one-pass kernels' share
+        if (deg + m + (DT != JX_F32 ? 1 : 0) <= GP_MAX) continue;  // the one-pass kernels' share
         if (deg > GB_MAX - 64) continue;                             // too little room for new candidates: list-based kernel
         const int mp = m < GB_MAX - deg ? m : GB_MAX - deg;          // new candidates in the pool (the closest ones)
         const int M = deg + mp;
@@ -679,10 +764,12 @@ static hipError_t launch_reverse_gram_dt(const InsertArgs& a, hipStream_t st) {
 
 hipError_t launch_forward_prune_gram(int dtype, const InsertArgs& a, hipStream_t st) {
     if (a.B <= 0) return hipSuccess;
+    if (dtype == JX_U8) return launch_forward_gram_dt<JX_U8>(a, st);
     return dtype == JX_F16 ? launch_forward_gram_dt<JX_F16>(a, st) : launch_forward_gram_dt<JX_F32>(a, st);
 }
 
 hipError_t launch_reverse_merge_gram(int dtype, const InsertArgs& a, hipStream_t st) {
+    if (dtype == JX_U8) return launch_reverse_gram_dt<JX_U8>(a, st);
     return dtype == JX_F16 ? launch_reverse_gram_dt<JX_F16>(a, st) : launch_reverse_gram_dt<JX_F32>(a, st);
 }
 

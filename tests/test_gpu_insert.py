@@ -171,3 +171,35 @@ def test_insert_errors(jx):
     assert g2.size()[0] == 9
     g2.insert(dev(x[:0]))      # empty insert is a no-op
     assert g2.size()[0] == 9
+
+
+def test_matrix_core_prune_on_uint8_variant():
+    """The matrix-core robustPrune also has a uint8 instantiation (int8 MFMA, exact integers).  It is slower than
+    the LDS-cached form for 128-byte vectors and therefore off by default (JX_GRAM_U8=1 switches it on, read once
+    per process): run it in a child process and require the oracle's graph bit for bit, build and consolidation."""
+    import os
+    import subprocess
+    import sys
+    code = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, 'tests')
+import oracle
+from paper_2601_07048_amd import jx
+from gpu_common import dev, u32, random_data
+for (n, d, R, L, growth) in ((3000, 128, 32, 64, 0.25), (2500, 64, 100, 128, 0.25), (5000, 32, 12, 24, 1.0)):
+    x = random_data(n, d, np.uint8, seed=n + R)
+    ref = oracle.Index(d, np.uint8, R, L, 1.2, n, batch_growth=growth)
+    ref.insert(x)
+    g = jx.Index(d, jx.U8, R, L, 1.2, capacity=n, max_batch=n, batch_growth=growth)
+    g.insert(dev(x))
+    assert g.size() == (n, ref.entry)
+    assert np.array_equal(u32(g.export_graph()[0]), ref.graph()[0]), 'build'
+    dele = np.random.default_rng(n).choice(n, n // 3, replace=False).astype(np.uint32)
+    ref.delete(dele); g.delete(dev(dele)); ref.consolidate(); g.consolidate()
+    assert np.array_equal(u32(g.export_graph()[0]), ref.graph()[0]), 'consolidate'
+print('variant ok')
+"""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, JX_GRAM_U8="1")
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
