@@ -51,7 +51,7 @@ extern "C" {
 /* rule that picks the m-bit code for m > 1 (Sec. 5.1 says only "simple scalar
  * quantization") */
 #define JX_RULE_MAXCOS 0 /* the grid point whose direction is closest to r ("extended" codes): exact sweep
-                           over the breakpoints of the grid scale; 2- and 4-bit codes with dim * (2^(m-1) - 1) <= 8192 */
+                           over the breakpoints of the grid scale; 2- and 4-bit codes with dim * (2^(m-1) - 1) <= 8192, dim <= 4096 */
 #define JX_RULE_MAXABS 1 /* grid scale t = (2^(m-1) - 1/2) / max_i |r_i| */
 
 /* error codes */

@@ -700,8 +700,8 @@ int jx_quantize(jx_index* idx, int32_t bits, const float* d_rotation, const floa
     if (bits != p.quant_bits) return fail(JX_EINVAL, "bits must equal params.quant_bits (%d)", p.quant_bits);
     if (query_bits != 4 && query_bits != 8) return fail(JX_EINVAL, "query_bits must be 4 or 8");
     if (rule != JX_RULE_MAXABS && rule != JX_RULE_MAXCOS) return fail(JX_EINVAL, "unknown code rule");
-    if (rule == JX_RULE_MAXCOS && bits > 1 && (bits == 8 || p.dim * ((1 << (bits - 1)) - 1) > 8192))
-        return fail(JX_EINVAL, "JX_RULE_MAXCOS supports 2- and 4-bit codes with dim * (2^(bits-1) - 1) <= 8192; use JX_RULE_MAXABS");
+    if (rule == JX_RULE_MAXCOS && bits > 1 && (bits == 8 || p.dim * ((1 << (bits - 1)) - 1) > 8192 || p.dim > 4096))
+        return fail(JX_EINVAL, "JX_RULE_MAXCOS supports 2- and 4-bit codes with dim * (2^(bits-1) - 1) <= 8192 and dim <= 4096; use JX_RULE_MAXABS");
     if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
     hipStream_t st = as_stream(stream);
     JX_HIP(hipMemcpyAsync(idx->d_P, d_rotation, (size_t)p.dim * p.dim * 4, hipMemcpyDeviceToDevice, st));

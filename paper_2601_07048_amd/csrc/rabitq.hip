@@ -191,13 +191,17 @@ __global__ void __launch_bounds__(256) encode_kernel(EncodeArgs a) {
 }
 
 // ---- max-cosine rule (m > 1): the grid point whose direction is closest to r.
-// One workgroup per vector.  The breakpoints t = j/|r_i| (j = 1 .. 2^(m-1)-1),
-// where coordinate i steps to level j, are sorted in LDS (bitonic network on the
-// double-precision keys); prefix sums in sorted order give <xbar,|r|> and
-// ||xbar||^2 after every breakpoint; the cosine is evaluated at the end of every
-// group of equal t and the first maximum wins (smallest t).  The level of a
-// coordinate is then the number of its own breakpoints that are <= t.
-#define MC_CAP 8192
+// One workgroup per vector.  The grid scale t steps coordinate i to level j at the breakpoint t = j/|r_i|
+// (j = 1 .. 2^(m-1)-1); after the breakpoints <= t have been applied,
+//     <xbar,|r|> = l1/2 + sum_j PrefA[cnt_j(t)],   ||xbar||^2 = d/4 + sum_j 2j cnt_j(t),
+// where cnt_j(t) counts the level-j breakpoints <= t and PrefA are prefix sums of the magnitudes in descending
+// order.  So only the d magnitudes are sorted (bitonic network in LDS); the level-j breakpoints j/|r|_(p) are then
+// already ascending in p, their quotients are tabulated once in double (comparisons are on the very values the
+// definition compares), and every breakpoint evaluates its cosine with one binary search per level: the state at
+// the end of its group of equal t.  The largest cosine wins, the smallest t among equals, and t -> 0+ competes.  The
+// level of a coordinate is then the number of its own breakpoints that are <= t.
+#define MC_CAP 8192   // breakpoints per vector
+#define MC_DMAX 4096  // dimensions
 
 __device__ __forceinline__ double block_scan_incl(double v, double* ws, int tid) {
     // inclusive scan over the 256 threads of the workgroup
@@ -217,110 +221,112 @@ __device__ __forceinline__ double block_scan_incl(double v, double* ws, int tid)
 
 __global__ void __launch_bounds__(256) encode_maxcos_kernel(EncodeArgs a) {
     extern __shared__ __align__(16) unsigned char dyn[];
-    double* key = reinterpret_cast<double*>(dyn);                       // [MC_CAP]
-    uint16_t* pay = reinterpret_cast<uint16_t*>(key + MC_CAP);          // [MC_CAP] (i << 3) | j
+    const int half = 1 << (a.bits - 1), nl = half - 1;
+    int dpad = 256;
+    while (dpad < a.d) dpad <<= 1;
+    float* sa = reinterpret_cast<float*>(dyn);                          // [dpad] magnitudes, descending
+    double* pref = reinterpret_cast<double*>(dyn + (size_t)dpad * 4);   // [dpad + 1] prefix sums of sa
+    double* Q = pref + dpad + 2;                                        // [nl][d] quotients j / sa[p]
     __shared__ double ws[8];
-    __shared__ double red_c[256];
-    __shared__ int red_k[256];
+    __shared__ double red_c[256], red_t[256];
+    __shared__ int s_npos;
     __shared__ double s_l1, s_l2, s_ip, s_best_t;
     const int tid = threadIdx.x;
     const long long v = blockIdx.x;
     const float* r = a.rot + (size_t)v * a.d;
     uint8_t* code = a.codes + (size_t)v * a.code_stride;
-    const int half = 1 << (a.bits - 1);
-    const int nbp = a.d * (half - 1);
 
-    // ---- sums and breakpoints
+    // ---- sums, magnitudes
     double l1 = 0.0, l2 = 0.0;
     for (int i = tid; i < a.d; i += 256) {
         const double x = fabs((double)r[i]);
         l1 += x;
         l2 += x * x;
     }
-    for (int e = tid; e < MC_CAP; e += 256) {
-        double t = __builtin_inf();
-        uint16_t p = 0xFFFF;
-        if (e < nbp) {
-            const int i = e / (half - 1), j = e % (half - 1) + 1;
-            const double x = fabs((double)r[i]);
-            if (x > 0.0) {
-                t = (double)j / x;
-                p = (uint16_t)((i << 3) | j);
-            }
-        }
-        key[e] = t;
-        pay[e] = p;
+    int npos_t = 0;
+    for (int e = tid; e < dpad; e += 256) {
+        const float x = e < a.d ? fabsf(r[e]) : 0.f;
+        sa[e] = x;
+        npos_t += x > 0.f ? 1 : 0;
     }
     {   // block sums (fixed order)
         const double t1 = block_scan_incl(l1, ws, tid);
         if (tid == 255) s_l1 = t1;
         const double t2 = block_scan_incl(l2, ws, tid);
         if (tid == 255) s_l2 = t2;
+        const double t3 = block_scan_incl((double)npos_t, ws, tid);
+        if (tid == 255) s_npos = (int)t3;
     }
     __syncthreads();
-    // ---- bitonic sort by (t, payload)
-    for (int k = 2; k <= MC_CAP; k <<= 1) {
+    // ---- bitonic sort, descending
+    for (int k = 2; k <= dpad; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int e = tid; e < MC_CAP / 2; e += 256) {
+            for (int e = tid; e < dpad / 2; e += 256) {
                 const int lo = ((e & ~(j - 1)) << 1) | (e & (j - 1));
                 const int hi = lo | j;
-                const bool up = (lo & k) == 0;
-                const double tl = key[lo], th = key[hi];
-                const uint16_t pl = pay[lo], ph = pay[hi];
-                const bool gt = tl > th || (tl == th && pl > ph);
-                if (gt == up) {
-                    key[lo] = th;
-                    key[hi] = tl;
-                    pay[lo] = ph;
-                    pay[hi] = pl;
+                const bool down = (lo & k) == 0;
+                const float xl = sa[lo], xh = sa[hi];
+                if ((xl < xh) == down) {
+                    sa[lo] = xh;
+                    sa[hi] = xl;
                 }
             }
             __syncthreads();
         }
     }
-    // ---- prefix sums in sorted order: thread t owns the 32 consecutive entries [32t, 32t+32)
-    constexpr int PER = MC_CAP / 256;
-    const int e0 = tid * PER;
-    double sa = 0.0, sn = 0.0;
-    for (int e = e0; e < e0 + PER; e++) {
-        const uint16_t p = pay[e];
-        if (p != 0xFFFF) {
-            sa += fabs((double)r[p >> 3]);
-            sn += 2.0 * (double)(p & 7);
+    const int npos = s_npos;  // the zeros sit behind the npos positive magnitudes
+    // ---- prefix sums (thread t owns dpad/256 consecutive entries) and the quotient lists
+    {
+        const int PER = dpad / 256, e0 = tid * PER;
+        double loc = 0.0;
+        for (int e = e0; e < e0 + PER; e++) loc += (double)sa[e];
+        double run = block_scan_incl(loc, ws, tid) - loc;
+        if (tid == 0) pref[0] = 0.0;
+        for (int e = e0; e < e0 + PER; e++) {
+            run += (double)sa[e];
+            pref[e + 1] = run;
         }
     }
-    const double off_a = block_scan_incl(sa, ws, tid) - sa;
-    const double off_n = block_scan_incl(sn, ws, tid) - sn;
+    for (int e = tid; e < nl * npos; e += 256) {
+        const int j = e / npos + 1, p = e - (j - 1) * npos;
+        Q[(size_t)(j - 1) * a.d + p] = (double)j / (double)sa[p];
+    }
+    __syncthreads();
+    // ---- every breakpoint evaluates the cosine at the end of its group of equal t
     const double ip0 = 0.5 * s_l1, nn0 = 0.25 * (double)a.d;
-    double best = -1.0;
-    int best_k = 0x7FFFFFFF;
-    {
-        double ca = off_a, cn = off_n;
-        for (int e = e0; e < e0 + PER; e++) {
-            const uint16_t p = pay[e];
-            if (p == 0xFFFF) break;
-            ca += fabs((double)r[p >> 3]);
-            cn += 2.0 * (double)(p & 7);
-            const bool last_of_group = (e + 1 >= MC_CAP) || key[e + 1] != key[e];
-            if (last_of_group) {
-                const double c = (ip0 + ca) / sqrt(nn0 + cn);
-                if (c > best) {
-                    best = c;
-                    best_k = e;
-                }
+    double best = -1.0, best_t = __builtin_inf();
+    for (int e = tid; e < nl * npos; e += 256) {
+        const int j = e / npos, p = e - j * npos;
+        const double t = Q[(size_t)j * a.d + p];
+        double ip = ip0, nn = nn0;
+        for (int jj = 0; jj < nl; jj++) {
+            const double* q = Q + (size_t)jj * a.d;
+            int lo = 0, hi = npos;  // number of level-(jj+1) breakpoints <= t
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (q[mid] <= t)
+                    lo = mid + 1;
+                else
+                    hi = mid;
             }
+            ip += pref[lo];
+            nn += 2.0 * (double)(jj + 1) * (double)lo;
+        }
+        const double c = ip / sqrt(nn);
+        if (c > best || (c == best && t < best_t)) {
+            best = c;
+            best_t = t;
         }
     }
     red_c[tid] = best;
-    red_k[tid] = best_k;
+    red_t[tid] = best_t;
     __syncthreads();
     for (int s = 128; s > 0; s >>= 1) {
         if (tid < s) {
-            const double oc = red_c[tid + s];
-            const int ok = red_k[tid + s];
-            if (oc > red_c[tid] || (oc == red_c[tid] && ok < red_k[tid])) {
+            const double oc = red_c[tid + s], ot = red_t[tid + s];
+            if (oc > red_c[tid] || (oc == red_c[tid] && ot < red_t[tid])) {
                 red_c[tid] = oc;
-                red_k[tid] = ok;
+                red_t[tid] = ot;
             }
         }
         __syncthreads();
@@ -328,7 +334,7 @@ __global__ void __launch_bounds__(256) encode_maxcos_kernel(EncodeArgs a) {
     if (tid == 0) {
         // the all-zero-level grid (t -> 0+) competes too; a later cosine must be strictly larger
         const double c0 = ip0 / sqrt(nn0);
-        s_best_t = (red_k[0] != 0x7FFFFFFF && red_c[0] > c0) ? key[red_k[0]] : 0.0;
+        s_best_t = (npos > 0 && nl > 0 && red_c[0] > c0) ? red_t[0] : 0.0;
     }
     __syncthreads();
     const double bt = s_best_t;
@@ -365,8 +371,11 @@ __global__ void __launch_bounds__(256) encode_maxcos_kernel(EncodeArgs a) {
 hipError_t launch_encode(const EncodeArgs& a, hipStream_t st) {
     if (a.n <= 0) return hipSuccess;
     if (a.bits > 1 && a.rule == JX_RULE_MAXCOS) {
-        if ((a.bits != 4 && a.bits != 2) || a.d * ((1 << (a.bits - 1)) - 1) > MC_CAP) return hipErrorInvalidValue;
-        const size_t sh = (size_t)MC_CAP * (8 + 2);
+        const int nl = (1 << (a.bits - 1)) - 1;
+        if ((a.bits != 4 && a.bits != 2) || a.d * nl > MC_CAP || a.d > MC_DMAX) return hipErrorInvalidValue;
+        int dpad = 256;
+        while (dpad < a.d) dpad <<= 1;
+        const size_t sh = (size_t)dpad * 4 + (size_t)(dpad + 2) * 8 + (size_t)nl * a.d * 8;
         hipError_t e = hipFuncSetAttribute((const void*)encode_maxcos_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(encode_maxcos_kernel, dim3((unsigned)a.n), dim3(256), sh, st, a);

@@ -152,7 +152,7 @@ class Index:
     def quantize(self, bits, rotation, centroid=None, query_bits=8, rule=None):
         assert rotation.dtype == torch.float32 and rotation.shape == (self.dim, self.dim)
         if rule is None:  # the max-cosine rule where the library offers it
-            rule = RULE_MAXCOS if (bits in (2, 4) and self.dim * ((1 << (bits - 1)) - 1) <= 8192) else RULE_MAXABS
+            rule = RULE_MAXCOS if (bits in (2, 4) and self.dim * ((1 << (bits - 1)) - 1) <= 8192 and self.dim <= 4096) else RULE_MAXABS
         with torch.cuda.device(self.device):
             _check(_lib.jx_quantize(self._h, C.c_int32(bits), _ptr(rotation), _ptr(centroid), C.c_int32(query_bits),
                                     C.c_int32(rule), _stream()))
