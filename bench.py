@@ -340,7 +340,7 @@ def main():
         qps_comp = timed_qps()
         cfg["delete"] = {"fraction": args.delete_frac, "deleted": int(victims.size), "mark_ms": round(t_mark * 1e3, 3),
                          "consolidate_s": round(t_cons, 3), "consolidate_vertices_per_s": round(n / t_cons, 1),
-                         "compact_s": round(t_comp, 3),
+                         "compact_s": round(t_comp, 4),
                          "recall_at_10": {"before": round(rec, 4), "marked": round(rec_marked, 4), "consolidated": round(rec_after, 4),
                                           "compacted": round(rec_comp, 4)},
                          "queries_per_s": {"before": round(qps_before, 1), "marked": round(qps_marked, 1),
