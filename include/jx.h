@@ -257,7 +257,9 @@ int jx_export_graph(jx_index* idx, uint32_t* d_adj, uint32_t* d_deg, void* strea
 
 /* Replace the index content by n vectors and a ready-made graph (used to
  * search a graph built elsewhere, e.g. by a reference implementation).
- * Rows must be filled from the left and padded with JX_NONE. */
+ * Rows must be filled from the left and padded with JX_NONE, ids must be
+ * below n: the table is checked on the device first (the call synchronises)
+ * and JX_EINVAL leaves the index untouched. */
 int jx_import_graph(jx_index* idx, const void* d_vecs, int64_t n, const uint32_t* d_adj, uint32_t entry_id,
                     void* stream);
 

@@ -255,6 +255,23 @@ __global__ void row_degrees_kernel(const uint32_t* adj, long long n, int R, uint
     deg[i] = (uint32_t)g;
 }
 
+// adjacency table handed in from outside: every entry must be a vertex id below n or the padding value, and a row
+// must be filled from the left (the kernels stop at the first padding entry); counts the offending entries
+__global__ void validate_adj_kernel(const uint32_t* adj, long long n, int R, uint32_t* bad) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n * R) return;
+    const uint32_t v = adj[i];
+    if (v == JX_NONE_ID) return;
+    const bool gap = (i % R) > 0 && adj[i - 1] == JX_NONE_ID;
+    if (v >= (unsigned long long)n || gap) atomicAdd(bad, 1u);
+}
+
+hipError_t launch_validate_adj(const uint32_t* adj, long long n, int R, uint32_t* bad, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(validate_adj_kernel, dim3((unsigned)((n * R + 255) / 256)), dim3(256), 0, st, adj, n, R, bad);
+    return hipGetLastError();
+}
+
 hipError_t launch_row_degrees(const uint32_t* adj, long long n, int R, uint32_t* deg, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(row_degrees_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, adj, n, R, deg);

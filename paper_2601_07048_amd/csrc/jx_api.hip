@@ -301,6 +301,15 @@ int jx_import_graph(jx_index* idx, const void* d_vecs, int64_t n, const uint32_t
     if (n < 1 || n > idx->p.capacity) return fail(JX_ECAPACITY, "n = %lld exceeds capacity", (long long)n);
     if (entry_id >= (uint64_t)n) return fail(JX_EINVAL, "entry id out of range");
     hipStream_t st = as_stream(stream);
+    {   // a table with ids out of range would send the search kernels out of bounds: check it before it is installed
+        uint32_t* d_bad = (uint32_t*)(idx->d_stats + 10);
+        uint32_t bad = 0;
+        JX_HIP(jx::launch_fill_u32(d_bad, 1, 0u, st));
+        JX_HIP(jx::launch_validate_adj(d_adj, n, idx->p.R, d_bad, st));
+        JX_HIP(hipMemcpyAsync(&bad, d_bad, 4, hipMemcpyDeviceToHost, st));
+        JX_HIP(hipStreamSynchronize(st));
+        if (bad) return fail(JX_EINVAL, "%u adjacency entries are out of range or follow a padding entry", bad);
+    }
     JX_HIP(hipMemcpyAsync(idx->d_vecs, d_vecs, (size_t)n * idx->vec_bytes, hipMemcpyDeviceToDevice, st));
     JX_HIP(hipMemcpyAsync(idx->d_adj, d_adj, (size_t)n * idx->p.R * 4, hipMemcpyDeviceToDevice, st));
     if (n < idx->n) JX_HIP(jx::launch_fill_u32(idx->d_adj + (size_t)n * idx->p.R, (idx->n - n) * idx->p.R, JX_NONE, st));

@@ -175,6 +175,7 @@ hipError_t launch_mips_augment(const float* in, long long n, int dim, float max_
                                float* norm_out, hipStream_t st);
 hipError_t launch_gather_probe(const uint8_t* table, int rec_bytes, const uint32_t* ids, long long n_ids, int blocks,
                                uint32_t* sink, hipStream_t st);
+hipError_t launch_validate_adj(const uint32_t* adj, long long n, int R, uint32_t* bad, hipStream_t st);
 hipError_t launch_row_degrees(const uint32_t* adj, long long n, int R, uint32_t* deg, hipStream_t st);
 
 }  // namespace jx

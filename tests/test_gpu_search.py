@@ -190,3 +190,22 @@ def test_bruteforce_parity(jx, dtype, n, d, k):
         assert np.allclose(dist[fin], rd[fin], rtol=1e-4)
         assert np.array_equal(np.isfinite(dist), fin)
         assert (ids == rid).mean() > 0.99
+
+
+def test_import_graph_rejects_a_bad_table(jx):
+    """Ids out of range or a row with a gap would send the kernels out of bounds: refused, index unchanged."""
+    x = random_data(300, 32, np.uint8, seed=1)
+    ix = oracle_index(x, 8, 16)
+    g = gpu_index_from_oracle(jx, x, ix, 8, 16)
+    adj, _ = ix.graph()
+    for bad in ("range", "gap"):
+        a = adj.copy()
+        if bad == "range":
+            a[7, 0] = 300
+        else:
+            a[9, :] = [5, 0xFFFFFFFF, 6, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF]
+        with pytest.raises(jx.JxError) as e:
+            g.import_graph(dev(x), dev(a), ix.entry)
+        assert e.value.code == -1
+    got, _ = g.export_graph()
+    assert np.array_equal(u32(got), adj)
