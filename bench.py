@@ -29,7 +29,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of one timed launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command
 # (profiles/beam_search_u8_N1M_L96.md); reported only when the run has the same shape.
-MEASURED_TRAFFIC = {(2, 1_000_000, 10_000, 96): 2.737e9 + 7.07e6}
+MEASURED_TRAFFIC = {(2, 1_000_000, 10_000, 96): 2.737e9 + 7.07e6,
+                    (3, 1_000_000, 10_000, 512): 4.765e10 + 3.85e6,   # profiles/build_search_f32_d960_4bit_N1M.md
+                    (4, 1_000_000, 10_000, 512): 2.087e10 + 3.85e6}   # profiles/build_search_f32_d1536_1bit_N1M.md
 
 SPEC = {
     2: dict(d=128, u8=True, bits=0, sweep=[16, 24, 32, 48, 64, 96, 128, 256], kernel="beam_search_kernel<u8>",
@@ -252,7 +254,7 @@ def main():
     alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * qrec + nq * out_k * 8
     achieved = alg_bytes / (beam_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": sp["kernel"], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((wl, n, nq, L_star)),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((wl, n, nq, L_star)) if not args.bits else None,
                 "bytes_per_launch": int(alg_bytes), "kernel_ms": round(beam_ms, 4),
                 "hops_per_query": round(st["hops"] / nq, 1), "dist_evals_per_query": round(st["dist_evals"] / nq, 1),
                 "stage_ms": {k2: round(v, 4) for k2, v in stage.items()},
