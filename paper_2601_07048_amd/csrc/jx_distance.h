@@ -97,22 +97,14 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
     constexpr int G = 64 / T;
     uint4 data[U][CPL];
     uint32_t ids[U];
-#ifndef JX_IDS_LAZY
 #pragma unroll
     for (int u = 0; u < U; u++) {
         int c = s0 + u * G + g;
         ids[u] = cand_id[c < n_new ? c : n_new - 1];
     }
-#endif
 #pragma unroll
     for (int u = 0; u < U; u++) {
         if (s0 + u * G < n_new) {  // wave-uniform
-#ifdef JX_IDS_LAZY
-            {
-                int c = s0 + u * G + g;
-                ids[u] = cand_id[c < n_new ? c : n_new - 1];
-            }
-#endif
 #pragma unroll
             for (int j = 0; j < CPL; j++) {
                 int ch = lig + T * j;
