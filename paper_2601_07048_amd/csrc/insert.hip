@@ -25,7 +25,9 @@
 
 namespace jx {
 
-#define INS_WPB 4      // wavefronts per workgroup
+#ifndef INS_WPB
+#define INS_WPB 1      // wavefronts per workgroup (they never cooperate: a slot is free as soon as its wavefront ends)
+#endif
 #define INS_RA JX_MAX_R
 
 // ------------------------------------------------------------------ entry point
@@ -700,7 +702,8 @@ static hipError_t launch_prune_pair(bool forward, const InsertArgs& a, hipStream
         hipLaunchKernelGGL((forward_prune_kernel<KIND, T, CPL>), grid, dim3(INS_WPB * 64), sh, st, a);
     } else {
         long long want = ((a.E ? a.E : a.B * a.R) + INS_WPB - 1) / INS_WPB;
-        unsigned grid = (unsigned)(want < 4096 ? (want < 1 ? 1 : want) : 4096);
+        const long long cap = 16384 / INS_WPB;  // persistent wavefronts, segments dealt round-robin
+        unsigned grid = (unsigned)(want < cap ? (want < 1 ? 1 : want) : cap);
         hipLaunchKernelGGL((reverse_merge_kernel<KIND, T, CPL>), dim3(grid), dim3(INS_WPB * 64),
                            (size_t)INS_WPB * a.vec_cache_bytes, st, a);
     }

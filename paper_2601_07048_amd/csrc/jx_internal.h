@@ -5,7 +5,7 @@
 #include "../../include/jx.h"
 
 #ifndef JX_BEAM_WPB
-#define JX_BEAM_WPB 4  // wavefronts (= queries) per workgroup of the beamSearch kernel
+#define JX_BEAM_WPB 1  // wavefronts (= queries) per workgroup of the beamSearch kernel: a slot is free again as soon as its query ends
 #endif
 
 namespace jx {

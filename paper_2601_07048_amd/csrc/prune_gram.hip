@@ -65,7 +65,9 @@ __device__ __forceinline__ float gram_store(A g) {
         return (float)g;
 }
 
-#define GP_WPB 4
+#ifndef GP_WPB
+#define GP_WPB 1  // wavefronts per workgroup (independent of each other)
+#endif
 #define GP_MAX 128
 
 struct GramLds {
@@ -749,15 +751,16 @@ static hipError_t launch_forward_gram_dt(const InsertArgs& a, hipStream_t st) {
 template <int DT>
 static hipError_t launch_reverse_gram_dt(const InsertArgs& a, hipStream_t st) {
     long long want = ((a.E ? a.E : a.B * a.R) + GP_WPB - 1) / GP_WPB;
-    dim3 grid((unsigned)(want < 2048 ? (want < 1 ? 1 : want) : 2048)), block(GP_WPB * 64);
+    const long long cap = 8192 / GP_WPB;  // persistent wavefronts, segments dealt round-robin
+    dim3 grid((unsigned)(want < cap ? (want < 1 ? 1 : want) : cap)), block(GP_WPB * 64);
     hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 2>), grid, block, 0, st, a);
     hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 3>), grid, block, 0, st, a);
     hipLaunchKernelGGL((reverse_merge_gram_kernel<DT, 4>), grid, block, 0, st, a);
-    {   // 129 .. 256 candidates: few and long, 4 wavefronts per workgroup with 27 KB of LDS each
+    {   // 129 .. 256 candidates: few and long, 27 KB of LDS per wavefront
         const size_t sh = sizeof(GramBigLds) * GP_WPB;
         hipError_t e = hipFuncSetAttribute((const void*)reverse_merge_gram_big_kernel<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((reverse_merge_gram_big_kernel<DT>), dim3(grid.x < 1024 ? grid.x : 1024), block, sh, st, a);
+        hipLaunchKernelGGL((reverse_merge_gram_big_kernel<DT>), dim3(grid.x < 4096 / GP_WPB ? grid.x : 4096 / GP_WPB), block, sh, st, a);
     }
     return hipGetLastError();
 }
