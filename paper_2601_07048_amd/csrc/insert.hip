@@ -350,6 +350,93 @@ __device__ __forceinline__ int prune_cached_u8_mfma(PruneLds* L, const unsigned 
     return nsel;
 }
 
+// robustPrune of a row that is mostly the output of an earlier robustPrune call
+// (uint8 vectors of 128 bytes, all M <= 128 candidates merged and sorted in
+// L->a_key, their vectors cached in LDS, L->a_dead[i] = 1 marks the entries that
+// were NOT selected together by that call: appended since, or new).
+//
+// Two entries that one call selected, i before j, satisfy "i does not discard j":
+// otherwise j would not have been selected.  Distances on uint8 data are exact
+// integers and alpha is fixed, so the same test gives the same answer now, and
+// only pairs with a marked entry have to be evaluated.  Marked entries are taken
+// in sorted order; when one is reached every earlier entry has its final state,
+// because only marked entries before it could have discarded anything.  An entry
+// beyond the R-th selected one is never output, so neither what it discards nor
+// whether it is discarded matters.
+template <int T, int CPL>
+__device__ __forceinline__ int prune_cached_u8_incremental(const DistSrc& cds, PruneLds* L, int M, int R, float alpha) {
+    constexpr int G = 64 / T;
+    constexpr int U0 = (8 / CPL) > 0 ? (8 / CPL) : 1;
+    constexpr int U = U0 < (64 / G) ? U0 : (64 / G);
+    const int lane = lane_id();
+    const int g = lane / T, lig = lane % T;
+    uint64_t dm[2], alive[2];
+    dm[0] = ballot(lane < M && L->a_dead[lane] != 0);
+    dm[1] = ballot(lane + 64 < M && L->a_dead[lane + 64] != 0);
+    alive[0] = M >= 64 ? ~0ull : ((1ull << M) - 1ull);
+    alive[1] = M <= 64 ? 0ull : (M >= 128 ? ~0ull : ((1ull << (M - 64)) - 1ull));
+    QueryRegs<K_U8, CPL, 0> q;
+    while (dm[0] | dm[1]) {
+        int t;
+        if (dm[0]) {
+            t = __builtin_ctzll(dm[0]);
+            dm[0] &= dm[0] - 1ull;
+        } else {
+            t = 64 + __builtin_ctzll(dm[1]);
+            dm[1] &= dm[1] - 1ull;
+        }
+        if (((alive[t >> 6] >> (t & 63)) & 1ull) == 0ull) continue;  // discarded by an earlier marked entry
+        const float dvt = __uint_as_float((uint32_t)(L->a_key[t] >> 32));
+        load_query<K_U8, T, CPL, 0>(q, cds, (int64_t)t, lig);
+        uint64_t rk[2] = {0ull, 0ull}, ck[2] = {0ull, 0ull};
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int c0 = h * 64;
+            if (c0 >= M) break;
+            const int nn = M - c0 < 64 ? M - c0 : 64;
+            if (lane < nn) L->cand_id[lane] = (uint32_t)(c0 + lane);
+            wave_sync();
+            for (int s0 = 0; s0 < nn; s0 += G * U)
+                eval_batch<K_U8, T, CPL, 0, U>(q, cds, s0, nn, L->cand_id, L->cand_key, g, lig);
+            wave_sync();
+            const int j = c0 + lane;
+            bool rkill = false, ckill = false;
+            if (lane < nn) {
+                const float d1 = (float)key_dist(L->cand_key[lane]);
+                const float dvj = __uint_as_float((uint32_t)(L->a_key[j] >> 32));
+                rkill = j > t && __fmul_rn(alpha, d1) <= dvj;  // t discards j
+                ckill = j < t && __fmul_rn(alpha, d1) <= dvt;  // j, if selected, discards t
+            }
+            rk[h] = ballot(rkill);
+            ck[h] = ballot(ckill);
+            wave_sync();
+        }
+        if ((ck[0] & alive[0]) | (ck[1] & alive[1])) {
+            alive[t >> 6] &= ~(1ull << (t & 63));
+        } else {
+            alive[0] &= ~rk[0];
+            alive[1] &= ~rk[1];
+        }
+    }
+    const int n0 = __builtin_popcountll(alive[0]);
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const int j = h * 64 + lane;
+        if (j < M && ((alive[h] >> lane) & 1ull)) {
+            const int pos = (h ? n0 : 0) + __builtin_popcountll(alive[h] & ((1ull << lane) - 1ull));
+            if (pos < R) {
+                const uint64_t k = L->a_key[j];
+                L->sel_id[pos] = (uint32_t)k;
+                L->sel_dist[pos] = (uint32_t)(k >> 32);
+            }
+        }
+    }
+    wave_sync();
+    const int total = n0 + __builtin_popcountll(alive[1]);
+    return total < R ? total : R;
+}
+
+
 template <int KIND, int T, int CPL>
 __global__ void __launch_bounds__(INS_WPB * 64) forward_prune_kernel(InsertArgs a) {
     __shared__ PruneLds lds[INS_WPB];
@@ -402,6 +489,7 @@ __global__ void __launch_bounds__(INS_WPB * 64) forward_prune_kernel(InsertArgs 
         a.keys[(size_t)i * a.R + j] = on ? (((uint64_t)v << 32) | L->sel_dist[j]) : JX_EMPTY_KEY;
         a.vals[(size_t)i * a.R + j] = on ? (uint32_t)xid : JX_NONE_ID;
     }
+    if (a.clean && lane == 0) a.clean[xid] = (uint8_t)(nsel < 255 ? nsel : 255);
 }
 
 template <int KIND, int T, int CPL>
@@ -438,6 +526,8 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
             deg += __builtin_popcountll(ballot(on));
         }
         if (a.force_prune) deg = 0;  // consolidation: the segment holds the whole candidate set
+        int nclean = (a.clean && !a.force_prune) ? (int)a.clean[v] : 0;
+        if (nclean > deg) nclean = deg;
         if (!a.force_prune && deg + m <= a.R) {
             for (int j = lane; j < m; j += 64) row[deg + j] = a.vals[lo + j];
             continue;
@@ -470,12 +560,17 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
             wave_sync();
         }
         const int nsort = cached ? M : deg;
+        // few entries besides those one earlier call selected together: only their pairs need evaluating
+        const bool incremental = KIND == K_U8 && cached && a.ds.rec_stride == 128 && M <= 128 && M - nclean <= 12 && nclean > 0;
         for (int j = lane; j < nsort; j += 64) {
             const uint64_t k = L->a_tmp[j];
             int rank = 0;
             for (int t = 0; t < nsort; t++) rank += (L->a_tmp[t] < k) ? 1 : 0;
             L->a_key[rank] = k;
-            L->a_dead[j] = 0;
+            if (incremental)
+                L->a_dead[rank] = j >= nclean ? 1 : 0;
+            else
+                L->a_dead[j] = 0;
         }
         int nsel;
         if (cached) {
@@ -499,9 +594,14 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
             none.dead = nullptr;
             __threadfence_block();
             wave_sync();
-            if (KIND == K_U8 && a.ds.rec_stride == 128 && M <= 128 && (long long)((M + 31) & ~31) * 128 <= a.vec_cache_bytes)
-                nsel = prune_cached_u8_mfma(L, vc, M, a.R, a.alpha);
-            else
+            if constexpr (KIND == K_U8) {
+                if (incremental)
+                    nsel = prune_cached_u8_incremental<T, CPL>(cds, L, M, a.R, a.alpha);
+                else if (a.ds.rec_stride == 128 && M <= 128 && (long long)((M + 31) & ~31) * 128 <= a.vec_cache_bytes)
+                    nsel = prune_cached_u8_mfma(L, vc, M, a.R, a.alpha);
+                else
+                    nsel = robust_prune_wave<KIND, T, CPL, true>(cds, L, M, none, a.R, a.alpha);
+            } else
                 nsel = robust_prune_wave<KIND, T, CPL, true>(cds, L, M, none, a.R, a.alpha);
         } else {
             BList B;
@@ -517,6 +617,7 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
             nsel = robust_prune_wave<KIND, T, CPL, false>(a.ds, L, deg, B, a.R, a.alpha);
         }
         for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? L->sel_id[j] : JX_NONE_ID;
+        if (a.clean && lane == 0) a.clean[v] = (uint8_t)(nsel < 255 ? nsel : 255);
         wave_sync();
     }
 }

@@ -65,6 +65,8 @@ struct InsertArgs {
     int force_prune;            // consolidation: ignore the existing row, always prune the candidate segment
     int gram;                   // float data: 1 (float32) / 2 (binary16) = prunes of at most 128 candidates go to the Gram-matrix kernels
     int vec_cache_bytes;        // reverse merge: LDS bytes per wavefront for candidate vectors (0 = never cache)
+    uint8_t* clean;             // [N] leading entries of each row that one robustPrune call selected together
+                                // (saturated at 255; 0 = nothing known), or NULL
 };
 
 hipError_t launch_entry_point(const void* vecs, int dtype, long long n, int d, double* partial, float* mean, double* dist,
@@ -198,6 +200,7 @@ struct jx_index {
     int64_t work_bytes;
     unsigned long long* d_stats;  // [8] search counters, [8] = vertices marked deleted so far
     uint8_t* d_deleted;  // [capacity] 1 = logically deleted
+    uint8_t* d_clean;    // [capacity] see InsertArgs::clean
     int any_delete;      // a delete call has been made since the graph was created / imported
     // RaBitQ state
     int quantized;    // 0 or bits

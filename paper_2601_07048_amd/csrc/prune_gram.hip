@@ -347,6 +347,7 @@ __global__ void __launch_bounds__(GP_WPB * 64) forward_prune_gram_kernel(InsertA
         a.keys[(size_t)i * a.R + j] = on ? (((uint64_t)v << 32) | L->sel_dist[j]) : JX_EMPTY_KEY;
         a.vals[(size_t)i * a.R + j] = on ? (uint32_t)xid : JX_NONE_ID;
     }
+    if (a.clean && lane == 0) a.clean[xid] = (uint8_t)(nsel < 255 ? nsel : 255);
 }
 
 // ---- reverse-edge merge (Alg. 4 step 3): the targets whose row overflows and whose candidates fit 128 slots
@@ -389,6 +390,7 @@ __global__ void __launch_bounds__(GP_WPB * 64) reverse_merge_gram_kernel(InsertA
         wave_sync();
         const int nsel = gram_prune_wave<DT, NT>(a.ds.recs, (size_t)a.ds.rec_stride, a.ds.nch * 16, L, M, v, false, a.R, a.alpha);
         for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? L->sel_id[j] : JX_NONE_ID;
+        if (a.clean && lane == 0) a.clean[v] = (uint8_t)(nsel < 255 ? nsel : 255);
         // the row has changed, so degree and overflow can no longer be derived from it: mark the segment as done
         if (lane == 0) const_cast<uint32_t*>(a.heads)[s] = head | 0x80000000u;
         wave_sync();
@@ -734,6 +736,7 @@ __global__ void __launch_bounds__(GP_WPB * 64) reverse_merge_gram_big_kernel(Ins
                                             mp < m);
         if (nsel < 0) continue;  // the prefix did not yield R neighbours: left to the list-based kernel
         for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? L->sel_id[j] : JX_NONE_ID;
+        if (a.clean && lane == 0) a.clean[v] = (uint8_t)(nsel < 255 ? nsel : 255);
         if (lane == 0) const_cast<uint32_t*>(a.heads)[s] = head | 0x80000000u;
         wave_sync();
     }

@@ -203,3 +203,55 @@ print('variant ok')
     env = dict(os.environ, JX_GRAM_U8="1")
     r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
     assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+def test_incremental_prune_of_full_rows(jx):
+    """uint8 rows remember which leading entries one robustPrune call selected together; the next prune of such a
+    row evaluates only the pairs that involve an appended or new entry.  Small R makes nearly every reverse edge
+    overflow its row; several insert calls, the oracle's graph bit for bit after each."""
+    n, d, R, L = 6000, 128, 16, 32
+    x = random_data(n, d, np.uint8, seed=77)
+    ref = oracle.Index(d, np.uint8, R, L, 1.2, n)
+    g = jx.Index(d, jx.U8, R, L, 1.2, capacity=n, max_batch=n)
+    for lo, hi in ((0, 500), (500, 2500), (2500, 2600), (2600, 6000)):
+        ref.insert(x[lo:hi])
+        g.insert(dev(x[lo:hi]))
+        assert np.array_equal(u32(g.export_graph()[0]), ref.graph()[0]), (lo, hi)
+    # deletion rewrites rows through the same kernel; inserts after it go on from the rewritten rows
+    dele = np.random.default_rng(5).choice(n, 900, replace=False).astype(np.uint32)
+    ref.delete(dele); g.delete(dev(dele)); ref.consolidate(); g.consolidate()
+    assert np.array_equal(u32(g.export_graph()[0]), ref.graph()[0])
+
+
+def test_incremental_prune_switched_off_gives_the_same_graph(jx):
+    """At a size the oracle does not reach in seconds: the graph built with the shortcut equals the graph built
+    without it (JX_INCR_PRUNE=0 is read once per process, hence the child process)."""
+    import hashlib
+    import os
+    import subprocess
+    import sys
+    n = 200_000
+    code = r"""
+import sys, hashlib, numpy as np, torch
+from paper_2601_07048_amd import jx, datagen
+n = %d
+x = torch.from_numpy(datagen.base(2, n)).cuda()
+g = jx.Index(128, jx.U8, 64, 128, 1.2, capacity=n, max_batch=n // 4 + 1)
+for lo in range(0, n, 50_000):
+    g.insert(x[lo:lo + 50_000])
+adj = g.export_graph()[0].cpu().numpy()
+print('sha', hashlib.sha256(adj.tobytes()).hexdigest())
+""" % n
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=dict(os.environ, JX_INCR_PRUNE="0"),
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and "sha " in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+    want = r.stdout.split("sha ")[1].split()[0]
+    from paper_2601_07048_amd import datagen
+    import torch
+    x = torch.from_numpy(datagen.base(2, n)).cuda()
+    g = jx.Index(128, jx.U8, 64, 128, 1.2, capacity=n, max_batch=n // 4 + 1)
+    for lo in range(0, n, 50_000):
+        g.insert(x[lo:lo + 50_000])
+    got = hashlib.sha256(g.export_graph()[0].cpu().numpy().tobytes()).hexdigest()
+    assert got == want
