@@ -178,10 +178,11 @@ int gram_mode(int dtype) {
     if (dtype == JX_U8) {
         static int u8 = -1;
         if (u8 < 0) {
-            const char* e = getenv("JX_GRAM_U8");
-            u8 = (e && atoi(e) == 1) ? 1 : 0;
+            const char* e = getenv("JX_GRAM_U8");  // 1: forward prune and reverse merge, 2: forward prune only
+            u8 = e ? atoi(e) : 0;
+            if (u8 != 1 && u8 != 2) u8 = 0;
         }
-        return u8 ? 3 : 0;
+        return u8 == 1 ? 3 : (u8 == 2 ? 7 : 0);
     }
     return dtype == JX_F16 ? 2 : 1;
 }
@@ -626,6 +627,7 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     // LDS room per wavefront for the vectors of a full row plus up to 32 new edges (96 x 128 bytes);
     // larger merges take the path that reads from global memory
     a.vec_cache_bytes = 12288;
+    if (a.gram == 7) a.gram = 0;
     JX_HIP(jx::launch_reverse_merge(p.dtype, a, st));
     return JX_OK;
 }
@@ -891,6 +893,7 @@ int jx_consolidate(jx_index* idx, void* stream) {
     a.force_prune = 1;
     a.clean = incremental_prune() ? idx->d_clean : nullptr;
     a.gram = gram_mode(p.dtype);
+    if (a.gram == 7) a.gram = 0;
     a.vec_cache_bytes = 12288;
     // 2. slices of consecutive vertices whose candidate lists fit the edge buffers; every new row is
     //    computed from its own old row and from rows of deleted vertices, none of which is rewritten here
