@@ -622,6 +622,224 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
     }
 }
 
+// Reverse-edge merge, lean form for the case that dominates streaming inserts into uint8 indices of 128-byte
+// vectors: the row overflows, all but at most four of its candidates were selected together by the row's previous
+// robustPrune call (see prune_cached_u8_incremental for why their pairs need no test), and everything fits 128
+// slots.  One pass over the candidates' vectors in global memory yields d(v,c) and d(x,c) for every entry x that
+// is appended or new (v and those entries sit in registers); ranks come from merging them into the sorted prefix;
+// Alg. 3 is the same walk over the marked entries.  No vector cache in LDS, so five times as many wavefronts are
+// resident as in the general kernel, which then finds these segments marked as done (bit 31 of the head).
+struct LeanLds {
+    uint64_t key[128];      // (float bits of d(v,c), id), candidate order: the row, then the new edges
+    uint64_t skey[128];     // the same, sorted
+    uint32_t id[128];
+    uint32_t dd[4][128];    // d(marked entry k, candidate j), candidate order
+    uint8_t orig[128];      // candidate index of sorted position p
+    uint8_t flag[128];      // sorted position p: 0 = selected by the previous call, else 1 + index of the marked entry
+};
+
+__global__ void __launch_bounds__(64) reverse_merge_u8_lean_kernel(InsertArgs a) {
+    __shared__ LeanLds lds;
+    LeanLds* F = &lds;
+    const int lane = lane_id();
+    const int g = lane >> 2, lig = lane & 3;
+    const long long nseg = *a.nseg;
+    const long long total = a.E ? a.E : a.B * a.R;
+    const uint8_t* recs = a.ds.recs;
+    for (long long s = blockIdx.x; s < nseg; s += gridDim.x) {
+        const uint32_t head = a.heads[s];
+        if (head & 0x80000000u) continue;
+        const long long lo = head;
+        const uint32_t v = (uint32_t)(a.keys[lo] >> 32);
+        if (v == JX_NONE_ID) continue;
+        int m = 0;
+        for (long long c0 = lo; c0 < total; c0 += 64) {
+            const long long j = c0 + lane;
+            const bool same = j < total && (uint32_t)(a.keys[j] >> 32) == v;
+            const uint64_t sm = ballot(same);
+            m += __builtin_popcountll(sm);
+            if (sm != ~0ull) break;
+        }
+        uint32_t* row = a.adj + (size_t)v * a.R;
+        int deg = 0;
+        for (int rb = 0; rb < a.R; rb += 64) {
+            const bool on = rb + lane < a.R && row[rb + lane] != JX_NONE_ID;
+            deg += __builtin_popcountll(ballot(on));
+        }
+        if (deg + m <= a.R) continue;  // an append: the general kernel does it
+        int nclean = (int)a.clean[v];
+        if (nclean > deg) nclean = deg;
+        const int M = deg + m, nd = M - nclean;
+        if (nclean == 0 || M > 128 || nd > 4) continue;
+        wave_sync();  // the previous segment's reads of the LDS arrays are done
+        for (int j = lane; j < M; j += 64) F->id[j] = j < deg ? row[j] : a.vals[lo + (j - deg)];
+        wave_sync();
+        // v and the marked entries, 32 bytes per lane of each 4-lane group
+        uint4 qv[2], qd[4][2];
+        uint32_t qqv, qqd[4];
+        {
+            const uint8_t* pv = recs + (size_t)v * 128 + lig * 32;
+            qv[0] = load16(pv);
+            qv[1] = load16(pv + 16);
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const uint32_t idk = F->id[nclean + (k < nd ? k : 0)];
+                const uint8_t* pk = recs + (size_t)idk * 128 + lig * 32;
+                qd[k][0] = load16(pk);
+                qd[k][1] = load16(pk + 16);
+            }
+            auto sq = [](const uint4 (&x)[2]) {
+                uint32_t t = 0;
+                t = __builtin_amdgcn_udot4(x[0].x, x[0].x, t, false);
+                t = __builtin_amdgcn_udot4(x[0].y, x[0].y, t, false);
+                t = __builtin_amdgcn_udot4(x[0].z, x[0].z, t, false);
+                t = __builtin_amdgcn_udot4(x[0].w, x[0].w, t, false);
+                t = __builtin_amdgcn_udot4(x[1].x, x[1].x, t, false);
+                t = __builtin_amdgcn_udot4(x[1].y, x[1].y, t, false);
+                t = __builtin_amdgcn_udot4(x[1].z, x[1].z, t, false);
+                t = __builtin_amdgcn_udot4(x[1].w, x[1].w, t, false);
+                return t;
+            };
+            qqv = group_sum<4>(sq(qv));
+#pragma unroll
+            for (int k = 0; k < 4; k++) qqd[k] = group_sum<4>(sq(qd[k]));
+        }
+        auto dot = [](const uint4 (&x)[2], const uint4 (&y)[2]) {
+            uint32_t t = 0;
+            t = __builtin_amdgcn_udot4(x[0].x, y[0].x, t, false);
+            t = __builtin_amdgcn_udot4(x[0].y, y[0].y, t, false);
+            t = __builtin_amdgcn_udot4(x[0].z, y[0].z, t, false);
+            t = __builtin_amdgcn_udot4(x[0].w, y[0].w, t, false);
+            t = __builtin_amdgcn_udot4(x[1].x, y[1].x, t, false);
+            t = __builtin_amdgcn_udot4(x[1].y, y[1].y, t, false);
+            t = __builtin_amdgcn_udot4(x[1].z, y[1].z, t, false);
+            t = __builtin_amdgcn_udot4(x[1].w, y[1].w, t, false);
+            return t;
+        };
+        // one pass over the candidates: 16 per step, two steps in flight
+        for (int c0 = 0; c0 < M; c0 += 32) {
+            uint4 x[2][2];
+            int jj[2];
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                jj[u] = c0 + 16 * u + g;
+                const uint32_t id = F->id[jj[u] < M ? jj[u] : M - 1];
+                const uint8_t* px = recs + (size_t)id * 128 + lig * 32;
+                x[u][0] = load16(px);
+                x[u][1] = load16(px + 16);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                if (c0 + 16 * u >= M) break;  // wave-uniform
+                const uint32_t aa = dot(x[u], x[u]);
+                const uint32_t dv = (uint32_t)group_sum<4>((int32_t)aa - 2 * (int32_t)dot(x[u], qv)) + qqv;
+                uint32_t dk[4];
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    dk[k] = 0;
+                    if (k < nd) dk[k] = (uint32_t)group_sum<4>((int32_t)aa - 2 * (int32_t)dot(x[u], qd[k])) + qqd[k];
+                }
+                if (lig == 0 && jj[u] < M) {
+                    F->key[jj[u]] = ((uint64_t)__float_as_uint((float)dv) << 32) | (uint64_t)F->id[jj[u]];
+#pragma unroll
+                    for (int k = 0; k < 4; k++)
+                        if (k < nd) F->dd[k][jj[u]] = dk[k];
+                }
+            }
+        }
+        wave_sync();
+        // ranks: the prefix is sorted already and every marked entry is merged into it.  Prefix entry: own index +
+        // marked entries below it; marked entry: prefix entries below it + marked entries below it
+        uint64_t kj[2];
+        int rank[2];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int j = h * 64 + lane;
+            kj[h] = j < M ? F->key[j] : JX_EMPTY_KEY;
+            rank[h] = j < nclean ? j : 0;
+        }
+        for (int k = 0; k < nd; k++) {
+            const uint64_t kt = F->key[nclean + k];
+            const int below = __builtin_popcountll(ballot(lane < nclean && kj[0] < kt)) +
+                              __builtin_popcountll(ballot(64 + lane < nclean && kj[1] < kt));
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const int j = h * 64 + lane;
+                rank[h] += (kt < kj[h]) ? 1 : 0;
+                if (j == nclean + k) rank[h] += below;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int j = h * 64 + lane;
+            if (j < M) {
+                F->skey[rank[h]] = kj[h];
+                F->orig[rank[h]] = (uint8_t)j;
+                F->flag[rank[h]] = j >= nclean ? (uint8_t)(1 + j - nclean) : (uint8_t)0;
+            }
+        }
+        wave_sync();
+        // Alg. 3 over the marked entries, sorted space
+        uint64_t sk[2], dm[2], alive[2];
+        float dvp[2];
+        int og[2];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int p = h * 64 + lane;
+            sk[h] = p < M ? F->skey[p] : JX_EMPTY_KEY;
+            dvp[h] = __uint_as_float((uint32_t)(sk[h] >> 32));
+            og[h] = p < M ? (int)F->orig[p] : 0;
+            dm[h] = ballot(p < M && F->flag[p] != 0);
+        }
+        alive[0] = M >= 64 ? ~0ull : ((1ull << M) - 1ull);
+        alive[1] = M <= 64 ? 0ull : (M >= 128 ? ~0ull : ((1ull << (M - 64)) - 1ull));
+        while (dm[0] | dm[1]) {
+            int t;
+            if (dm[0]) {
+                t = __builtin_ctzll(dm[0]);
+                dm[0] &= dm[0] - 1ull;
+            } else {
+                t = 64 + __builtin_ctzll(dm[1]);
+                dm[1] &= dm[1] - 1ull;
+            }
+            if (((alive[t >> 6] >> (t & 63)) & 1ull) == 0ull) continue;
+            const int k = (int)F->flag[t] - 1;
+            const float dvt = __uint_as_float((uint32_t)(F->skey[t] >> 32));
+            uint64_t rk[2], ck[2];
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const int p = h * 64 + lane;
+                const float d1 = (float)F->dd[k][og[h]];
+                const float ad = __fmul_rn(a.alpha, d1);
+                rk[h] = ballot(p < M && p > t && ad <= dvp[h]);
+                ck[h] = ballot(p < M && p < t && ad <= dvt);
+            }
+            if ((ck[0] & alive[0]) | (ck[1] & alive[1])) {
+                alive[t >> 6] &= ~(1ull << (t & 63));
+            } else {
+                alive[0] &= ~rk[0];
+                alive[1] &= ~rk[1];
+            }
+        }
+        const int n0 = __builtin_popcountll(alive[0]);
+        const int tot = n0 + __builtin_popcountll(alive[1]);
+        const int nsel = tot < a.R ? tot : a.R;
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int p = h * 64 + lane;
+            if (p < M && ((alive[h] >> lane) & 1ull)) {
+                const int pos = (h ? n0 : 0) + __builtin_popcountll(alive[h] & ((1ull << lane) - 1ull));
+                if (pos < a.R) row[pos] = (uint32_t)sk[h];
+            }
+        }
+        for (int j = nsel + lane; j < a.R; j += 64) row[j] = JX_NONE_ID;
+        if (lane == 0) {
+            a.clean[v] = (uint8_t)(nsel < 255 ? nsel : 255);
+            const_cast<uint32_t*>(a.heads)[s] = head | 0x80000000u;
+        }
+    }
+}
+
 // ------------------------------------------------------------------ radix sort
 
 #define RS_ITEMS 16
@@ -838,6 +1056,14 @@ hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st) 
 hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st) {
     if (a.gram) {
         hipError_t e = launch_reverse_merge_gram(dtype, a, st);
+        if (e != hipSuccess) return e;
+    }
+    if (dtype == JX_U8 && a.clean && !a.force_prune && a.ds.rec_stride == 128 && a.ds.nch == 8) {
+        // overflowing rows that are almost entirely their previous prune's output: lean kernel first
+        const long long want = a.E ? a.E : a.B * a.R;
+        const unsigned grid = (unsigned)(want < 8192 ? (want < 1 ? 1 : want) : 8192);
+        hipLaunchKernelGGL(reverse_merge_u8_lean_kernel, dim3(grid), dim3(64), 0, st, a);
+        hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (dtype == JX_U8) return launch_prune_shape<K_U8>(false, a, st);
