@@ -623,17 +623,18 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
 }
 
 // Reverse-edge merge, lean form for the case that dominates streaming inserts into uint8 indices of 128-byte
-// vectors: the row overflows, all but at most four of its candidates were selected together by the row's previous
+// vectors: the row overflows, all but a few (LEAN_ND) of its candidates were selected together by the row's previous
 // robustPrune call (see prune_cached_u8_incremental for why their pairs need no test), and everything fits 128
 // slots.  One pass over the candidates' vectors in global memory yields d(v,c) and d(x,c) for every entry x that
 // is appended or new (v and those entries sit in registers); ranks come from merging them into the sorted prefix;
 // Alg. 3 is the same walk over the marked entries.  No vector cache in LDS, so five times as many wavefronts are
 // resident as in the general kernel, which then finds these segments marked as done (bit 31 of the head).
+#define LEAN_ND 12  // marked entries per row the lean kernel accepts (taken four at a time)
 struct LeanLds {
     uint64_t key[128];      // (float bits of d(v,c), id), candidate order: the row, then the new edges
     uint64_t skey[128];     // the same, sorted
     uint32_t id[128];
-    uint32_t dd[4][128];    // d(marked entry k, candidate j), candidate order
+    uint32_t dd[LEAN_ND][128];  // d(marked entry k, candidate j), candidate order
     uint8_t orig[128];      // candidate index of sorted position p
     uint8_t flag[128];      // sorted position p: 0 = selected by the previous call, else 1 + index of the marked entry
 };
@@ -666,44 +667,30 @@ __global__ void __launch_bounds__(64) reverse_merge_u8_lean_kernel(InsertArgs a)
             const bool on = rb + lane < a.R && row[rb + lane] != JX_NONE_ID;
             deg += __builtin_popcountll(ballot(on));
         }
-        if (deg + m <= a.R) continue;  // an append: the general kernel does it
+        if (deg + m <= a.R) {  // the row still fits: append in (distance, source) order
+            for (int j = lane; j < m; j += 64) row[deg + j] = a.vals[lo + j];
+            if (lane == 0) const_cast<uint32_t*>(a.heads)[s] = head | 0x80000000u;
+            continue;
+        }
         int nclean = (int)a.clean[v];
         if (nclean > deg) nclean = deg;
         const int M = deg + m, nd = M - nclean;
-        if (nclean == 0 || M > 128 || nd > 4) continue;
+        if (nclean == 0 || M > 128 || nd > LEAN_ND) continue;
         wave_sync();  // the previous segment's reads of the LDS arrays are done
         for (int j = lane; j < M; j += 64) F->id[j] = j < deg ? row[j] : a.vals[lo + (j - deg)];
         wave_sync();
-        // v and the marked entries, 32 bytes per lane of each 4-lane group
-        uint4 qv[2], qd[4][2];
-        uint32_t qqv, qqd[4];
-        {
-            const uint8_t* pv = recs + (size_t)v * 128 + lig * 32;
-            qv[0] = load16(pv);
-            qv[1] = load16(pv + 16);
-#pragma unroll
-            for (int k = 0; k < 4; k++) {
-                const uint32_t idk = F->id[nclean + (k < nd ? k : 0)];
-                const uint8_t* pk = recs + (size_t)idk * 128 + lig * 32;
-                qd[k][0] = load16(pk);
-                qd[k][1] = load16(pk + 16);
-            }
-            auto sq = [](const uint4 (&x)[2]) {
-                uint32_t t = 0;
-                t = __builtin_amdgcn_udot4(x[0].x, x[0].x, t, false);
-                t = __builtin_amdgcn_udot4(x[0].y, x[0].y, t, false);
-                t = __builtin_amdgcn_udot4(x[0].z, x[0].z, t, false);
-                t = __builtin_amdgcn_udot4(x[0].w, x[0].w, t, false);
-                t = __builtin_amdgcn_udot4(x[1].x, x[1].x, t, false);
-                t = __builtin_amdgcn_udot4(x[1].y, x[1].y, t, false);
-                t = __builtin_amdgcn_udot4(x[1].z, x[1].z, t, false);
-                t = __builtin_amdgcn_udot4(x[1].w, x[1].w, t, false);
-                return t;
-            };
-            qqv = group_sum<4>(sq(qv));
-#pragma unroll
-            for (int k = 0; k < 4; k++) qqd[k] = group_sum<4>(sq(qd[k]));
-        }
+        auto sq = [](const uint4 (&x)[2]) {
+            uint32_t t = 0;
+            t = __builtin_amdgcn_udot4(x[0].x, x[0].x, t, false);
+            t = __builtin_amdgcn_udot4(x[0].y, x[0].y, t, false);
+            t = __builtin_amdgcn_udot4(x[0].z, x[0].z, t, false);
+            t = __builtin_amdgcn_udot4(x[0].w, x[0].w, t, false);
+            t = __builtin_amdgcn_udot4(x[1].x, x[1].x, t, false);
+            t = __builtin_amdgcn_udot4(x[1].y, x[1].y, t, false);
+            t = __builtin_amdgcn_udot4(x[1].z, x[1].z, t, false);
+            t = __builtin_amdgcn_udot4(x[1].w, x[1].w, t, false);
+            return t;
+        };
         auto dot = [](const uint4 (&x)[2], const uint4 (&y)[2]) {
             uint32_t t = 0;
             t = __builtin_amdgcn_udot4(x[0].x, y[0].x, t, false);
@@ -716,34 +703,57 @@ __global__ void __launch_bounds__(64) reverse_merge_u8_lean_kernel(InsertArgs a)
             t = __builtin_amdgcn_udot4(x[1].w, y[1].w, t, false);
             return t;
         };
-        // one pass over the candidates: 16 per step, two steps in flight
-        for (int c0 = 0; c0 < M; c0 += 32) {
-            uint4 x[2][2];
-            int jj[2];
+        // v and four marked entries at a time sit in registers, 32 bytes per lane of each 4-lane group; every group
+        // of four takes one pass over the candidates (16 per step, two steps in flight)
+        uint4 qv[2];
+        {
+            const uint8_t* pv = recs + (size_t)v * 128 + lig * 32;
+            qv[0] = load16(pv);
+            qv[1] = load16(pv + 16);
+        }
+        const uint32_t qqv = group_sum<4>(sq(qv));
+        for (int kb = 0; kb < nd; kb += 4) {
+            const int nk = nd - kb < 4 ? nd - kb : 4;
+            uint4 qd[4][2];
+            uint32_t qqd[4];
 #pragma unroll
-            for (int u = 0; u < 2; u++) {
-                jj[u] = c0 + 16 * u + g;
-                const uint32_t id = F->id[jj[u] < M ? jj[u] : M - 1];
-                const uint8_t* px = recs + (size_t)id * 128 + lig * 32;
-                x[u][0] = load16(px);
-                x[u][1] = load16(px + 16);
+            for (int k = 0; k < 4; k++) {
+                const uint32_t idk = F->id[nclean + kb + (k < nk ? k : 0)];
+                const uint8_t* pk = recs + (size_t)idk * 128 + lig * 32;
+                qd[k][0] = load16(pk);
+                qd[k][1] = load16(pk + 16);
             }
 #pragma unroll
-            for (int u = 0; u < 2; u++) {
-                if (c0 + 16 * u >= M) break;  // wave-uniform
-                const uint32_t aa = dot(x[u], x[u]);
-                const uint32_t dv = (uint32_t)group_sum<4>((int32_t)aa - 2 * (int32_t)dot(x[u], qv)) + qqv;
-                uint32_t dk[4];
+            for (int k = 0; k < 4; k++) qqd[k] = group_sum<4>(sq(qd[k]));
+            for (int c0 = 0; c0 < M; c0 += 32) {
+                uint4 x[2][2];
+                int jj[2];
 #pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    dk[k] = 0;
-                    if (k < nd) dk[k] = (uint32_t)group_sum<4>((int32_t)aa - 2 * (int32_t)dot(x[u], qd[k])) + qqd[k];
+                for (int u = 0; u < 2; u++) {
+                    jj[u] = c0 + 16 * u + g;
+                    const uint32_t id = F->id[jj[u] < M ? jj[u] : M - 1];
+                    const uint8_t* px = recs + (size_t)id * 128 + lig * 32;
+                    x[u][0] = load16(px);
+                    x[u][1] = load16(px + 16);
                 }
-                if (lig == 0 && jj[u] < M) {
-                    F->key[jj[u]] = ((uint64_t)__float_as_uint((float)dv) << 32) | (uint64_t)F->id[jj[u]];
 #pragma unroll
-                    for (int k = 0; k < 4; k++)
-                        if (k < nd) F->dd[k][jj[u]] = dk[k];
+                for (int u = 0; u < 2; u++) {
+                    if (c0 + 16 * u >= M) break;  // wave-uniform
+                    const uint32_t aa = dot(x[u], x[u]);
+                    uint32_t dv = 0;
+                    if (kb == 0) dv = (uint32_t)group_sum<4>((int32_t)aa - 2 * (int32_t)dot(x[u], qv)) + qqv;
+                    uint32_t dk[4];
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        dk[k] = 0;
+                        if (k < nk) dk[k] = (uint32_t)group_sum<4>((int32_t)aa - 2 * (int32_t)dot(x[u], qd[k])) + qqd[k];
+                    }
+                    if (lig == 0 && jj[u] < M) {
+                        if (kb == 0) F->key[jj[u]] = ((uint64_t)__float_as_uint((float)dv) << 32) | (uint64_t)F->id[jj[u]];
+#pragma unroll
+                        for (int k = 0; k < 4; k++)
+                            if (k < nk) F->dd[kb + k][jj[u]] = dk[k];
+                    }
                 }
             }
         }
