@@ -850,6 +850,182 @@ __global__ void __launch_bounds__(64) reverse_merge_u8_lean_kernel(InsertArgs a)
     }
 }
 
+// Forward robustPrune, lean form for uint8 vectors of 128 bytes and frontiers of at most 128 entries.  The
+// selection loop of Alg. 3 has one dependent memory round trip per selected neighbour; here up to four pivots --
+// the next live candidates in order -- are taken per round: one pass over the live candidates behind the first
+// pivot loads every vector once and tests it against all four (the pivots sit in registers), then the pivots are
+// resolved in order: a pivot that is still live is selected and discards what it discards, one that an earlier
+// pivot discarded is skipped (its tests were wasted).  Every test is the pairwise test of Alg. 3 on exact
+// integers, so the result is the sequential algorithm's.
+struct FwdLds {
+    uint32_t id[128];
+    float dx[128];        // d(x, candidate)
+    uint32_t sel_id[128];
+    uint32_t sel_dist[128];
+    uint8_t cand[128];    // live candidates behind the first pivot, compacted
+    uint8_t kb[128];      // bit i: pivot i discards this candidate
+};
+
+__global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a) {
+    __shared__ FwdLds lds;
+    FwdLds* F = &lds;
+    const int lane = lane_id();
+    const int g = lane >> 2, lig = lane & 3;
+    const long long i = blockIdx.x;
+    if (i >= a.B) return;
+    long long xid = a.id_base + i;
+    if (xid >= a.id_skip) xid++;
+    const uint32_t* ids = a.cand_ids + (size_t)i * a.L;
+    const uint32_t* dbits = a.cand_dist + (size_t)i * a.L;
+    const uint8_t* recs = a.ds.recs;
+    uint64_t alive[2];
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const int j = h * 64 + lane;
+        uint32_t id = JX_NONE_ID;
+        if (j < a.L) id = ids[j];
+        const bool valid = id != JX_NONE_ID;
+        if (valid) {
+            F->id[j] = id;
+            F->dx[j] = __uint_as_float(dbits[j]);
+        }
+        alive[h] = ballot(valid);  // the frontier is filled from the left
+    }
+    wave_sync();
+    auto dot = [](const uint4 (&x)[2], const uint4 (&y)[2]) {
+        uint32_t t = 0;
+        t = __builtin_amdgcn_udot4(x[0].x, y[0].x, t, false);
+        t = __builtin_amdgcn_udot4(x[0].y, y[0].y, t, false);
+        t = __builtin_amdgcn_udot4(x[0].z, y[0].z, t, false);
+        t = __builtin_amdgcn_udot4(x[0].w, y[0].w, t, false);
+        t = __builtin_amdgcn_udot4(x[1].x, y[1].x, t, false);
+        t = __builtin_amdgcn_udot4(x[1].y, y[1].y, t, false);
+        t = __builtin_amdgcn_udot4(x[1].z, y[1].z, t, false);
+        t = __builtin_amdgcn_udot4(x[1].w, y[1].w, t, false);
+        return t;
+    };
+    int nsel = 0;
+    while (nsel < a.R && (alive[0] | alive[1])) {
+        // ---- pivots: the next live candidates, as many as may still be selected, at most four
+        int t[4], np = 0;
+        {
+            uint64_t m0 = alive[0], m1 = alive[1];
+            const int room = a.R - nsel < 4 ? a.R - nsel : 4;
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                t[k] = 0;
+                if (k < room) {
+                    if (m0) {
+                        t[k] = __builtin_ctzll(m0);
+                        m0 &= m0 - 1ull;
+                        np = k + 1;
+                    } else if (m1) {
+                        t[k] = 64 + __builtin_ctzll(m1);
+                        m1 &= m1 - 1ull;
+                        np = k + 1;
+                    }
+                }
+            }
+        }
+        // ---- live candidates behind the first pivot
+        int n_alive = 0;
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int j = h * 64 + lane;
+            const bool on = ((alive[h] >> lane) & 1ull) && j > t[0];
+            const uint64_t m = ballot(on);
+            if (on) F->cand[n_alive + prefix_count(m)] = (uint8_t)j;
+            n_alive += __builtin_popcountll(m);
+        }
+        if (n_alive == 0 || nsel + 1 >= a.R) {
+            // the last neighbour there is, or the last one there is room for: nothing left to discard
+            if (lane == 0) {
+                F->sel_id[nsel] = F->id[t[0]];
+                F->sel_dist[nsel] = __float_as_uint(F->dx[t[0]]);
+            }
+            nsel++;
+            break;
+        }
+        wave_sync();
+        uint4 qd[4][2];
+        uint32_t qqd[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const uint32_t idk = F->id[t[k < np ? k : 0]];
+            const uint8_t* pk = recs + (size_t)idk * 128 + lig * 32;
+            qd[k][0] = load16(pk);
+            qd[k][1] = load16(pk + 16);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; k++) qqd[k] = group_sum<4>(dot(qd[k], qd[k]));
+        for (int c0 = 0; c0 < n_alive; c0 += 32) {
+            uint4 x[2][2];
+            int jj[2], jc[2];
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                jj[u] = c0 + 16 * u + g;
+                jc[u] = (int)F->cand[jj[u] < n_alive ? jj[u] : n_alive - 1];
+                const uint8_t* px = recs + (size_t)F->id[jc[u]] * 128 + lig * 32;
+                x[u][0] = load16(px);
+                x[u][1] = load16(px + 16);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                if (c0 + 16 * u >= n_alive) break;  // wave-uniform
+                const uint32_t aa = dot(x[u], x[u]);
+                uint32_t bits = 0;
+                const float dxc = F->dx[jc[u]];
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    if (k < np) {
+                        const uint32_t dk = (uint32_t)group_sum<4>((int32_t)aa - 2 * (int32_t)dot(x[u], qd[k])) + qqd[k];
+                        if (jc[u] > t[k] && __fmul_rn(a.alpha, (float)dk) <= dxc) bits |= 1u << k;
+                    }
+                }
+                if (lig == 0 && jj[u] < n_alive) F->kb[jc[u]] = (uint8_t)bits;
+            }
+        }
+        wave_sync();
+        uint64_t K[4][2];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const int j = h * 64 + lane;
+            const bool on = ((alive[h] >> lane) & 1ull) && j > t[0];
+            const uint32_t b = on ? (uint32_t)F->kb[j] : 0u;
+#pragma unroll
+            for (int k = 0; k < 4; k++) K[k][h] = ballot((b >> k) & 1u);
+        }
+        // ---- resolve the pivots in order
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            if (k < np && nsel < a.R) {
+                const int tk = t[k];
+                if ((alive[tk >> 6] >> (tk & 63)) & 1ull) {
+                    if (lane == 0) {
+                        F->sel_id[nsel] = F->id[tk];
+                        F->sel_dist[nsel] = __float_as_uint(F->dx[tk]);
+                    }
+                    nsel++;
+                    alive[tk >> 6] &= ~(1ull << (tk & 63));
+                    alive[0] &= ~K[k][0];
+                    alive[1] &= ~K[k][1];
+                }
+            }
+        }
+        wave_sync();
+    }
+    wave_sync();
+    uint32_t* row = a.adj + (size_t)xid * a.R;
+    for (int j = lane; j < a.R; j += 64) {
+        const bool on = j < nsel;
+        const uint32_t v = on ? F->sel_id[j] : JX_NONE_ID;
+        row[j] = v;
+        a.keys[(size_t)i * a.R + j] = on ? (((uint64_t)v << 32) | F->sel_dist[j]) : JX_EMPTY_KEY;
+        a.vals[(size_t)i * a.R + j] = on ? (uint32_t)xid : JX_NONE_ID;
+    }
+    if (a.clean && lane == 0) a.clean[xid] = (uint8_t)(nsel < 255 ? nsel : 255);
+}
+
 // ------------------------------------------------------------------ radix sort
 
 #define RS_ITEMS 16
@@ -1053,10 +1229,24 @@ static hipError_t launch_prune_shape(bool forward, const InsertArgs& a, hipStrea
     return hipErrorInvalidValue;
 }
 
+// JX_LEAN_FWD=0 sends uint8 frontiers to the general kernel (comparisons)
+static bool lean_forward_prune() {
+    static int on = -1;
+    if (on < 0) {
+        const char* e = getenv("JX_LEAN_FWD");
+        on = (e && atoi(e) == 0) ? 0 : 1;
+    }
+    return on != 0;
+}
+
 hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st) {
     if (a.gram) {
         hipError_t e = launch_forward_prune_gram(dtype, a, st);
         if (e != hipSuccess || a.L <= 128) return e;  // wider frontiers: the list-based kernel takes the rest
+    }
+    if (dtype == JX_U8 && !a.gram && a.ds.rec_stride == 128 && a.ds.nch == 8 && a.L <= 128 && lean_forward_prune()) {
+        hipLaunchKernelGGL(forward_prune_u8_lean_kernel, dim3((unsigned)a.B), dim3(64), 0, st, a);
+        return hipGetLastError();
     }
     if (dtype == JX_U8) return launch_prune_shape<K_U8>(true, a, st);
     if (dtype == JX_F16) return launch_prune_shape<K_F16>(true, a, st);
