@@ -6,7 +6,7 @@
 //   forward prune : one wavefront per new point runs robustPrune (Alg. 3) on
 //                   its final frontier, writes adjacency row, emits reverse
 //                   edges (target, distance, source) to the kept neighbours only
-//   sort          : stable LSD radix sort (4-bit digits) of the unified edge
+//   sort          : stable LSD radix sort (8-bit digits) of the unified edge
 //                   buffer on the 64-bit key (target << 32 | distance bits);
 //                   stability leaves equal keys in emission order = ascending
 //                   source id, so the order is (target, distance, source)
@@ -1031,20 +1031,6 @@ __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a)
 #define RS_ITEMS 16
 #define RS_TILE (256 * RS_ITEMS)
 
-__global__ void __launch_bounds__(256) radix_hist_kernel(const uint64_t* keys, long long n, int shift, uint32_t* table, int ntiles) {
-    __shared__ uint32_t cnt[16];
-    if (threadIdx.x < 16) cnt[threadIdx.x] = 0;
-    __syncthreads();
-    const long long base = (long long)blockIdx.x * RS_TILE;
-#pragma unroll
-    for (int e = 0; e < RS_ITEMS; e++) {
-        const long long i = base + e * 256 + threadIdx.x;
-        if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & 15], 1u);
-    }
-    __syncthreads();
-    if (threadIdx.x < 16) table[(size_t)threadIdx.x * ntiles + blockIdx.x] = cnt[threadIdx.x];
-}
-
 // exclusive prefix sum of `total` counters, single workgroup
 __global__ void __launch_bounds__(1024) radix_scan_kernel(uint32_t* table, long long total) {
     __shared__ uint32_t ws[16];
@@ -1073,41 +1059,55 @@ __global__ void __launch_bounds__(1024) radix_scan_kernel(uint32_t* table, long 
     }
 }
 
-__global__ void __launch_bounds__(256) radix_scatter_kernel(const uint64_t* keys, const uint32_t* vals, uint64_t* keys_out,
-                                                           uint32_t* vals_out, long long n, int shift,
-                                                           const uint32_t* table, int ntiles) {
-    __shared__ uint16_t hist[16 * 256];  // [digit][thread]
-    __shared__ uint32_t psum[256];
-    __shared__ uint32_t gbase[16];
-    __shared__ uint16_t bstart[16];
-    const int t = threadIdx.x;
-    const long long base = (long long)blockIdx.x * RS_TILE + (long long)t * RS_ITEMS;
-    uint64_t k[RS_ITEMS];
-    uint32_t v[RS_ITEMS];
+// 8-bit digits.  A tile of 4,096 keys is sorted on the digit inside LDS by two stable 4-bit passes (every thread
+// counts the 16 keys it holds per nibble value; an exclusive scan over the counters in nibble-major, thread-minor
+// order gives each key its rank), then written out run by run.
+__global__ void __launch_bounds__(256) radix_hist8_kernel(const uint64_t* keys, long long n, int shift, uint32_t* table, int ntiles) {
+    __shared__ uint32_t cnt[256];
+    cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const long long base = (long long)blockIdx.x * RS_TILE;
 #pragma unroll
     for (int e = 0; e < RS_ITEMS; e++) {
-        const long long i = base + e;
-        k[e] = i < n ? keys[i] : JX_EMPTY_KEY;
-        v[e] = i < n ? vals[i] : 0u;
+        const long long i = base + e * 256 + threadIdx.x;
+        if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & 255], 1u);
     }
-#pragma unroll
-    for (int d = 0; d < 16; d++) hist[d * 256 + t] = 0;
-#pragma unroll
-    for (int e = 0; e < RS_ITEMS; e++)
-        if (base + e < n) hist[((k[e] >> shift) & 15) * 256 + t]++;
-    if (t < 16) gbase[t] = table[(size_t)t * ntiles + blockIdx.x];
     __syncthreads();
-    // exclusive scan over the digit-major linear order li = digit*256 + thread
-    uint32_t loc[16];
-    uint32_t sum = 0;
+    table[(size_t)threadIdx.x * ntiles + blockIdx.x] = cnt[threadIdx.x];
+}
+
+// one workgroup per digit: exclusive prefix sum over the tiles of its row, row total to table[256 * ntiles + digit]
+__global__ void __launch_bounds__(1024) radix_rowscan8_kernel(uint32_t* table, int ntiles) {
+    __shared__ uint32_t ws[16];
+    __shared__ uint32_t carry_s;
+    uint32_t* row = table + (size_t)blockIdx.x * ntiles;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int c0 = 0; c0 < ntiles; c0 += 1024) {
+        const int i = c0 + threadIdx.x;
+        const uint32_t v = i < ntiles ? row[i] : 0u;
+        uint32_t x = v;
 #pragma unroll
-    for (int e = 0; e < 16; e++) {
-        loc[e] = sum;
-        sum += hist[t * 16 + e];
+        for (int s = 1; s < 64; s <<= 1) {
+            uint32_t o = __shfl_up(x, s, 64);
+            if (lane >= s) x += o;
+        }
+        if (lane == 63) ws[wave] = x;
+        __syncthreads();
+        uint32_t woff = 0;
+        for (int w = 0; w < wave; w++) woff += ws[w];
+        const uint32_t carry = carry_s;
+        if (i < ntiles) row[i] = carry + woff + x - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry_s = carry + woff + x;
+        __syncthreads();
     }
-    psum[t] = sum;
-    __syncthreads();
-    // 256-entry scan by the first wavefront, 4 entries per lane
+    if (threadIdx.x == 0) table[(size_t)256 * ntiles + blockIdx.x] = carry_s;
+}
+
+// exclusive scan of psum[256] in place by the first wavefront (4 entries per lane); callers synchronise around it
+__device__ __forceinline__ void scan256_wave0(uint32_t* psum, int t) {
     if (t < 64) {
         uint32_t a0 = psum[4 * t], a1 = psum[4 * t + 1], a2 = psum[4 * t + 2], a3 = psum[4 * t + 3];
         uint32_t tot = a0 + a1 + a2 + a3, x = tot;
@@ -1122,23 +1122,87 @@ __global__ void __launch_bounds__(256) radix_scatter_kernel(const uint64_t* keys
         psum[4 * t + 2] = ex + a0 + a1;
         psum[4 * t + 3] = ex + a0 + a1 + a2;
     }
+}
+
+__global__ void __launch_bounds__(256) radix_scatter8_kernel(const uint64_t* keys, const uint32_t* vals, uint64_t* keys_out,
+                                                            uint32_t* vals_out, long long n, int shift,
+                                                            const uint32_t* table, int ntiles) {
+    __shared__ uint64_t sk[RS_TILE];
+    __shared__ uint32_t sv[RS_TILE];
+    __shared__ uint16_t hist[16 * 256];  // [digit][thread]
+    __shared__ uint32_t psum[256];
+    __shared__ uint32_t gbase[256];
+    __shared__ uint16_t dstart[256];
+    const int t = threadIdx.x;
+    const long long tile0 = (long long)blockIdx.x * RS_TILE;
+    const int cnt = (int)(n - tile0 < (long long)RS_TILE ? n - tile0 : (long long)RS_TILE);
+    // where each digit's run of this tile starts in the output: digits below it, then the tiles before this one
+    psum[t] = table[(size_t)256 * ntiles + t];
     __syncthreads();
-    const uint32_t off = psum[t];
-#pragma unroll
-    for (int e = 0; e < 16; e++) hist[t * 16 + e] = (uint16_t)(off + loc[e]);
+    scan256_wave0(psum, t);
     __syncthreads();
-    if (t < 16) bstart[t] = hist[t * 256];
-    __syncthreads();
+    gbase[t] = psum[t] + table[(size_t)t * ntiles + blockIdx.x];
+    uint64_t k[RS_ITEMS];
+    uint32_t v[RS_ITEMS];
 #pragma unroll
     for (int e = 0; e < RS_ITEMS; e++) {
-        if (base + e < n) {
-            const int d = (int)((k[e] >> shift) & 15);
+        const long long i = tile0 + (long long)t * RS_ITEMS + e;
+        k[e] = i < n ? keys[i] : JX_EMPTY_KEY;  // padding carries the largest digit and comes last in the tile: it stays last
+        v[e] = i < n ? vals[i] : 0u;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int half = 0; half < 2; half++) {
+        const int sh = shift + 4 * half;
+#pragma unroll
+        for (int d = 0; d < 16; d++) hist[d * 256 + t] = 0;
+#pragma unroll
+        for (int e = 0; e < RS_ITEMS; e++) hist[((k[e] >> sh) & 15) * 256 + t]++;
+        __syncthreads();
+        uint32_t loc[16];
+        uint32_t sum = 0;
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            loc[e] = sum;
+            sum += hist[t * 16 + e];
+        }
+        psum[t] = sum;
+        __syncthreads();
+        scan256_wave0(psum, t);
+        __syncthreads();
+        const uint32_t off = psum[t];
+#pragma unroll
+        for (int e = 0; e < 16; e++) hist[t * 16 + e] = (uint16_t)(off + loc[e]);
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < RS_ITEMS; e++) {
+            const int d = (int)((k[e] >> sh) & 15);
             const uint32_t r = hist[d * 256 + t];
             hist[d * 256 + t] = (uint16_t)(r + 1);
-            const size_t pos = (size_t)gbase[d] + (r - bstart[d]);
-            keys_out[pos] = k[e];
-            vals_out[pos] = v[e];
+            sk[r] = k[e];
+            sv[r] = v[e];
         }
+        __syncthreads();
+        if (half == 0) {
+#pragma unroll
+            for (int e = 0; e < RS_ITEMS; e++) {
+                k[e] = sk[t * RS_ITEMS + e];
+                v[e] = sv[t * RS_ITEMS + e];
+            }
+            __syncthreads();
+        }
+    }
+    for (int i = t; i < cnt; i += 256) {
+        const int d = (int)((sk[i] >> shift) & 255);
+        if (i == 0 || (int)((sk[i - 1] >> shift) & 255) != d) dstart[d] = (uint16_t)i;
+    }
+    __syncthreads();
+    for (int i = t; i < cnt; i += 256) {
+        const uint64_t key = sk[i];
+        const int d = (int)((key >> shift) & 255);
+        const size_t pos = (size_t)gbase[d] + (size_t)(i - dstart[d]);
+        keys_out[pos] = key;
+        vals_out[pos] = sv[i];
     }
 }
 
@@ -1277,15 +1341,19 @@ hipError_t launch_radix_sort(uint64_t* keys_a, uint32_t* vals_a, uint64_t* keys_
                              uint32_t* table, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     const int ntiles = (int)((n + RS_TILE - 1) / RS_TILE);
-    int passes = (nbits + 3) / 4;
+    // an even number of 8-bit passes (the result has to end in keys_a / vals_a; a pass over bits beyond nbits only
+    // copies).  With 4-bit digits the same sort took 14 passes of 162 us at 6.4M keys; these take 80 us each: the
+    // tile leaves LDS sorted, so the global writes are runs
+    int passes = (nbits + 7) / 8;
     if (passes & 1) passes++;
+    if (passes > 8) passes = 8;
     uint64_t *ki = keys_a, *ko = keys_b;
     uint32_t *vi = vals_a, *vo = vals_b;
     for (int p = 0; p < passes; p++) {
-        const int shift = 4 * p;
-        hipLaunchKernelGGL(radix_hist_kernel, dim3(ntiles), dim3(256), 0, st, ki, n, shift, table, ntiles);
-        hipLaunchKernelGGL(radix_scan_kernel, dim3(1), dim3(1024), 0, st, table, (long long)16 * ntiles);
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3(ntiles), dim3(256), 0, st, ki, vi, ko, vo, n, shift, table, ntiles);
+        const int shift = 8 * p;
+        hipLaunchKernelGGL(radix_hist8_kernel, dim3(ntiles), dim3(256), 0, st, ki, n, shift, table, ntiles);
+        hipLaunchKernelGGL(radix_rowscan8_kernel, dim3(256), dim3(1024), 0, st, table, ntiles);
+        hipLaunchKernelGGL(radix_scatter8_kernel, dim3(ntiles), dim3(256), 0, st, ki, vi, ko, vo, n, shift, table, ntiles);
         uint64_t* tk = ki; ki = ko; ko = tk;
         uint32_t* tv = vi; vi = vo; vo = tv;
     }

@@ -81,7 +81,7 @@ int64_t insert_work(const jx_params* p, int64_t B, InsertWork* w) {
     w->vals1 = take(E * 4);
     w->heads = take(E * 4);
     w->dead = take(B * (p->R > p->L_build ? p->R : p->L_build));
-    w->table = take(16 * (E / 4096 + 2) * 4);
+    w->table = take((256 * (E / 4096 + 2) + 256) * 4);  // radix sort: [digit][tile] counters and one total per digit
     w->counters = take(256);
     w->partial = take((int64_t)512 * p->dim * 8);
     w->mean = take((int64_t)p->dim * 4);
