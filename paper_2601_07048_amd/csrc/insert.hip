@@ -1208,10 +1208,18 @@ __global__ void __launch_bounds__(256) radix_scatter8_kernel(const uint64_t* key
 
 __global__ void __launch_bounds__(256) segment_heads_kernel(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg) {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const uint32_t t = (uint32_t)(keys[i] >> 32);
-    if (t == JX_NONE_ID) return;
-    if (i == 0 || (uint32_t)(keys[i - 1] >> 32) != t) heads[atomicAdd(nseg, 1u)] = (uint32_t)i;
+    bool is_head = false;
+    if (i < n) {
+        const uint32_t t = (uint32_t)(keys[i] >> 32);
+        is_head = t != JX_NONE_ID && (i == 0 || (uint32_t)(keys[i - 1] >> 32) != t);
+    }
+    // one atomic per wavefront instead of one per segment (the order of the list does not matter)
+    const uint64_t m = ballot(is_head);
+    if (m == 0ull) return;
+    uint32_t base = 0;
+    if (lane_id() == 0) base = atomicAdd(nseg, (uint32_t)__builtin_popcountll(m));
+    base = readlane32(base, 0);
+    if (is_head) heads[base + prefix_count(m)] = (uint32_t)i;
 }
 
 // ------------------------------------------------------------------ launchers
