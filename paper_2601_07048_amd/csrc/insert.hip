@@ -1206,20 +1206,47 @@ __global__ void __launch_bounds__(256) radix_scatter8_kernel(const uint64_t* key
     }
 }
 
-__global__ void __launch_bounds__(256) segment_heads_kernel(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg) {
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    bool is_head = false;
-    if (i < n) {
-        const uint32_t t = (uint32_t)(keys[i] >> 32);
-        is_head = t != JX_NONE_ID && (i == 0 || (uint32_t)(keys[i - 1] >> 32) != t);
+__global__ void __launch_bounds__(1024) segment_heads_kernel(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg) {
+    __shared__ uint32_t woff[17];
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    // 4 consecutive keys per thread
+    const long long i0 = ((long long)blockIdx.x * 1024 + threadIdx.x) * 4;
+    bool is_head[4];
+    int mine = 0;
+    uint32_t prev = JX_NONE_ID;
+    if (i0 > 0 && i0 < n) prev = (uint32_t)(keys[i0 - 1] >> 32);
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        const long long i = i0 + e;
+        uint32_t t = JX_NONE_ID;
+        if (i < n) t = (uint32_t)(keys[i] >> 32);
+        is_head[e] = t != JX_NONE_ID && (i == 0 || t != prev);
+        mine += is_head[e] ? 1 : 0;
+        prev = t;
     }
-    // one atomic per wavefront instead of one per segment (the order of the list does not matter)
-    const uint64_t m = ballot(is_head);
-    if (m == 0ull) return;
-    uint32_t base = 0;
-    if (lane_id() == 0) base = atomicAdd(nseg, (uint32_t)__builtin_popcountll(m));
-    base = readlane32(base, 0);
-    if (is_head) heads[base + prefix_count(m)] = (uint32_t)i;
+    // one atomic per workgroup (same-address atomics serialise; the order of the list does not matter)
+    uint32_t x = (uint32_t)mine;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        uint32_t o = __shfl_up(x, s, 64);
+        if (lane >= s) x += o;
+    }
+    if (lane == 63) woff[wave] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t tot = 0;
+        for (int w = 0; w < 16; w++) {
+            const uint32_t c = woff[w];
+            woff[w] = tot;
+            tot += c;
+        }
+        woff[16] = tot ? atomicAdd(nseg, tot) : 0u;
+    }
+    __syncthreads();
+    uint32_t pos = woff[16] + woff[wave] + x - (uint32_t)mine;
+#pragma unroll
+    for (int e = 0; e < 4; e++)
+        if (is_head[e]) heads[pos++] = (uint32_t)(i0 + e);
 }
 
 // ------------------------------------------------------------------ launchers
@@ -1381,7 +1408,7 @@ hipError_t launch_argmin(const double* dist, long long n, uint32_t* out_id, hipS
 
 hipError_t launch_segment_heads(const uint64_t* keys, long long n, uint32_t* heads, uint32_t* nseg, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(segment_heads_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, keys, n, heads, nseg);
+    hipLaunchKernelGGL(segment_heads_kernel, dim3((unsigned)((n + 4095) / 4096)), dim3(1024), 0, st, keys, n, heads, nseg);
     return hipGetLastError();
 }
 
