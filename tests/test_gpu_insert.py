@@ -50,6 +50,15 @@ def _graphs(ref, g):
     (6000, 128, 20, 40, None, 0.25),      # small merges: one or two 32-slot tiles of the Gram-matrix path
     (6000, 128, 90, 128, None, 0.25),     # merges beyond 96 candidates: the global-memory path
     (5000, 128, 64, 64, [2500, 2500], 0.25),
+    # 128-byte vectors take the lean prune and merge kernels: degenerate degrees and frontiers
+    (600, 128, 1, 1, None, 0.25),
+    (600, 128, 1, 4, [1, 599], 1.0),
+    (800, 128, 2, 3, None, 0.25),
+    (800, 128, 3, 8, None, 0.5),
+    (1500, 128, 5, 128, None, 0.25),      # far more candidates than room: every round ends on the R cap
+    (1200, 128, 127, 128, None, 0.25),    # rows of 127 + new edges: the 128-slot limit of the lean merge
+    (1200, 128, 200, 128, None, 0.25),    # R above the frontier width: rows never fill from the forward prune
+    (3000, 128, 12, 128, [100] * 30, 1.0),  # many small calls: appended tails between prunes
 ])
 def test_insert_u8_graph_bit_exact(jx, n, d, R, L, calls, growth):
     x = random_data(n, d, np.uint8, seed=n + R)
