@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of one timed launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command
 # (profiles/beam_search_u8_N1M_L96.md); reported only when the run has the same shape.
-MEASURED_TRAFFIC = {(2, 1_000_000, 10_000, 96): 2.737e9 + 7.07e6,
+MEASURED_TRAFFIC = {(2, 1_000_000, 10_000, 96): 2.985e9 + 1.92e6,
                     (3, 1_000_000, 10_000, 512): 4.765e10 + 3.85e6,   # profiles/build_search_f32_d960_4bit_N1M.md
                     (4, 1_000_000, 10_000, 512): 2.087e10 + 3.85e6}   # profiles/build_search_f32_d1536_1bit_N1M.md
 
@@ -253,7 +253,10 @@ def main():
     out_k = rerank if rerank else k
     alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * qrec + nq * out_k * 8
     achieved = alg_bytes / (beam_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": sp["kernel"], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+    kernel_name = sp["kernel"]
+    if sp["u8"] and not sp["bits"] and 64 <= L_star <= 128 and nq <= 32768 and R <= 64 and os.environ.get("JX_BEAM_PAIR") is None:
+        kernel_name = "beam_search_pair_kernel<u8>"  # the two-expansions-per-round form serves this shape
+    roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((wl, n, nq, L_star)) if not args.bits else None,
                 "bytes_per_launch": int(alg_bytes), "kernel_ms": round(beam_ms, 4),
                 "hops_per_query": round(st["hops"] / nq, 1), "dist_evals_per_query": round(st["dist_evals"] / nq, 1),
