@@ -319,7 +319,7 @@ __device__ __forceinline__ void frontier_merge(uint64_t (&fk)[NREG], uint64_t* f
 
 // rows of at most 64 entries only (the launcher checks)
 template <int KIND, int T, int CPL, int NREG, int QB>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NREG <= 2 ? JX_WPE_EXACT : 1, 8)))
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(((KIND <= K_F32 || KIND == K_F16) && NREG <= 2 && CPL <= 2) ? JX_WPE_EXACT : 1, 8)))
 beam_search_pair_kernel(BeamArgs a) {
     constexpr int G = 64 / T;
     constexpr int U0 = (8 / CPL) > 0 ? (8 / CPL) : 1;
@@ -538,9 +538,10 @@ static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st) {
     const int nreg = (a.L + 63) / 64;
     const int H = a.hash_slots;
     dim3 grid((unsigned)((a.nq + JX_BEAM_WPB - 1) / JX_BEAM_WPB)), block(JX_BEAM_WPB * 64);
-    if constexpr (KIND == K_U8) {
+    if constexpr (CPL <= 2 && (KIND == K_U8 || KIND == K_RQ4 || KIND == K_RQ1)) {
         // batches that do not fill the machine several times over are bound by the lifetime of a query: two
-        // expansions per round (JX_BEAM_PAIR=0 switches it off)
+        // expansions per round (JX_BEAM_PAIR=0 switches it off).  Not for float vectors: their searches are bound by
+        // bandwidth, and the dropped second lists cost 12 % at d = 200, L = 128
         if (nreg <= 2 && a.L >= 64 && a.R <= 64 && a.nq <= pair_max_queries()) {  // measured: +2..5 % from L = 64, -3 % at L = 32
             const size_t sh = (size_t)nreg * 64 * 8 + 128 * 8 + 128 * 4 + (size_t)H * (a.tag_bits ? 2 : 4);
             dim3 pgrid((unsigned)a.nq), pblock(64);
