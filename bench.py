@@ -254,7 +254,7 @@ def main():
     alg_bytes = st["adj_bytes"] + st["vec_bytes"] + nq * qrec + nq * out_k * 8
     achieved = alg_bytes / (beam_ms * 1e-3) / 1e9
     kernel_name = sp["kernel"]
-    if (sp["u8"] or sp["bits"]) and 64 <= L_star <= 128 and nq <= 32768 and R <= 64 and os.environ.get("JX_BEAM_PAIR") is None:
+    if sp["u8"] and 64 <= L_star <= 128 and nq <= 32768 and R <= 64 and os.environ.get("JX_BEAM_PAIR") is None:
         kernel_name = kernel_name.replace("beam_search_kernel", "beam_search_pair_kernel")  # two expansions per round
     roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((wl, n, nq, L_star)) if not args.bits else None,

@@ -541,8 +541,10 @@ static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st) {
     if constexpr (CPL <= 2 && (KIND == K_U8 || KIND == K_RQ4 || KIND == K_RQ1)) {
         // batches that do not fill the machine several times over are bound by the lifetime of a query: two
         // expansions per round (JX_BEAM_PAIR=0 switches it off).  Not for float vectors: their searches are bound by
-        // bandwidth, and the dropped second lists cost 12 % at d = 200, L = 128
-        if (nreg <= 2 && a.L >= 64 && a.R <= 64 && a.nq <= pair_max_queries()) {  // measured: +2..5 % from L = 64, -3 % at L = 32
+        // bandwidth, and the dropped second lists cost 12 % at d = 200, L = 128.
+        // measured: +2..6 % for records of one 128-byte line from L = 64 (-3 % at L = 32); -8..-11 % for the 496- and
+        // 208-byte records of d = 960 / 1536 codes, whose searches run at 7 TB/s and pay for every dropped list
+        if (nreg <= 2 && a.L >= 64 && a.R <= 64 && a.ds.rec_stride <= 128 && a.nq <= pair_max_queries()) {
             const size_t sh = (size_t)nreg * 64 * 8 + 128 * 8 + 128 * 4 + (size_t)H * (a.tag_bits ? 2 : 4);
             dim3 pgrid((unsigned)a.nq), pblock(64);
             if (nreg <= 1)
