@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7, 8])
-    ap.add_argument("--n", type=int, default=1_000_000)
+    ap.add_argument("--n", type=int, default=0, help="base vectors (0 = the workload's own: 1,000,000; 10,000,000 for the streaming workload 5)")
     ap.add_argument("--nq", type=int, default=10_000)
     ap.add_argument("--recall", type=float, default=0.95)
     ap.add_argument("--L", type=int, default=0, help="force the beam width (0 = smallest with recall >= target)")
@@ -89,7 +89,7 @@ def main():
     wl = args.workload
     sp = SPEC[wl]
     R, L_build, alpha, k, d = 64, 128, 1.2, 10, sp["d"]
-    n, nq = args.n, args.nq
+    n, nq = args.n or (10_000_000 if args.workload == 5 else 1_000_000), args.nq
     if args.bits and sp["bits"]:
         sp = dict(sp, bits=args.bits, kernel=f"beam_search_kernel<{args.bits}-bit RaBitQ>",
                   text=sp["text"].replace("4-bit", f"{args.bits}-bit").replace("1-bit", f"{args.bits}-bit"))
