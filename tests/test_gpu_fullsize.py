@@ -76,6 +76,45 @@ def test_fullsize_search_sampled_against_oracle(jx, big):
     assert np.array_equal(gd.cpu().numpy().astype(np.float64)[sample[:16]], od)
 
 
+def test_fullsize_two_expansions_per_round_equal_one(jx, big):
+    """All 10,000 queries at the beam widths the two-expansion kernel serves: ids, distances and the expansion and
+    evaluation counters equal those of the one-expansion kernel (JX_BEAM_PAIR=0 is read once per process, so the
+    other side runs in a child process on the same graph, imported from a file)."""
+    import hashlib
+    import os
+    import subprocess
+    import sys
+    import tempfile
+    x, q, g, adj, deg = big
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r"""
+import sys, hashlib, numpy as np, torch
+from paper_2601_07048_amd import jx, datagen
+n, entry, path = int(sys.argv[1]), int(sys.argv[2]), sys.argv[3]
+x = torch.from_numpy(datagen.base(2, n)).cuda()
+adj = torch.from_numpy(np.load(path)).cuda()
+g = jx.Index(128, jx.U8, 64, 128, 1.2, capacity=n, max_batch=n // 4 + 1)
+g.import_graph(x, adj, entry)
+q = torch.from_numpy(datagen.queries(2, 10000)).cuda()
+for L in (64, 96, 128):
+    ids, dist, st = g.search(q, 10, L, stats=True)
+    h = hashlib.sha256(ids.cpu().numpy().tobytes() + dist.cpu().numpy().tobytes()).hexdigest()
+    print('res', L, h, st['hops'], st['dist_evals'])
+"""
+    with tempfile.TemporaryDirectory() as td:
+        path = os.path.join(td, "adj.npy")
+        np.save(path, u32(adj))
+        r = subprocess.run([sys.executable, "-c", code, str(N), str(g.size()[1]), path], cwd=root,
+                           env=dict(os.environ, JX_BEAM_PAIR="0"), capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and r.stdout.count("res ") == 3, r.stdout[-2000:] + r.stderr[-2000:]
+    want = {int(l.split()[1]): l.split()[2:] for l in r.stdout.splitlines() if l.startswith("res ")}
+    dq = dev(q)
+    for L in (64, 96, 128):
+        ids, dist, st = g.search(dq, 10, L, stats=True)
+        h = hashlib.sha256(ids.cpu().numpy().tobytes() + dist.cpu().numpy().tobytes()).hexdigest()
+        assert [h, str(st["hops"]), str(st["dist_evals"])] == want[L], L
+
+
 def test_fullsize_build_matches_oracle(jx, big):
     """The whole 1M-point adjacency table against the oracle's build with the
     same insertion order and batch schedule (about a minute on 16 host cores)."""
