@@ -857,41 +857,24 @@ __global__ void __launch_bounds__(64) reverse_merge_u8_lean_kernel(InsertArgs a)
 // resolved in order: a pivot that is still live is selected and discards what it discards, one that an earlier
 // pivot discarded is skipped (its tests were wasted).  Every test is the pairwise test of Alg. 3 on exact
 // integers, so the result is the sequential algorithm's.
+template <int MAXC>
 struct FwdLds {
-    uint32_t id[128];
-    float dx[128];        // d(x, candidate)
-    uint32_t sel_id[128];
-    uint32_t sel_dist[128];
-    uint8_t cand[128];    // live candidates behind the first pivot, compacted
-    uint8_t kb[128];      // bit i: pivot i discards this candidate
+    uint32_t id[MAXC];
+    float dx[MAXC];        // d(x, candidate)
+    uint32_t sel_id[MAXC];
+    uint32_t sel_dist[MAXC];
+    uint16_t cand[MAXC];   // live candidates behind the first pivot, compacted
+    uint8_t kb[MAXC];      // bit i: pivot i discards this candidate
 };
 
-__global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a) {
-    __shared__ FwdLds lds;
-    FwdLds* F = &lds;
+// The rounds described above on the candidates F->id / F->dx (sorted by (distance, id); alive = one bit per
+// candidate).  Returns the number of selected neighbours, F->sel_id / F->sel_dist in selection order.
+template <int MAXC>
+__device__ __forceinline__ int multi_pivot_prune_u8(FwdLds<MAXC>* F, const uint8_t* recs, uint64_t (&alive)[MAXC / 64], const int R,
+                                                    const float alpha) {
+    constexpr int NW = MAXC / 64;
     const int lane = lane_id();
     const int g = lane >> 2, lig = lane & 3;
-    const long long i = blockIdx.x;
-    if (i >= a.B) return;
-    long long xid = a.id_base + i;
-    if (xid >= a.id_skip) xid++;
-    const uint32_t* ids = a.cand_ids + (size_t)i * a.L;
-    const uint32_t* dbits = a.cand_dist + (size_t)i * a.L;
-    const uint8_t* recs = a.ds.recs;
-    uint64_t alive[2];
-#pragma unroll
-    for (int h = 0; h < 2; h++) {
-        const int j = h * 64 + lane;
-        uint32_t id = JX_NONE_ID;
-        if (j < a.L) id = ids[j];
-        const bool valid = id != JX_NONE_ID;
-        if (valid) {
-            F->id[j] = id;
-            F->dx[j] = __uint_as_float(dbits[j]);
-        }
-        alive[h] = ballot(valid);  // the frontier is filled from the left
-    }
-    wave_sync();
     auto dot = [](const uint4 (&x)[2], const uint4 (&y)[2]) {
         uint32_t t = 0;
         t = __builtin_amdgcn_udot4(x[0].x, y[0].x, t, false);
@@ -904,25 +887,34 @@ __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a)
         t = __builtin_amdgcn_udot4(x[1].w, y[1].w, t, false);
         return t;
     };
+    auto any_alive = [&]() {
+        uint64_t m = 0;
+#pragma unroll
+        for (int w = 0; w < NW; w++) m |= alive[w];
+        return m != 0ull;
+    };
     int nsel = 0;
-    while (nsel < a.R && (alive[0] | alive[1])) {
+    while (nsel < R && any_alive()) {
         // ---- pivots: the next live candidates, as many as may still be selected, at most four
         int t[4], np = 0;
         {
-            uint64_t m0 = alive[0], m1 = alive[1];
-            const int room = a.R - nsel < 4 ? a.R - nsel : 4;
+            uint64_t m[NW];
+#pragma unroll
+            for (int w = 0; w < NW; w++) m[w] = alive[w];
+            const int room = R - nsel < 4 ? R - nsel : 4;
 #pragma unroll
             for (int k = 0; k < 4; k++) {
                 t[k] = 0;
                 if (k < room) {
-                    if (m0) {
-                        t[k] = __builtin_ctzll(m0);
-                        m0 &= m0 - 1ull;
-                        np = k + 1;
-                    } else if (m1) {
-                        t[k] = 64 + __builtin_ctzll(m1);
-                        m1 &= m1 - 1ull;
-                        np = k + 1;
+                    bool found = false;
+#pragma unroll
+                    for (int w = 0; w < NW; w++) {
+                        if (!found && m[w]) {
+                            t[k] = 64 * w + __builtin_ctzll(m[w]);
+                            m[w] &= m[w] - 1ull;
+                            np = k + 1;
+                            found = true;
+                        }
                     }
                 }
             }
@@ -930,14 +922,14 @@ __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a)
         // ---- live candidates behind the first pivot
         int n_alive = 0;
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
+        for (int h = 0; h < NW; h++) {
             const int j = h * 64 + lane;
             const bool on = ((alive[h] >> lane) & 1ull) && j > t[0];
             const uint64_t m = ballot(on);
-            if (on) F->cand[n_alive + prefix_count(m)] = (uint8_t)j;
+            if (on) F->cand[n_alive + prefix_count(m)] = (uint16_t)j;
             n_alive += __builtin_popcountll(m);
         }
-        if (n_alive == 0 || nsel + 1 >= a.R) {
+        if (n_alive == 0 || nsel + 1 >= R) {
             // the last neighbour there is, or the last one there is room for: nothing left to discard
             if (lane == 0) {
                 F->sel_id[nsel] = F->id[t[0]];
@@ -979,16 +971,16 @@ __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a)
                 for (int k = 0; k < 4; k++) {
                     if (k < np) {
                         const uint32_t dk = (uint32_t)group_sum<4>((int32_t)aa - 2 * (int32_t)dot(x[u], qd[k])) + qqd[k];
-                        if (jc[u] > t[k] && __fmul_rn(a.alpha, (float)dk) <= dxc) bits |= 1u << k;
+                        if (jc[u] > t[k] && __fmul_rn(alpha, (float)dk) <= dxc) bits |= 1u << k;
                     }
                 }
                 if (lig == 0 && jj[u] < n_alive) F->kb[jc[u]] = (uint8_t)bits;
             }
         }
         wave_sync();
-        uint64_t K[4][2];
+        uint64_t K[4][NW];
 #pragma unroll
-        for (int h = 0; h < 2; h++) {
+        for (int h = 0; h < NW; h++) {
             const int j = h * 64 + lane;
             const bool on = ((alive[h] >> lane) & 1ull) && j > t[0];
             const uint32_t b = on ? (uint32_t)F->kb[j] : 0u;
@@ -998,23 +990,57 @@ __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a)
         // ---- resolve the pivots in order
 #pragma unroll
         for (int k = 0; k < 4; k++) {
-            if (k < np && nsel < a.R) {
+            if (k < np && nsel < R) {
                 const int tk = t[k];
-                if ((alive[tk >> 6] >> (tk & 63)) & 1ull) {
+                bool live = false;
+#pragma unroll
+                for (int w = 0; w < NW; w++)
+                    if (w == (tk >> 6)) live = (alive[w] >> (tk & 63)) & 1ull;
+                if (live) {
                     if (lane == 0) {
                         F->sel_id[nsel] = F->id[tk];
                         F->sel_dist[nsel] = __float_as_uint(F->dx[tk]);
                     }
                     nsel++;
-                    alive[tk >> 6] &= ~(1ull << (tk & 63));
-                    alive[0] &= ~K[k][0];
-                    alive[1] &= ~K[k][1];
+#pragma unroll
+                    for (int w = 0; w < NW; w++) {
+                        if (w == (tk >> 6)) alive[w] &= ~(1ull << (tk & 63));
+                        alive[w] &= ~K[k][w];
+                    }
                 }
             }
         }
         wave_sync();
     }
     wave_sync();
+    return nsel;
+}
+
+__global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a) {
+    __shared__ FwdLds<128> lds;
+    FwdLds<128>* F = &lds;
+    const int lane = lane_id();
+    const long long i = blockIdx.x;
+    if (i >= a.B) return;
+    long long xid = a.id_base + i;
+    if (xid >= a.id_skip) xid++;
+    const uint32_t* ids = a.cand_ids + (size_t)i * a.L;
+    const uint32_t* dbits = a.cand_dist + (size_t)i * a.L;
+    uint64_t alive[2];
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const int j = h * 64 + lane;
+        uint32_t id = JX_NONE_ID;
+        if (j < a.L) id = ids[j];
+        const bool valid = id != JX_NONE_ID;
+        if (valid) {
+            F->id[j] = id;
+            F->dx[j] = __uint_as_float(dbits[j]);
+        }
+        alive[h] = ballot(valid);  // the frontier is filled from the left
+    }
+    wave_sync();
+    const int nsel = multi_pivot_prune_u8<128>(F, a.ds.recs, alive, a.R, a.alpha);
     uint32_t* row = a.adj + (size_t)xid * a.R;
     for (int j = lane; j < a.R; j += 64) {
         const bool on = j < nsel;
@@ -1024,6 +1050,53 @@ __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a)
         a.vals[(size_t)i * a.R + j] = on ? (uint32_t)xid : JX_NONE_ID;
     }
     if (a.clean && lane == 0) a.clean[xid] = (uint8_t)(nsel < 255 ? nsel : 255);
+}
+
+// The same rounds for consolidation after deletions (Sec. 4.6): the segment holds the whole candidate set of its
+// vertex, sorted by (distance, id); sets of at most 512 are pruned here and marked, larger ones are left to the
+// general kernel.
+__global__ void __launch_bounds__(64) consol_prune_u8_lean_kernel(InsertArgs a) {
+    __shared__ FwdLds<512> lds;
+    FwdLds<512>* F = &lds;
+    const int lane = lane_id();
+    const long long nseg = *a.nseg;
+    const long long total = a.E ? a.E : a.B * a.R;
+    for (long long s = blockIdx.x; s < nseg; s += gridDim.x) {
+        const uint32_t head = a.heads[s];
+        if (head & 0x80000000u) continue;
+        const long long lo = head;
+        const uint32_t v = (uint32_t)(a.keys[lo] >> 32);
+        if (v == JX_NONE_ID) continue;
+        int m = 0;
+        for (long long c0 = lo; c0 < total; c0 += 64) {
+            const long long j = c0 + lane;
+            const bool same = j < total && (uint32_t)(a.keys[j] >> 32) == v;
+            const uint64_t sm = ballot(same);
+            m += __builtin_popcountll(sm);
+            if (sm != ~0ull) break;
+        }
+        if (m > 512) continue;
+        wave_sync();  // the previous segment's reads of the LDS arrays are done
+        uint64_t alive[8];
+#pragma unroll
+        for (int h = 0; h < 8; h++) {
+            const int j = h * 64 + lane;
+            const bool valid = j < m;
+            if (valid) {
+                F->id[j] = a.vals[lo + j];
+                F->dx[j] = __uint_as_float((uint32_t)a.keys[lo + j]);
+            }
+            alive[h] = ballot(valid);
+        }
+        wave_sync();
+        const int nsel = multi_pivot_prune_u8<512>(F, a.ds.recs, alive, a.R, a.alpha);
+        uint32_t* row = a.adj + (size_t)v * a.R;
+        for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? F->sel_id[j] : JX_NONE_ID;
+        if (lane == 0) {
+            if (a.clean) a.clean[v] = (uint8_t)(nsel < 255 ? nsel : 255);
+            const_cast<uint32_t*>(a.heads)[s] = head | 0x80000000u;
+        }
+    }
 }
 
 // ------------------------------------------------------------------ radix sort
@@ -1355,6 +1428,14 @@ hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st) 
 hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st) {
     if (a.gram) {
         hipError_t e = launch_reverse_merge_gram(dtype, a, st);
+        if (e != hipSuccess) return e;
+    }
+    if (dtype == JX_U8 && a.force_prune && a.ds.rec_stride == 128 && a.ds.nch == 8 && lean_forward_prune()) {
+        // consolidation: candidate sets of at most 512 take the multi-pivot form
+        const long long want = a.E ? a.E : a.B * a.R;
+        const unsigned grid = (unsigned)(want < 8192 ? (want < 1 ? 1 : want) : 8192);
+        hipLaunchKernelGGL(consol_prune_u8_lean_kernel, dim3(grid), dim3(64), 0, st, a);
+        hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (dtype == JX_U8 && a.clean && !a.force_prune && a.ds.rec_stride == 128 && a.ds.nch == 8) {
