@@ -65,6 +65,7 @@ extern "C" {
 #define JX_MAX_L 512    /* largest beam width L / L_build */
 #define JX_MAX_R 256    /* largest out-degree R */
 #define JX_MAX_BF_K 128 /* largest k of jx_bruteforce */
+#define JX_STATIC_SCRATCH_BYTES (16 << 20) /* device scratch of jx_bruteforce_static, held per GPU for the life of the process */
 
 typedef struct jx_index jx_index; /* opaque, host side */
 
@@ -181,6 +182,27 @@ int jx_beam_frontier(jx_index* idx, const void* d_queries, int64_t nq, int32_t L
  * ground truth of Sec. 6.1).  k <= JX_MAX_BF_K. */
 int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, uint32_t* d_out_ids,
                   float* d_out_dist, void* stream);
+
+/*
+ * jx_bruteforce for callers that cannot allocate device memory and have no
+ * arena either: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same kernels and same results as jx_bruteforce, but
+ * no index is needed: d_base is [n][dim] of `dtype` (JX_U8 | JX_F32 | JX_F16,
+ * dim a multiple of 16 / 4 / 8), d_queries [nq][dim] of the same type, outputs
+ * [nq][k], k <= JX_MAX_BF_K.  The per-query partial lists live in a scratch
+ * array of JX_STATIC_SCRATCH_BYTES that is part of the library's device code
+ * (one copy per GPU, resolved with hipGetSymbolAddress at the first call on
+ * that GPU); the call performs no hipMalloc / hipFree and calls no allocating
+ * library routine.  Limit: nq * nsplit * k * 8 <= JX_STATIC_SCRATCH_BYTES with
+ * nsplit = clamp(ceil(2048 / ceil(nq / 64)), 1, min(64, ceil(n / 64))) --
+ * e.g. 10,000 queries at k = 10 (nsplit 14: 11.2 MB), or any nq * k <= 32,768;
+ * beyond it JX_ECAPACITY and nothing is launched.  All calls on one GPU share
+ * that GPU's scratch: calls that overlap in time on one GPU (different streams
+ * or threads) race; consecutive calls on one stream are safe.  Nothing has to
+ * be cleared between calls: every list that is read is written first.
+ */
+int jx_bruteforce_static(const void* d_base, int64_t n, int32_t dim, int32_t dtype, const void* d_queries, int64_t nq,
+                         int32_t k, uint32_t* d_out_ids, float* d_out_dist, void* stream);
 
 /* Batch deletion (Sec. 4.6 and 6.5: mark, consolidate, compact; the scheme of
  * FreshDiskANN that the paper adopts).

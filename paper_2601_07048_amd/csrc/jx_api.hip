@@ -6,9 +6,15 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 #include <vector>
 #include "jx_internal.h"
+
+// Scratch of jx_bruteforce_static: one copy per GPU, held from the moment the code object is loaded until the
+// process ends.  Host code never uses this name as an address (it is only the host-side handle of the symbol); the
+// device address is looked up once per device with hipGetSymbolAddress, see static_scratch().
+static __device__ __align__(256) unsigned char scratch[JX_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -199,6 +205,35 @@ bool incremental_prune() {
 }
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// split of the base set used by the brute-force kernels: at least ~2048 workgroups, at most 64 partial lists per query
+int64_t bruteforce_nsplit(int64_t n, int64_t nq) {
+    int64_t tiles_b = (n + 63) / 64;
+    int64_t nqt = (nq + 63) / 64;
+    int64_t nsplit = (2048 + nqt - 1) / nqt;
+    if (nsplit > 64) nsplit = 64;
+    if (nsplit > tiles_b) nsplit = tiles_b;
+    if (nsplit < 1) nsplit = 1;
+    return nsplit;
+}
+
+// Device address of `scratch` on the current device, resolved on first use per device and kept.
+int static_scratch(unsigned char** out) {
+    static std::mutex mu;
+    static unsigned char* ptr[64] = {nullptr};
+    int dev = -1;
+    JX_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return fail(JX_EHIP, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        JX_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(JX_EHIP, "hipGetSymbolAddress returned a null address");
+        ptr[dev] = (unsigned char*)p;
+    }
+    *out = ptr[dev];
+    return JX_OK;
+}
 
 // Visited table of beamSearch for beam width L on n vertices.  While ids fit slots x 2^15 the table holds 16-bit
 // tags (see BeamArgs::tag_bits): twice the slots in the same LDS, 16 % fewer repeated distance evaluations at L = 96.
@@ -527,14 +562,8 @@ int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, u
     if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
     if (nq <= 0) return JX_OK;
     hipStream_t st = as_stream(stream);
-    // split the base set so that the grid has at least ~2048 workgroups, and
-    // slice the queries so that the per-slice partial lists fit the workspace
-    int64_t tiles_b = (idx->n + 63) / 64;
-    int64_t nqt = (nq + 63) / 64;
-    int64_t nsplit = (2048 + nqt - 1) / nqt;
-    if (nsplit > 64) nsplit = 64;
-    if (nsplit > tiles_b) nsplit = tiles_b;
-    if (nsplit < 1) nsplit = 1;
+    // split the base set, and slice the queries so that the per-slice partial lists fit the workspace
+    const int64_t nsplit = bruteforce_nsplit(idx->n, nq);
     int64_t per_q = nsplit * k * 8;
     int64_t slice = idx->work_bytes / per_q;
     slice = (slice / 64) * 64;
@@ -556,6 +585,41 @@ int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, u
         a.out_dist = d_out_dist + (size_t)q0 * k;
         JX_HIP(jx::launch_bruteforce(a, st));
     }
+    return JX_OK;
+}
+
+int jx_bruteforce_static(const void* d_base, int64_t n, int32_t dim, int32_t dtype, const void* d_queries, int64_t nq,
+                         int32_t k, uint32_t* d_out_ids, float* d_out_dist, void* stream) {
+    if (dtype != JX_U8 && dtype != JX_F32 && dtype != JX_F16) return fail(JX_EINVAL, "dtype must be JX_U8, JX_F32 or JX_F16");
+    if (dim <= 0 || (dtype == JX_U8 && dim % 16) || (dtype == JX_F32 && dim % 4) || (dtype == JX_F16 && dim % 8))
+        return fail(JX_EINVAL, "dim must be a positive multiple of 16 (uint8), 4 (float32) or 8 (binary16)");
+    if (n < 1 || n > 0x7FFFFFFELL) return fail(JX_EINVAL, "n out of range");
+    if (k < 1 || k > JX_MAX_BF_K) return fail(JX_EINVAL, "k must be in [1, %d]", JX_MAX_BF_K);
+    if (nq < 0) return fail(JX_EINVAL, "nq < 0");
+    if (nq == 0) return JX_OK;
+    if (!d_base || !d_queries || !d_out_ids || !d_out_dist) return fail(JX_EINVAL, "NULL argument");
+    const int64_t nsplit = bruteforce_nsplit(n, nq);
+    const int64_t need = nq * nsplit * k * 8;
+    if (need > (int64_t)JX_STATIC_SCRATCH_BYTES)
+        return fail(JX_ECAPACITY, "nq * nsplit * k * 8 = %lld * %lld * %d * 8 = %lld bytes of partial lists exceed the static scratch of %lld bytes",
+                    (long long)nq, (long long)nsplit, (int)k, (long long)need, (long long)JX_STATIC_SCRATCH_BYTES);
+    unsigned char* sc = nullptr;
+    int rc = static_scratch(&sc);
+    if (rc) return rc;
+    jx::BfArgs a;
+    memset(&a, 0, sizeof a);
+    a.base = d_base;
+    a.queries = d_queries;
+    a.dtype = dtype;
+    a.d = dim;
+    a.n = n;
+    a.nq = nq;
+    a.k = k;
+    a.nsplit = (int)nsplit;
+    a.partial = (uint64_t*)sc;  // every list the merge reads is written by the tile kernel first: nothing to clear
+    a.out_ids = d_out_ids;
+    a.out_dist = d_out_dist;
+    JX_HIP(jx::launch_bruteforce(a, as_stream(stream)));
     return JX_OK;
 }
 

@@ -25,6 +25,7 @@ EXPORTS = [
     "jx_arena_bytes", "jx_create", "jx_destroy", "jx_insert", "jx_quantize", "jx_search", "jx_beam_frontier",
     "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_import_codes", "jx_rotate",
     "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_compact", "jx_deleted_count", "jx_probe_gather", "jx_mips_augment", "jx_strerror", "jx_last_error",
+    "jx_bruteforce_static",
 ]
 
 
@@ -244,6 +245,25 @@ class Index:
         with torch.cuda.device(self.device):
             _check(_lib.jx_deleted_count(self._h, C.byref(n), _stream()))
         return n.value
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def bruteforce_static(base: torch.Tensor, queries: torch.Tensor, k: int, out=None):
+    """jx_bruteforce_static: exhaustive kNN without an index or an arena; the caller passes the output tensors
+    (`out`) when it must not allocate either."""
+    dtype = {torch.uint8: U8, torch.float32: F32, torch.float16: F16}[base.dtype]
+    assert queries.dtype == base.dtype and queries.shape[1] == base.shape[1]
+    nq = queries.shape[0]
+    if out is None:
+        out = (torch.empty((nq, k), dtype=torch.int32, device=base.device),
+               torch.empty((nq, k), dtype=torch.float32, device=base.device))
+    ids, dist = out
+    with torch.cuda.device(base.device):
+        _check(_lib.jx_bruteforce_static(_ptr(base), C.c_int64(base.shape[0]), C.c_int32(base.shape[1]), C.c_int32(dtype),
+                                         _ptr(queries), C.c_int64(nq), C.c_int32(k), _ptr(ids), _ptr(dist), _stream()))
+    return ids, dist
 
 
 def mips_augment(x: torch.Tensor, max_norm: float = 0.0, is_query: bool = False, dim_out: int = 0, want_norms: bool = False):
