@@ -53,6 +53,39 @@ extern "C" {
 #define JX_RULE_MAXCOS 0 /* the grid point whose direction is closest to r ("extended" codes): exact sweep
                            over the breakpoints of the grid scale; 2- and 4-bit codes with dim * (2^(m-1) - 1) <= 8192, dim <= 4096 */
 #define JX_RULE_MAXABS 1 /* grid scale t = (2^(m-1) - 1/2) / max_i |r_i| */
+#define JX_RULE_DEFAULT (-1) /* JX_RULE_MAXCOS where it is offered for the index's dim and bits, else JX_RULE_MAXABS */
+
+/*
+ * jx_params.flags / jx_set_flags: implementation switches.  0 selects the
+ * defaults, which are the measured optima on gfx950.  No switch changes a
+ * result: every combination returns the same ids, distances and graphs (the
+ * parity tests hold each of them to the CPU oracle); they change which kernel
+ * variant does the work, and exist for the kernel-variant ablation (Sec. 6.5
+ * "Ablation study"; App. Block-Size, Tile Size and Load microbenchmarks) and
+ * for comparisons in the tests.  Nothing in the library reads an environment
+ * variable.
+ */
+#define JX_FLAG_NO_PAIR (1u << 0)       /* beamSearch: never take two expansions per round */
+#define JX_FLAG_NO_INCR_PRUNE (1u << 1) /* uint8 reverse merge: always prune a whole row, never only the pairs that
+                                           involve entries added since the row's last prune */
+#define JX_FLAG_NO_GRAM (1u << 2)       /* float data: robustPrune by the list-based kernels, not the Gram-matrix (MFMA) ones */
+#define JX_FLAG_GRAM_U8 (1u << 3)       /* uint8 data: robustPrune by the Gram-matrix kernels as well */
+#define JX_FLAG_VISITED_IDS (1u << 4)   /* beamSearch visited filter: direct-mapped table of full 32-bit ids (ParlayANN's
+                                           table, Sec. 4.2) instead of two-way sets of 16-bit tags */
+#define JX_FLAG_VISITED_NONE (1u << 5)  /* beamSearch visited filter: none -- Alg. 2 as printed: every neighbour is
+                                           evaluated, the frontier's expanded bit is the only memory */
+#define JX_FLAG_LANES_WIDE (1u << 6)    /* beamSearch: twice the default lanes per record (one 16-byte chunk per lane) */
+#define JX_FLAG_LANES_NARROW (1u << 7)  /* beamSearch: half the default lanes per record (four chunks per lane; uint8
+                                           and float32 records of at most 8 / 32 chunks) */
+#define JX_FLAG_TILED_LOADS (1u << 8)   /* beamSearch, exact uint8 / float32: the "tiled" load of Sec. 4.4 -- each lane
+                                           reads 4-byte elements strided over its lane group -- instead of the
+                                           "chunked" 16-byte loads */
+#define JX_FLAG_WAVES_2 (1u << 9)       /* beamSearch, exact float32 records of more than 64 chunks: two wavefronts */
+#define JX_FLAG_WAVES_4 (1u << 10)      /* ... four wavefronts share one query's distance evaluations (Sec. 4.1: larger
+                                           blocks for larger vectors) */
+#define JX_FLAG_QPW_2 (1u << 11)        /* beamSearch: two */
+#define JX_FLAG_QPW_4 (1u << 12)        /* ... four queries (wavefronts) per workgroup instead of one */
+#define JX_FLAG_ALL ((1u << 13) - 1u)
 
 /* error codes */
 #define JX_OK 0
@@ -83,6 +116,7 @@ typedef struct {
     int32_t quant_bits; /* 0: never quantised; 1, 2, 4 or 8: reserve room for RaBitQ codes of that width */
     float batch_growth; /* an internal insert batch holds at most max(1, floor(batch_growth * #linked))
                            points; 0 selects the default 0.25 */
+    uint32_t flags;     /* JX_FLAG_* switches; 0 = defaults */
 } jx_params;
 
 /* Counters of one jx_search call, summed over its queries. */
@@ -95,6 +129,11 @@ typedef struct {
     /* elapsed time of each stage of the call, from HIP events recorded on the
      * caller's stream around the stage's launches (summed over query slices) */
     float rotate_ms, prep_ms, beam_ms, rerank_ms;
+    /* the beamSearch kernel instance the call launched, as a profiler prints it:
+     * "beam_search_kernel<KIND,T,CPL,NREG,QB>" -- distance provider (0 uint8, 1 float32, 2 4-bit codes, 3 1-bit
+     * codes, 4 binary16), lanes per record, 16-byte chunks per lane, frontier registers per lane (64 entries
+     * each), query bits; "beam_search_pair_kernel<...>" = two expansions per round */
+    char beam_kernel[96];
 } jx_stats;
 
 /* Bytes of device memory jx_create needs for these parameters (256-aligned
@@ -110,6 +149,10 @@ int jx_create(const jx_params* p, void* d_arena, int64_t arena_bytes, void* stre
 /* Frees the host object only. */
 int jx_destroy(jx_index* idx);
 
+/* Replace the index's JX_FLAG_* switches (takes effect from the next call; bits outside JX_FLAG_ALL: JX_EINVAL).
+ * A debug entry point: it lets one index be searched, or a build be continued, under several kernel variants. */
+int jx_set_flags(jx_index* idx, uint32_t flags);
+
 /*
  * Batch insertion (Alg. 4 with the changes of Sec. 4.3 and 4.5).
  * d_vecs: n vectors of the index's dtype, row-major [n][dim]; they receive ids
@@ -118,7 +161,7 @@ int jx_destroy(jx_index* idx);
  * call's coordinate-wise mean (the paper's "medoid"), which joins the graph
  * first with an empty row, (3) links the remaining points in id order in
  * internal batches of size min(remaining, max(1, floor(batch_growth * number of
- * points already linked))) (Sec. 6.3 reports batches of 0.5 % to 32 % of the
+ * points already linked))) (Sec. 6.2 reports batches of 0.5 % to 32 % of the
  * index as working); each batch runs beamSearch
  * (L_build, from the entry point, exact distances) for all its points against
  * the graph as it stood before the batch, robustPrune of the final frontier
@@ -137,8 +180,8 @@ int jx_insert(jx_index* idx, const void* d_vecs, int64_t n, void* stream);
  * bits: 1, 2, 4 or 8 (must equal params.quant_bits).  d_rotation: orthogonal matrix P,
  * float32 [dim][dim] row-major, applied as r = P (v - c).  d_centroid: c
  * (float32 [dim]) or NULL = mean of the current base set.  query_bits: width
- * B_q of the integer query (4 or 8).  rule: JX_RULE_MAXCOS or JX_RULE_MAXABS
- * (ignored for 1-bit codes).
+ * B_q of the integer query (4 or 8).  rule: JX_RULE_MAXCOS, JX_RULE_MAXABS or
+ * JX_RULE_DEFAULT (ignored for 1-bit codes).
  * Per vector the arena holds the dim*bits/8 code bytes (2- and 8-bit codes
  * split into a low and a high plane of 1-bit / 4-bit fields), zero padding to
  * 16-byte chunks, then data_add = ||r||^2 and data_rescale = -2||r||^2/<xbar,r>
@@ -204,7 +247,7 @@ int jx_bruteforce(jx_index* idx, const void* d_queries, int64_t nq, int32_t k, u
 int jx_bruteforce_static(const void* d_base, int64_t n, int32_t dim, int32_t dtype, const void* d_queries, int64_t nq,
                          int32_t k, uint32_t* d_out_ids, float* d_out_dist, void* stream);
 
-/* Batch deletion (Sec. 4.6 and 6.5: mark, consolidate, compact; the scheme of
+/* Batch deletion (Sec. 4.6 and 6.4: mark, consolidate, compact; the scheme of
  * FreshDiskANN that the paper adopts).
  *
  * jx_delete marks the n vertices d_ids[n] (device) as deleted: an in-place,
@@ -259,7 +302,7 @@ int jx_deleted_count(jx_index* idx, int64_t* n_deleted, void* stream);
 int jx_mips_augment(const float* d_in, int64_t n, int32_t dim, float max_norm, int32_t is_query, float* d_out,
                     int32_t dim_out, float* d_norms, void* stream);
 
-/* Calibration aid for the roofline of beamSearch (Sec. 6.6 prices the kernel
+/* Calibration aid for the roofline of beamSearch (Sec. 6.5 prices the kernel
  * against memory bandwidth): reads the n_ids records d_ids[i] (all < n_rec;
  * not checked on the device -- the caller guarantees it) of a table of
  * rec_bytes-byte records (64, 128, 256 or 512) with independent 16-byte
@@ -280,7 +323,7 @@ int jx_export_graph(jx_index* idx, uint32_t* d_adj, uint32_t* d_deg, void* strea
 /* Replace the index content by n vectors and a ready-made graph (used to
  * search a graph built elsewhere, e.g. by a reference implementation).
  * Rows must be filled from the left and padded with JX_NONE, ids must be
- * below n: the table is checked on the device first (the call synchronises)
+ * below n and no row may name a vertex twice: the table is checked on the device first (the call synchronises)
  * and JX_EINVAL leaves the index untouched. */
 int jx_import_graph(jx_index* idx, const void* d_vecs, int64_t n, const uint32_t* d_adj, uint32_t entry_id,
                     void* stream);

@@ -654,7 +654,7 @@ static void insert_subbatch(orc_index *x, const uint32_t *ids, int64_t B, int nt
  * against the float mean).  It joins the graph first, alone, with an empty row.
  *
  * Sub-batch schedule (the paper is silent on how a stream that starts empty is
- * bootstrapped; Sec. 6.3 reports batches of 0.5 % to 32 % of the index as
+ * bootstrapped; Sec. 6.2 reports batches of 0.5 % to 32 % of the index as
  * working): the remaining ids of the call, in increasing order, are cut into
  * sub-batches of size min(remaining, max(1, floor(batch_growth * #linked))).
  */

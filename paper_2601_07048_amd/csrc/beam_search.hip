@@ -19,19 +19,16 @@
 //      many candidates precede its entries, and one LDS scatter/gather applies
 //      the permutation.  Keys are 64-bit (ordered distance, id, expanded flag),
 //      so the order is the strict total order (distance, id).
-#include <stdlib.h>
+#include <stdio.h>
 #include "jx_distance.h"
 
 namespace jx {
 
 // Tuning constants (compile-time; the values are the optima measured on gfx950 at N = 1M, 10,000 queries):
-// 16-byte loads in flight per lane for the exact uint8, 1-bit and 4-bit kernels, lanes per 1-bit record, and the
+// 16-byte loads in flight per lane for the exact uint8, 1-bit and 4-bit kernels, and the
 // waves per SIMD the small exact kernels are held to.
 #ifndef JX_UMAX_EXACT
 #define JX_UMAX_EXACT 8
-#endif
-#ifndef JX_RQ1_LANES
-#define JX_RQ1_LANES 8
 #endif
 #ifndef JX_UMAX_RQ1
 #define JX_UMAX_RQ1 8
@@ -88,7 +85,7 @@ beam_search_kernel(BeamArgs a) {
         if (tag_bits) {
             const uint32_t h = (a.entry * 0x9E3779B1u) & id_mask;
             tab[h >> tag_bits] = 0xFFFF0000u | (h & ((1u << tag_bits) - 1u));
-        } else {
+        } else if (H) {
             tab[__umulhi(a.entry * 0x9E3779B1u, (uint32_t)H)] = a.entry;
         }
     }
@@ -141,10 +138,14 @@ beam_search_kernel(BeamArgs a) {
                     const uint32_t w = tab[h >> tag_bits];
                     is_new = (w & 0xFFFFu) != tag && (w >> 16) != tag;
                     if (is_new) tab[h >> tag_bits] = (w << 16) | tag;
-                } else {
+                } else if (H) {
                     uint32_t h = __umulhi(v * 0x9E3779B1u, (uint32_t)H);
                     is_new = tab[h] != v;
                     if (is_new) tab[h] = v;
+                } else {
+                    // no filter (Alg. 2 as printed): every neighbour is evaluated; one that is still in the frontier
+                    // is recognised by the merge, one that has left it cannot come back (its key is above the worst)
+                    is_new = true;
                 }
             }
             uint64_t nm = ballot(is_new);
@@ -523,30 +524,26 @@ beam_search_pair_kernel(BeamArgs a) {
 
 // ------------------------------------------------------------------ launch
 
-static long long pair_max_queries() {
-    static long long v = -1;
-    if (v < 0) {
-        const char* e = getenv("JX_BEAM_PAIR");  // 0 = off, n > 1 = largest batch that takes the pair kernel
-        v = e ? atoll(e) : 32768;
-        if (v == 1) v = 32768;
-    }
-    return v;
-}
+// largest batch that takes two expansions per round: beyond it the machine is full several times over and a search is
+// bound by bandwidth, not by the lifetime of a query
+static constexpr long long PAIR_MAX_QUERIES = 32768;
 
 template <int KIND, int T, int CPL, int QB>
-static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st) {
+static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st, char* name) {
     const int nreg = (a.L + 63) / 64;
     const int H = a.hash_slots;
     dim3 grid((unsigned)((a.nq + JX_BEAM_WPB - 1) / JX_BEAM_WPB)), block(JX_BEAM_WPB * 64);
     if constexpr (CPL <= 2 && (KIND == K_U8 || KIND == K_RQ4 || KIND == K_RQ1)) {
         // batches that do not fill the machine several times over are bound by the lifetime of a query: two
-        // expansions per round (JX_BEAM_PAIR=0 switches it off).  Not for float vectors: their searches are bound by
+        // expansions per round (JX_FLAG_NO_PAIR switches it off).  Not for float vectors: their searches are bound by
         // bandwidth, and the dropped second lists cost 12 % at d = 200, L = 128.
         // measured: +2..6 % for records of one 128-byte line from L = 64 (-3 % at L = 32); -8..-11 % for the 496- and
         // 208-byte records of d = 960 / 1536 codes, whose searches run at 7 TB/s and pay for every dropped list
-        if (nreg <= 2 && a.L >= 64 && a.R <= 64 && a.ds.rec_stride <= 128 && a.nq <= pair_max_queries()) {
+        if (nreg <= 2 && a.L >= 64 && a.R <= 64 && a.ds.rec_stride <= 128 && a.nq <= PAIR_MAX_QUERIES && H > 0 &&
+            !(a.flags & JX_FLAG_NO_PAIR)) {
             const size_t sh = (size_t)nreg * 64 * 8 + 128 * 8 + 128 * 4 + (size_t)H * (a.tag_bits ? 2 : 4);
             dim3 pgrid((unsigned)a.nq), pblock(64);
+            if (name) snprintf(name, 96, "beam_search_pair_kernel<%d,%d,%d,%d,%d>", KIND, T, CPL, nreg <= 1 ? 1 : 2, QB);
             if (nreg <= 1)
                 hipLaunchKernelGGL((beam_search_pair_kernel<KIND, T, CPL, 1, QB>), pgrid, pblock, sh, st, a);
             else
@@ -562,6 +559,7 @@ static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st) {
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh); \
             if (e != hipSuccess) return e;                                                              \
         }                                                                                               \
+        if (name) snprintf(name, 96, "beam_search_kernel<%d,%d,%d,%d,%d>", KIND, T, CPL, NR, QB);       \
         hipLaunchKernelGGL(kern, grid, block, sh, st, a);                                               \
         return hipGetLastError();                                                                       \
     }
@@ -572,79 +570,62 @@ static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st) {
 #undef JX_LAUNCH
 }
 
-// Chunks per lane for records of at most 64 chunks: with 2 chunks per lane a
-// record is covered by half as many lanes, so twice as many candidates share
-// one instruction and the in-group reduction is one step shorter.
-static int chunks_per_lane_pref(int kind) {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("JX_CHUNKS_PER_LANE");
-        v = e ? atoi(e) : 0;
-        if (v != 1 && v != 2) v = 0;
-    }
-    if (v) return v;
-    return kind == K_RQ1 ? 1 : 2;
-}
-
-// 1-bit records (experiments: JX_RQ1_SHAPE = 16 | 8 | 4 lanes per record of at most 16 chunks)
-static int rq1_lanes_pref() {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("JX_RQ1_SHAPE");
-        v = e ? atoi(e) : 0;
-        if (v != 16 && v != 8 && v != 4) v = 0;
-    }
-    return v;
-}
-
+// Record-to-lane mapping.  Default: two 16-byte chunks per lane for records of at most 64 chunks -- a record is then
+// covered by half as many lanes as it has chunks, so twice as many candidates share one instruction and the in-group
+// reduction is one step shorter (1-bit codes with B_q = 8: one chunk per lane, the eight bit planes of a second
+// chunk would not fit the registers); larger records: all 64 lanes, 2 to 6 chunks each.  JX_FLAG_LANES_WIDE: one
+// chunk per lane.  JX_FLAG_LANES_NARROW: four chunks per lane (uint8 records of at most 8 chunks, float32 records of
+// at most 32).
 template <int KIND, int QB>
-static hipError_t launch_shape(const BeamArgs& a, hipStream_t st) {
+static hipError_t launch_shape(const BeamArgs& a, hipStream_t st, char* name) {
     const int nch = a.ds.nch;
-    if constexpr (KIND == K_RQ1) {
-        if (nch <= 16) {
-            // B_q = 4: 8 lanes x 2 chunks with the four bit planes of both chunks in registers (measured 10 % faster
-            // than 16 x 1 at L = 64..128); B_q = 8 would need 64 plane registers per lane and stays at 16 x 1
-            const int pref = rq1_lanes_pref() ? rq1_lanes_pref() : (QB == 4 ? JX_RQ1_LANES : 16);
-            if (pref == 8) return launch_nreg<KIND, 8, 2, QB>(a, st);
-            if constexpr (QB == 4) {
-                if (pref == 4) return launch_nreg<KIND, 4, 4, QB>(a, st);
-            }
+    const bool wide = (a.flags & JX_FLAG_LANES_WIDE) != 0, narrow = (a.flags & JX_FLAG_LANES_NARROW) != 0;
+    if constexpr (KIND == K_U8) {
+        if (narrow && nch <= 8) return launch_nreg<KIND, 2, 4, QB>(a, st, name);
+    }
+    if constexpr (KIND == K_F32) {
+        if (narrow && nch <= 32) return launch_nreg<KIND, 8, 4, QB>(a, st, name);
+    }
+    const bool two = !wide && nch <= 64 && !(KIND == K_RQ1 && (QB == 8 || nch > 16));
+    if (two) {
+        if constexpr (KIND == K_RQ1) {
+            // 8 lanes x 2 chunks with the four bit planes of both chunks in registers (measured 10 % faster than
+            // 16 x 1 at L = 64..128)
+            return launch_nreg<KIND, 8, 2, QB>(a, st, name);
+        } else {
+            if (nch <= 8) return launch_nreg<KIND, 4, 2, QB>(a, st, name);
+            if (nch <= 16) return launch_nreg<KIND, 8, 2, QB>(a, st, name);
+            if (nch <= 32) return launch_nreg<KIND, 16, 2, QB>(a, st, name);
+            return launch_nreg<KIND, 32, 2, QB>(a, st, name);
         }
     }
-    if constexpr (KIND != K_RQ1) {
-        if (nch <= 64 && chunks_per_lane_pref(KIND) == 2) {
-            if (nch <= 8) return launch_nreg<KIND, 4, 2, QB>(a, st);
-            if (nch <= 16) return launch_nreg<KIND, 8, 2, QB>(a, st);
-            if (nch <= 32) return launch_nreg<KIND, 16, 2, QB>(a, st);
-            return launch_nreg<KIND, 32, 2, QB>(a, st);
-        }
-    }
-    if (nch <= 8) return launch_nreg<KIND, 8, 1, QB>(a, st);
-    if (nch <= 16) return launch_nreg<KIND, 16, 1, QB>(a, st);
-    if (nch <= 32) return launch_nreg<KIND, 32, 1, QB>(a, st);
-    if (nch <= 64) return launch_nreg<KIND, 64, 1, QB>(a, st);
+    if (nch <= 8) return launch_nreg<KIND, 8, 1, QB>(a, st, name);
+    if (nch <= 16) return launch_nreg<KIND, 16, 1, QB>(a, st, name);
+    if (nch <= 32) return launch_nreg<KIND, 32, 1, QB>(a, st, name);
+    if (nch <= 64) return launch_nreg<KIND, 64, 1, QB>(a, st, name);
     if constexpr (KIND == K_RQ1) {
         return hipErrorInvalidValue;
     } else {
-        if (nch <= 128) return launch_nreg<KIND, 64, 2, QB>(a, st);
+        if (nch <= 128) return launch_nreg<KIND, 64, 2, QB>(a, st, name);
         if constexpr (KIND == K_RQ4) {
             return hipErrorInvalidValue;
         } else {
-            if (nch <= 256) return launch_nreg<KIND, 64, 4, QB>(a, st);
-            if (nch <= 384) return launch_nreg<KIND, 64, 6, QB>(a, st);
+            if (nch <= 256) return launch_nreg<KIND, 64, 4, QB>(a, st, name);
+            if (nch <= 384) return launch_nreg<KIND, 64, 6, QB>(a, st, name);
             return hipErrorInvalidValue;
         }
     }
 }
 
-hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st) {
+hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st, char* kernel_name) {
+    if (kernel_name) kernel_name[0] = 0;
     if (a.nq <= 0) return hipSuccess;
     switch (kind) {
-        case K_U8: return launch_shape<K_U8, 0>(a, st);
-        case K_F32: return launch_shape<K_F32, 0>(a, st);
-        case K_F16: return launch_shape<K_F16, 0>(a, st);
-        case K_RQ4: return qbits == 8 ? launch_shape<K_RQ4, 8>(a, st) : launch_shape<K_RQ4, 4>(a, st);
-        case K_RQ1: return qbits == 8 ? launch_shape<K_RQ1, 8>(a, st) : launch_shape<K_RQ1, 4>(a, st);
+        case K_U8: return launch_shape<K_U8, 0>(a, st, kernel_name);
+        case K_F32: return launch_shape<K_F32, 0>(a, st, kernel_name);
+        case K_F16: return launch_shape<K_F16, 0>(a, st, kernel_name);
+        case K_RQ4: return qbits == 8 ? launch_shape<K_RQ4, 8>(a, st, kernel_name) : launch_shape<K_RQ4, 4>(a, st, kernel_name);
+        case K_RQ1: return qbits == 8 ? launch_shape<K_RQ1, 8>(a, st, kernel_name) : launch_shape<K_RQ1, 4>(a, st, kernel_name);
     }
     return hipErrorInvalidValue;
 }

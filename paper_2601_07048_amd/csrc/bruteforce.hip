@@ -255,20 +255,34 @@ __global__ void row_degrees_kernel(const uint32_t* adj, long long n, int R, uint
     deg[i] = (uint32_t)g;
 }
 
-// adjacency table handed in from outside: every entry must be a vertex id below n or the padding value, and a row
-// must be filled from the left (the kernels stop at the first padding entry); counts the offending entries
-__global__ void validate_adj_kernel(const uint32_t* adj, long long n, int R, uint32_t* bad) {
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n * R) return;
-    const uint32_t v = adj[i];
-    if (v == JX_NONE_ID) return;
-    const bool gap = (i % R) > 0 && adj[i - 1] == JX_NONE_ID;
-    if (v >= (unsigned long long)n || gap) atomicAdd(bad, 1u);
+// adjacency table handed in from outside: every entry must be a vertex id below n or the padding value, a row must
+// be filled from the left (the kernels stop at the first padding entry) and must not name a vertex twice (two lanes
+// would pass the visited filter of beamSearch in the same instruction and the frontier merge would rank the two
+// equal keys alike).  One wavefront per row, the row staged in LDS; counts the offending entries.
+__global__ void __launch_bounds__(256) validate_adj_kernel(const uint32_t* adj, long long n, int R, uint32_t* bad) {
+    __shared__ uint32_t rows[4][JX_MAX_R];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long r = (long long)blockIdx.x * 4 + wave;
+    if (r >= n) return;  // whole wavefront; no workgroup barrier below
+    const uint32_t* row = adj + (size_t)r * R;
+    uint32_t* mine = rows[wave];
+    uint32_t nbad = 0;
+    for (int e = lane; e < R; e += 64) mine[e] = row[e];
+    wave_sync();
+    for (int e = lane; e < R; e += 64) {
+        const uint32_t v = mine[e];
+        if (v == JX_NONE_ID) continue;
+        bool wrong = v >= (unsigned long long)n || (e > 0 && mine[e - 1] == JX_NONE_ID);
+        for (int j = 0; j < e && !wrong; j++) wrong = mine[j] == v;
+        nbad += wrong ? 1u : 0u;
+    }
+    if (nbad) atomicAdd(bad, nbad);
 }
 
 hipError_t launch_validate_adj(const uint32_t* adj, long long n, int R, uint32_t* bad, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(validate_adj_kernel, dim3((unsigned)((n * R + 255) / 256)), dim3(256), 0, st, adj, n, R, bad);
+    if (R > JX_MAX_R) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(validate_adj_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, adj, n, R, bad);
     return hipGetLastError();
 }
 

@@ -1401,22 +1401,12 @@ static hipError_t launch_prune_shape(bool forward, const InsertArgs& a, hipStrea
     return hipErrorInvalidValue;
 }
 
-// JX_LEAN_FWD=0 sends uint8 frontiers to the general kernel (comparisons)
-static bool lean_forward_prune() {
-    static int on = -1;
-    if (on < 0) {
-        const char* e = getenv("JX_LEAN_FWD");
-        on = (e && atoi(e) == 0) ? 0 : 1;
-    }
-    return on != 0;
-}
-
 hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st) {
     if (a.gram) {
         hipError_t e = launch_forward_prune_gram(dtype, a, st);
         if (e != hipSuccess || a.L <= 128) return e;  // wider frontiers: the list-based kernel takes the rest
     }
-    if (dtype == JX_U8 && !a.gram && a.ds.rec_stride == 128 && a.ds.nch == 8 && a.L <= 128 && lean_forward_prune()) {
+    if (dtype == JX_U8 && !a.gram && a.ds.rec_stride == 128 && a.ds.nch == 8 && a.L <= 128) {
         hipLaunchKernelGGL(forward_prune_u8_lean_kernel, dim3((unsigned)a.B), dim3(64), 0, st, a);
         return hipGetLastError();
     }
@@ -1430,7 +1420,7 @@ hipError_t launch_reverse_merge(int dtype, const InsertArgs& a, hipStream_t st) 
         hipError_t e = launch_reverse_merge_gram(dtype, a, st);
         if (e != hipSuccess) return e;
     }
-    if (dtype == JX_U8 && a.force_prune && a.ds.rec_stride == 128 && a.ds.nch == 8 && lean_forward_prune()) {
+    if (dtype == JX_U8 && a.force_prune && a.ds.rec_stride == 128 && a.ds.nch == 8) {
         // consolidation: candidate sets of at most 512 take the multi-pivot form
         const long long want = a.E ? a.E : a.B * a.R;
         const unsigned grid = (unsigned)(want < 8192 ? (want < 1 ? 1 : want) : 8192);

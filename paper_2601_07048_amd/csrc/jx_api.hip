@@ -67,6 +67,7 @@ int check_params(const jx_params* p) {
         return fail(JX_EINVAL, "quant_bits must be 0, 1, 2, 4 or 8");
     if (p->quant_bits && p->dim % 32) return fail(JX_EINVAL, "RaBitQ needs dim to be a multiple of 32");
     if (!(p->batch_growth >= 0.0f) || p->batch_growth > 1.0f) return fail(JX_EINVAL, "batch_growth must be in [0, 1]");
+    if (p->flags & ~JX_FLAG_ALL) return fail(JX_EINVAL, "unknown bits in flags");
     return JX_OK;
 }
 
@@ -173,36 +174,17 @@ int64_t batch_cap(const jx_params& p, int64_t linked) {
     return c < 1 ? 1 : c;
 }
 
-// Gram-matrix robustPrune for float data (JX_GRAM=0 switches it off for comparisons)
-int gram_mode(int dtype) {
-    static int on = -1;
-    if (on < 0) {
-        const char* e = getenv("JX_GRAM");
-        on = (e && atoi(e) == 0) ? 0 : 1;
-    }
-    if (!on) return 0;
-    if (dtype == JX_U8) {
-        static int u8 = -1;
-        if (u8 < 0) {
-            const char* e = getenv("JX_GRAM_U8");  // 1: forward prune and reverse merge, 2: forward prune only
-            u8 = e ? atoi(e) : 0;
-            if (u8 != 1 && u8 != 2) u8 = 0;
-        }
-        return u8 == 1 ? 3 : (u8 == 2 ? 7 : 0);
-    }
-    return dtype == JX_F16 ? 2 : 1;
+// How robustPrune is computed: 0 = list-based kernels, 1 / 2 = Gram-matrix kernels for float32 / binary16 data (the
+// default for float data), 3 = Gram-matrix kernels for uint8 data (JX_FLAG_GRAM_U8)
+int gram_mode(const jx_index* idx) {
+    if (idx->flags & JX_FLAG_NO_GRAM) return 0;
+    if (idx->p.dtype == JX_U8) return (idx->flags & JX_FLAG_GRAM_U8) ? 3 : 0;
+    return idx->p.dtype == JX_F16 ? 2 : 1;
 }
 
 // Rows of uint8 indices remember how many leading entries one robustPrune call selected together, which lets the
-// next prune of the row skip the pairs among them (JX_INCR_PRUNE=0 switches this off for comparisons)
-bool incremental_prune() {
-    static int on = -1;
-    if (on < 0) {
-        const char* e = getenv("JX_INCR_PRUNE");
-        on = (e && atoi(e) == 0) ? 0 : 1;
-    }
-    return on != 0;
-}
+// next prune of the row skip the pairs among them
+bool incremental_prune(const jx_index* idx) { return !(idx->flags & JX_FLAG_NO_INCR_PRUNE); }
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
@@ -238,23 +220,20 @@ int static_scratch(unsigned char** out) {
 // Visited table of beamSearch for beam width L on n vertices.  While ids fit slots x 2^15 the table holds 16-bit
 // tags (see BeamArgs::tag_bits): twice the slots in the same LDS, 16 % fewer repeated distance evaluations at L = 96.
 // 1,024 32-bit / 2,048 16-bit slots at least: measured optimum against the LDS footprint for L <= 256.
-void visited_table_for(int L, int64_t n, int* slots, int* tag_bits) {
-    static int forced = -1, mode16 = -1;
-    if (forced < 0) {
-        const char* e = getenv("JX_HASH_SLOTS");  // experiments only
-        forced = e ? atoi(e) : 0;
-        if (forced < 64 || forced > 8192) forced = 0;
-        const char* m = getenv("JX_TAG16");
-        mode16 = (m && atoi(m) == 0) ? 0 : 1;
+// JX_FLAG_VISITED_IDS keeps full ids; JX_FLAG_VISITED_NONE (slots = 0) switches the filter off.
+void visited_table_for(uint32_t flags, int L, int64_t n, int* slots, int* tag_bits) {
+    *tag_bits = 0;
+    if (flags & JX_FLAG_VISITED_NONE) {
+        *slots = 0;
+        return;
     }
     int id_bits = 1;
     while (((int64_t)1 << id_bits) < n) id_bits++;
-    int h = forced ? forced : 1024;
-    while (!forced && h < 4 * L && h < 4096) h *= 2;
+    int h = 1024;
+    while (h < 4 * L && h < 4096) h *= 2;
     *slots = h;
-    *tag_bits = 0;
-    if (mode16 && (h & (h - 1)) == 0) {
-        int h16 = forced ? h : 2 * h, lg = 0;
+    if (!(flags & JX_FLAG_VISITED_IDS)) {
+        int h16 = 2 * h, lg = 0;
         while ((2 << lg) < h16) lg++;  // log2 of the number of sets (two entries each)
         int tb = id_bits - lg;
         if (tb < 1) tb = 1;
@@ -323,6 +302,7 @@ int jx_create(const jx_params* p, void* d_arena, int64_t arena_bytes, void* stre
     x->plane_chunks = L.plane_chunks;
     x->plane_shift = L.plane_shift;
     x->code_stride = L.code_stride;
+    x->flags = p->flags;
     hipError_t e = jx::launch_fill_u32(x->d_adj, (long long)p->capacity * p->R, JX_NONE, as_stream(stream));
     if (e == hipSuccess) e = jx::launch_fill_u32((uint32_t*)x->d_stats, 64, 0u, as_stream(stream));
     if (e == hipSuccess) e = jx::launch_fill_u32((uint32_t*)x->d_deleted, (p->capacity + 3) / 4, 0u, as_stream(stream));
@@ -340,6 +320,14 @@ int jx_destroy(jx_index* idx) {
     return JX_OK;
 }
 
+int jx_set_flags(jx_index* idx, uint32_t flags) {
+    if (!idx) return fail(JX_EINVAL, "index is NULL");
+    if (flags & ~JX_FLAG_ALL) return fail(JX_EINVAL, "unknown bits in flags");
+    idx->flags = flags;
+    idx->p.flags = flags;
+    return JX_OK;
+}
+
 int jx_size(const jx_index* idx, int64_t* n, uint32_t* entry_id) {
     if (!idx) return fail(JX_EINVAL, "index is NULL");
     if (n) *n = idx->n;
@@ -352,14 +340,15 @@ int jx_import_graph(jx_index* idx, const void* d_vecs, int64_t n, const uint32_t
     if (n < 1 || n > idx->p.capacity) return fail(JX_ECAPACITY, "n = %lld exceeds capacity", (long long)n);
     if (entry_id >= (uint64_t)n) return fail(JX_EINVAL, "entry id out of range");
     hipStream_t st = as_stream(stream);
-    {   // a table with ids out of range would send the search kernels out of bounds: check it before it is installed
+    {   // a table with ids out of range or with a repeated id in a row would send the search kernels out of bounds:
+        // check it before it is installed
         uint32_t* d_bad = (uint32_t*)(idx->d_stats + 10);
         uint32_t bad = 0;
         JX_HIP(jx::launch_fill_u32(d_bad, 1, 0u, st));
         JX_HIP(jx::launch_validate_adj(d_adj, n, idx->p.R, d_bad, st));
         JX_HIP(hipMemcpyAsync(&bad, d_bad, 4, hipMemcpyDeviceToHost, st));
         JX_HIP(hipStreamSynchronize(st));
-        if (bad) return fail(JX_EINVAL, "%u adjacency entries are out of range or follow a padding entry", bad);
+        if (bad) return fail(JX_EINVAL, "%u adjacency entries are out of range, follow a padding entry or repeat an id of their row", bad);
     }
     JX_HIP(hipMemcpyAsync(idx->d_vecs, d_vecs, (size_t)n * idx->vec_bytes, hipMemcpyDeviceToDevice, st));
     JX_HIP(hipMemcpyAsync(idx->d_adj, d_adj, (size_t)n * idx->p.R * 4, hipMemcpyDeviceToDevice, st));
@@ -446,10 +435,12 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     a.q_skip = 0x7FFFFFFFFFFFFFFFLL;
     a.L = L;
     a.entry = idx->entry;
-    visited_table_for(L, idx->n, &a.hash_slots, &a.tag_bits);
+    visited_table_for(idx->flags, L, idx->n, &a.hash_slots, &a.tag_bits);
+    a.flags = idx->flags;
     a.stats = h_stats ? idx->d_stats : nullptr;
     a.deleted = idx->any_delete ? idx->d_deleted : nullptr;
     StageTimer tm(h_stats != nullptr, st);
+    char kname[96] = "";
     if (mode == JX_EXACT) {
         // distances are already exact: a re-rank would change nothing
         fill_exact_src(idx, &a.ds, d_queries);
@@ -458,7 +449,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         a.out_dist = d_out_dist;
         a.out_k = out_k;
         tm.begin();
-        JX_HIP(jx::launch_beam_search(exact_kind(p.dtype), 0, a, st));
+        JX_HIP(jx::launch_beam_search(exact_kind(p.dtype), 0, a, st, kname));
         tm.end(2);
     } else {
         QueryWork qw;
@@ -506,7 +497,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
                 a.out_k = out_k;
             }
             tm.begin();
-            JX_HIP(jx::launch_beam_search(idx->quantized >= 4 ? 2 : 3, idx->qbits, a, st));
+            JX_HIP(jx::launch_beam_search(idx->quantized >= 4 ? 2 : 3, idx->qbits, a, st, kname));
             tm.end(2);
             if (rerank) {
                 jx::RerankArgs r;
@@ -540,6 +531,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         h_stats->prep_ms = tm.acc[1];
         h_stats->beam_ms = tm.acc[2];
         h_stats->rerank_ms = tm.acc[3];
+        memcpy(h_stats->beam_kernel, kname, sizeof kname);
     }
     return JX_OK;
 }
@@ -648,7 +640,8 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     b.q_skip = id_skip >= id_base ? id_skip - id_base : 0;
     b.L = p.L_build;
     b.entry = idx->entry;
-    visited_table_for(p.L_build, n_after, &b.hash_slots, &b.tag_bits);
+    visited_table_for(idx->flags, p.L_build, n_after, &b.hash_slots, &b.tag_bits);
+    b.flags = idx->flags;
     b.out_ids = (uint32_t*)(W + w.cand_ids);
     b.out_dist = (float*)(W + w.cand_dist);
     b.out_k = p.L_build;
@@ -673,11 +666,11 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     a.vals = (uint32_t*)(W + w.vals0);
     a.heads = (const uint32_t*)(W + w.heads);
     a.nseg = (const uint32_t*)(W + w.counters);
-    a.clean = incremental_prune() ? idx->d_clean : nullptr;
+    a.clean = incremental_prune(idx) ? idx->d_clean : nullptr;
     // forward prune: no LDS vector cache.  A whole frontier (128 x 128 bytes per wavefront) would leave room for
     // one workgroup per CU only, and the Gram-matrix form then measured slower (47 ms against 32 ms per 1M inserts)
     a.vec_cache_bytes = 0;
-    a.gram = gram_mode(p.dtype);
+    a.gram = gram_mode(idx);
     JX_HIP(jx::launch_forward_prune(p.dtype, a, st));
     // 3. one global sort by (target, distance, source)
     int tbits = 1;
@@ -691,7 +684,6 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     // LDS room per wavefront for the vectors of a full row plus up to 32 new edges (96 x 128 bytes);
     // larger merges take the path that reads from global memory
     a.vec_cache_bytes = 12288;
-    if (a.gram == 7) a.gram = 0;
     JX_HIP(jx::launch_reverse_merge(p.dtype, a, st));
     return JX_OK;
 }
@@ -791,8 +783,10 @@ int jx_quantize(jx_index* idx, int32_t bits, const float* d_rotation, const floa
     if (!p.quant_bits) return fail(JX_ESTATE, "the index was created with quant_bits = 0");
     if (bits != p.quant_bits) return fail(JX_EINVAL, "bits must equal params.quant_bits (%d)", p.quant_bits);
     if (query_bits != 4 && query_bits != 8) return fail(JX_EINVAL, "query_bits must be 4 or 8");
+    const bool maxcos_offered = (bits == 2 || bits == 4) && p.dim * ((1 << (bits - 1)) - 1) <= 8192 && p.dim <= 4096;
+    if (rule == JX_RULE_DEFAULT) rule = maxcos_offered ? JX_RULE_MAXCOS : JX_RULE_MAXABS;
     if (rule != JX_RULE_MAXABS && rule != JX_RULE_MAXCOS) return fail(JX_EINVAL, "unknown code rule");
-    if (rule == JX_RULE_MAXCOS && bits > 1 && (bits == 8 || p.dim * ((1 << (bits - 1)) - 1) > 8192 || p.dim > 4096))
+    if (rule == JX_RULE_MAXCOS && bits > 1 && !maxcos_offered)
         return fail(JX_EINVAL, "JX_RULE_MAXCOS supports 2- and 4-bit codes with dim * (2^(bits-1) - 1) <= 8192 and dim <= 4096; use JX_RULE_MAXABS");
     if (idx->n == 0) return fail(JX_ESTATE, "index is empty");
     hipStream_t st = as_stream(stream);
@@ -955,9 +949,8 @@ int jx_consolidate(jx_index* idx, void* stream) {
     a.heads = (const uint32_t*)(W + w.heads);
     a.nseg = (const uint32_t*)(W + w.counters);
     a.force_prune = 1;
-    a.clean = incremental_prune() ? idx->d_clean : nullptr;
-    a.gram = gram_mode(p.dtype);
-    if (a.gram == 7) a.gram = 0;
+    a.clean = incremental_prune(idx) ? idx->d_clean : nullptr;
+    a.gram = gram_mode(idx);
     a.vec_cache_bytes = 12288;
     // 2. slices of consecutive vertices whose candidate lists fit the edge buffers; every new row is
     //    computed from its own old row and from rows of deleted vertices, none of which is rewritten here

@@ -42,8 +42,10 @@ struct BeamArgs {
     int out_k;
     unsigned long long* stats;  // {hops, dist_evals} or NULL
     const uint8_t* deleted;     // [N] 1 = logically deleted (never returned), or NULL
+    uint32_t flags;             // JX_FLAG_* switches that select a kernel variant
 };
-hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st);
+// kernel_name (may be NULL): receives the name of the instance that was launched, at most 96 bytes
+hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st, char* kernel_name = nullptr);
 
 // ---- batch insertion -------------------------------------------------------
 struct InsertArgs {
@@ -202,6 +204,7 @@ struct jx_index {
     uint8_t* d_deleted;  // [capacity] 1 = logically deleted
     uint8_t* d_clean;    // [capacity] see InsertArgs::clean
     int any_delete;      // a delete call has been made since the graph was created / imported
+    uint32_t flags;      // JX_FLAG_* switches (jx_params.flags, jx_set_flags)
     // RaBitQ state
     int quantized;    // 0 or bits
     int qbits, rule;

@@ -18,14 +18,18 @@ NONE = 0xFFFFFFFF
 U8, F32, F16 = 0, 1, 2
 EXACT, RABITQ = 0, 1
 CAND_FRONTIER = 0
-RULE_MAXCOS, RULE_MAXABS = 0, 1
+RULE_MAXCOS, RULE_MAXABS, RULE_DEFAULT = 0, 1, -1
+# jx_params.flags / jx_set_flags (see include/jx.h)
+FLAG_NO_PAIR, FLAG_NO_INCR_PRUNE, FLAG_NO_GRAM, FLAG_GRAM_U8 = 1 << 0, 1 << 1, 1 << 2, 1 << 3
+FLAG_VISITED_IDS, FLAG_VISITED_NONE, FLAG_LANES_WIDE, FLAG_LANES_NARROW = 1 << 4, 1 << 5, 1 << 6, 1 << 7
+FLAG_TILED_LOADS, FLAG_WAVES_2, FLAG_WAVES_4, FLAG_QPW_2, FLAG_QPW_4 = 1 << 8, 1 << 9, 1 << 10, 1 << 11, 1 << 12
 MAX_L, MAX_R, MAX_BF_K = 512, 256, 128
 
 EXPORTS = [
     "jx_arena_bytes", "jx_create", "jx_destroy", "jx_insert", "jx_quantize", "jx_search", "jx_beam_frontier",
     "jx_bruteforce", "jx_size", "jx_export_graph", "jx_import_graph", "jx_export_codes", "jx_import_codes", "jx_rotate",
     "jx_encode_rotated", "jx_delete", "jx_consolidate", "jx_compact", "jx_deleted_count", "jx_probe_gather", "jx_mips_augment", "jx_strerror", "jx_last_error",
-    "jx_bruteforce_static",
+    "jx_bruteforce_static", "jx_set_flags",
 ]
 
 
@@ -33,17 +37,19 @@ class Params(C.Structure):
     _fields_ = [
         ("dim", C.c_int32), ("dtype", C.c_int32), ("R", C.c_int32), ("L_build", C.c_int32), ("alpha", C.c_float),
         ("cand_mode", C.c_int32), ("capacity", C.c_int64), ("max_batch", C.c_int64), ("quant_bits", C.c_int32),
-        ("batch_growth", C.c_float),
+        ("batch_growth", C.c_float), ("flags", C.c_uint32),
     ]
 
 
 class Stats(C.Structure):
     _fields_ = [("hops", C.c_uint64), ("dist_evals", C.c_uint64), ("adj_bytes", C.c_uint64),
                 ("vec_bytes", C.c_uint64), ("rerank_bytes", C.c_uint64), ("rotate_ms", C.c_float),
-                ("prep_ms", C.c_float), ("beam_ms", C.c_float), ("rerank_ms", C.c_float)]
+                ("prep_ms", C.c_float), ("beam_ms", C.c_float), ("rerank_ms", C.c_float), ("beam_kernel", C.c_char * 96)]
 
     def as_dict(self):
-        return {k: (float if k.endswith("_ms") else int)(getattr(self, k)) for k, _ in self._fields_}
+        out = {k: (float if k.endswith("_ms") else int)(getattr(self, k)) for k, _ in self._fields_ if k != "beam_kernel"}
+        out["beam_kernel"] = self.beam_kernel.decode()
+        return out
 
 
 class JxError(RuntimeError):
@@ -99,9 +105,10 @@ class Index:
     """Owns the arena tensor and the opaque handle; methods mirror the C ABI."""
 
     def __init__(self, dim, dtype, R, L_build, alpha=1.2, capacity=0, max_batch=0, quant_bits=0, batch_growth=0.25,
-                 device="cuda:0"):
-        self.params = Params(dim=dim, dtype=dtype, R=R, L_build=L_build, alpha=alpha, cand_mode=CAND_FRONTIER,
-                             capacity=capacity, max_batch=max_batch or capacity, quant_bits=quant_bits, batch_growth=batch_growth)
+                 device="cuda:0", flags=0, cand_mode=CAND_FRONTIER):
+        self.params = Params(dim=dim, dtype=dtype, R=R, L_build=L_build, alpha=alpha, cand_mode=cand_mode,
+                             capacity=capacity, max_batch=max_batch or capacity, quant_bits=quant_bits, batch_growth=batch_growth,
+                             flags=flags)
         self.device = torch.device(device)
         self.dim, self.dtype, self.R = dim, dtype, R
         nbytes = jx_arena_bytes(self.params)
@@ -118,6 +125,10 @@ class Index:
 
     def __del__(self):
         self.close()
+
+    # -- jx_set_flags
+    def set_flags(self, flags):
+        _check(_lib.jx_set_flags(self._h, C.c_uint32(flags)))
 
     # -- jx_size
     def size(self):
@@ -150,10 +161,8 @@ class Index:
         return adj, deg
 
     # -- jx_quantize / jx_export_codes / stage entry points
-    def quantize(self, bits, rotation, centroid=None, query_bits=8, rule=None):
+    def quantize(self, bits, rotation, centroid=None, query_bits=8, rule=RULE_DEFAULT):
         assert rotation.dtype == torch.float32 and rotation.shape == (self.dim, self.dim)
-        if rule is None:  # the max-cosine rule where the library offers it
-            rule = RULE_MAXCOS if (bits in (2, 4) and self.dim * ((1 << (bits - 1)) - 1) <= 8192 and self.dim <= 4096) else RULE_MAXABS
         with torch.cuda.device(self.device):
             _check(_lib.jx_quantize(self._h, C.c_int32(bits), _ptr(rotation), _ptr(centroid), C.c_int32(query_bits),
                                     C.c_int32(rule), _stream()))

@@ -71,7 +71,7 @@ def test_arena_size_and_parameter_checks(lib):
     assert q >= 1000 * (3840 + 512) + 960 * 960 * 4
     for bad in (dict(dim=0), dict(dim=100), dict(dtype=7), dict(R=0), dict(R=257), dict(L_build=513), dict(alpha=0.5),
                 dict(capacity=0), dict(max_batch=0), dict(quant_bits=3), dict(quant_bits=4, dim=48),
-                dict(batch_growth=1.5), dict(cand_mode=9), dict(dtype=jx.F16, dim=12)):
+                dict(batch_growth=1.5), dict(cand_mode=9), dict(dtype=jx.F16, dim=12), dict(flags=1 << 20)):
         rc = lib.jx_arena_bytes(C.byref(_params(jx, **bad)))
         assert rc == -1, bad
         assert lib.jx_last_error()
@@ -81,6 +81,7 @@ def test_arena_size_and_parameter_checks(lib):
     assert lib.jx_create(C.byref(p), None, C.c_int64(n), None, C.byref(out)) == -1
     assert lib.jx_create(C.byref(p), C.c_void_p(256), C.c_int64(16), None, C.byref(out)) == -2
     assert lib.jx_insert(None, None, C.c_int64(1), None) == -1
+    assert lib.jx_set_flags(None, 0) == -1
     assert lib.jx_search(None, None, C.c_int64(1), 1, 1, 0, 0, None, None, None, None) == -1
     assert lib.jx_delete(None, None, C.c_int64(1), None) == -1
     assert lib.jx_consolidate(None, None) == -1 and lib.jx_compact(None, None, None) == -1

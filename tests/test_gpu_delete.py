@@ -225,7 +225,7 @@ def test_rabitq_search_skips_deleted(jx):
     from paper_2601_07048_amd import datagen
     n, d, R, L = 3000, 128, 32, 64
     x = random_data(n, d, np.float32, seed=31)
-    q = random_data(100, d, np.float32, seed=32)
+    q = random_data(2000, d, np.float32, seed=32)
     ref = oracle.Index(d, x.dtype, R, L, 1.2, n)
     ref.insert(x)
     adj, _ = ref.graph()
@@ -244,7 +244,7 @@ def test_rabitq_search_skips_deleted(jx):
     ref.delete(dele)
     oi = ref.search(q, 10, L, mode=1, rerank=L)["ids"]
     r_g, r_o = oracle.recall_at_k(ids, gt), oracle.recall_at_k(oi, gt)
-    assert abs(r_g - r_o) <= 0.005 and r_g > 0.7
+    assert abs(r_g - r_o) <= 0.002 and r_g > 0.7, (r_g, r_o)
     assert (ids == oi).all(axis=1).mean() > 0.95
 
 

@@ -76,43 +76,45 @@ def test_fullsize_search_sampled_against_oracle(jx, big):
     assert np.array_equal(gd.cpu().numpy().astype(np.float64)[sample[:16]], od)
 
 
-def test_fullsize_two_expansions_per_round_equal_one(jx, big):
-    """All 10,000 queries at the beam widths the two-expansion kernel serves: ids, distances and the expansion and
-    evaluation counters equal those of the one-expansion kernel (JX_BEAM_PAIR=0 is read once per process, so the
-    other side runs in a child process on the same graph, imported from a file)."""
-    import hashlib
-    import os
-    import subprocess
-    import sys
-    import tempfile
+def test_fullsize_kernel_variants_against_oracle_and_each_other(jx, big):
+    """The variants of the beamSearch kernel that the library can be switched to (jx_set_flags) on the 1M-point
+    graph: one expansion per round instead of two, a table of full ids, no visited filter, one / four chunks per lane.
+    Each must give the oracle's ids and distances on sampled queries, and -- all 10,000 queries -- exactly the
+    default variant's results and expansion count; the evaluation count changes only with the visited filter."""
     x, q, g, adj, deg = big
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    code = r"""
-import sys, hashlib, numpy as np, torch
-from paper_2601_07048_amd import jx, datagen
-n, entry, path = int(sys.argv[1]), int(sys.argv[2]), sys.argv[3]
-x = torch.from_numpy(datagen.base(2, n)).cuda()
-adj = torch.from_numpy(np.load(path)).cuda()
-g = jx.Index(128, jx.U8, 64, 128, 1.2, capacity=n, max_batch=n // 4 + 1)
-g.import_graph(x, adj, entry)
-q = torch.from_numpy(datagen.queries(2, 10000)).cuda()
-for L in (64, 96, 128):
-    ids, dist, st = g.search(q, 10, L, stats=True)
-    h = hashlib.sha256(ids.cpu().numpy().tobytes() + dist.cpu().numpy().tobytes()).hexdigest()
-    print('res', L, h, st['hops'], st['dist_evals'])
-"""
-    with tempfile.TemporaryDirectory() as td:
-        path = os.path.join(td, "adj.npy")
-        np.save(path, u32(adj))
-        r = subprocess.run([sys.executable, "-c", code, str(N), str(g.size()[1]), path], cwd=root,
-                           env=dict(os.environ, JX_BEAM_PAIR="0"), capture_output=True, text=True, timeout=600)
-    assert r.returncode == 0 and r.stdout.count("res ") == 3, r.stdout[-2000:] + r.stderr[-2000:]
-    want = {int(l.split()[1]): l.split()[2:] for l in r.stdout.splitlines() if l.startswith("res ")}
+    ref = oracle.Index(128, np.uint8, R, LB, 1.2, N)
+    ref.set_graph(x, u32(adj), g.size()[1])
+    sample = np.random.default_rng(3).choice(NQ, 100, replace=False)
     dq = dev(q)
-    for L in (64, 96, 128):
-        ids, dist, st = g.search(dq, 10, L, stats=True)
-        h = hashlib.sha256(ids.cpu().numpy().tobytes() + dist.cpu().numpy().tobytes()).hexdigest()
-        assert [h, str(st["hops"]), str(st["dist_evals"])] == want[L], L
+    variants = {"one expansion per round": jx.FLAG_NO_PAIR, "full-id table": jx.FLAG_VISITED_IDS,
+                "no visited filter": jx.FLAG_VISITED_NONE, "one chunk per lane": jx.FLAG_LANES_WIDE,
+                "four chunks per lane": jx.FLAG_LANES_NARROW | jx.FLAG_NO_PAIR}
+    try:
+        for L in (64, 96, 128):
+            g.set_flags(0)
+            ids0, dist0, st0 = g.search(dq, 10, L, stats=True)
+            assert st0["beam_kernel"].startswith("beam_search_pair_kernel<0,4,2,")
+            want = ref.search(q[sample], 10, L)
+            no_filter = ref.search(q[sample], 10, L, filter=oracle.FILTER_NONE)
+            assert np.array_equal(u32(ids0)[sample], want["ids"])
+            for name, fl in variants.items():
+                g.set_flags(fl)
+                ids, dist, st = g.search(dq, 10, L, stats=True)
+                assert "pair" not in st["beam_kernel"] or not (fl & (jx.FLAG_NO_PAIR | jx.FLAG_VISITED_NONE)), name
+                assert np.array_equal(u32(ids)[sample], want["ids"]), (name, L)
+                assert np.array_equal(dist.cpu().numpy().astype(np.float64)[sample], want["dist"]), (name, L)
+                assert torch.equal(ids, ids0) and torch.equal(dist, dist0), (name, L)
+                assert st["hops"] == st0["hops"], (name, L)
+                if fl & jx.FLAG_VISITED_NONE:
+                    # Alg. 2 as printed evaluates every neighbour of every expanded vertex: the oracle without a
+                    # filter counts the same evaluations on the sampled queries, so check the total's magnitude
+                    assert st["dist_evals"] > 1.5 * st0["dist_evals"]
+                    one = g.search(dev(q[sample]), 10, L, stats=True)[2]
+                    assert one["dist_evals"] == no_filter["evals"] and one["hops"] == no_filter["hops"], L
+                elif not (fl & jx.FLAG_VISITED_IDS):
+                    assert st["dist_evals"] == st0["dist_evals"], (name, L)
+    finally:
+        g.set_flags(0)
 
 
 def test_fullsize_build_matches_oracle(jx, big):
@@ -179,6 +181,36 @@ def test_fullsize_delete_consolidate_sampled_against_oracle(jx, big):
     assert not dead[u32(ids)].any()
 
 
+def test_streaming_inserts_of_100k_match_oracle(jx):
+    """The streaming workload's shape: ten jx_insert calls of 100,000 points into one growing index (workload 2's
+    generator, R = 64, L_build = 128).  The whole adjacency table equals the oracle's after calls 1, 5 and 10, and a
+    10,000-query batch at L = 128 on the final index gives the oracle's ids and distances on sampled queries."""
+    n, B = 1_000_000, 100_000
+    x = datagen.base(2, n)
+    dx = dev(x)
+    g = jx.Index(128, jx.U8, R, LB, 1.2, capacity=n, max_batch=B)
+    ref = oracle.Index(128, np.uint8, R, LB, 1.2, n)
+    for call in range(1, 11):
+        lo, hi = (call - 1) * B, call * B
+        g.insert(dx[lo:hi])
+        ref.insert(x[lo:hi])
+        if call in (1, 5, 10):
+            adj, _ = g.export_graph()
+            oadj, _ = ref.graph()
+            assert g.size() == (hi, ref.entry)
+            bad = np.nonzero((u32(adj) != oadj).any(axis=1))[0]
+            assert bad.size == 0, f"after call {call}: {bad.size} rows differ, first {bad[:5]}"
+            print(f"streaming parity: call {call} ok ({hi} points)", flush=True)
+    q = datagen.queries(2, NQ)
+    ids, dist = g.search(dev(q), 10, 128)
+    sample = np.random.default_rng(9).choice(NQ, 300, replace=False)
+    want = ref.search(q[sample], 10, 128)
+    assert np.array_equal(u32(ids)[sample], want["ids"])
+    assert np.array_equal(dist.cpu().numpy().astype(np.float64)[sample], want["dist"])
+    gt, _ = g.bruteforce(dev(q), 10)
+    assert oracle.recall_at_k(u32(ids)[:2000], u32(gt)[:2000]) >= 0.95
+
+
 def _device_base(workload, n, d):
     dx = torch.empty((n, d), dtype=torch.float32, device="cuda")
     step = 16 * datagen.CHUNK
@@ -225,7 +257,7 @@ def test_fullsize_rabitq_sampled_against_oracle(jx, workload, bits, qbits):
         assert same_rows.mean() >= 0.9  # a different float32 rotation may move a vector to a neighbouring sweep optimum
     assert np.allclose(meta[srows][same_rows], wm[same_rows], rtol=1e-4)
     # searches
-    sample = np.arange(0, 2000, 10)
+    sample = np.arange(0, 2000)   # every query: the recall comparison needs the sample size
     dq = dev(q)
     L = 128
     ids, dist, st = g.search(dq, 10, L, mode=jx.RABITQ, rerank=40, stats=True)
@@ -236,7 +268,33 @@ def test_fullsize_rabitq_sampled_against_oracle(jx, workload, bits, qbits):
     assert np.allclose(dist.cpu().numpy().astype(np.float64)[sample][m], want["dist"][m], rtol=1e-4)
     gt, _ = g.bruteforce(dq, 10)
     gtn = u32(gt)[sample]
-    assert abs(oracle.recall_at_k(gi, gtn) - oracle.recall_at_k(want["ids"], gtn)) <= 0.005
+    assert abs(oracle.recall_at_k(gi, gtn) - oracle.recall_at_k(want["ids"], gtn)) <= 0.002
     oid, od = oracle.bruteforce(x, q[sample[:4]], 10)
     assert (u32(gt)[sample[:4]] == oid).mean() >= 0.95  # float32 vs double near-ties may swap neighbours
     assert st["rerank_bytes"] == 40 * 2000 * d * 4
+    if workload == 4:
+        # Which stage caps recall@10 on the 1-bit workload (the beam-width sweep with re-rank 40 saturates near
+        # 0.85).  At L = 256 the true neighbours ARE in the frontier; they are not among its first 40 entries by
+        # estimate; and ranking the same frontier with the oracle's float-query estimator in double (no integer
+        # query) puts no more of them there: the cap is the 1-bit code's resolution against the 40-candidate
+        # re-rank, not the graph, the integer query or float32.
+        Lw = 256
+        fi, _ = g.beam_frontier(dq, Lw, mode=jx.RABITQ)
+        fi = u32(fi)
+        gta = u32(gt)
+        in_front = np.mean([len(set(fi[i]) & set(gta[i])) for i in range(2000)]) / 10
+        in_40 = np.mean([len(set(fi[i, :40]) & set(gta[i])) for i in range(2000)]) / 10
+        assert in_front >= 0.95 and in_40 <= in_front - 0.05, (in_front, in_40)
+        sub = np.arange(0, 2000, 20)
+        _, q64 = oracle.rabitq_rotate(q[sub], P, cen)
+        hit_int = hit_flt = 0
+        for a_, i in enumerate(sub):
+            row = fi[i][fi[i] != 0xFFFFFFFF]
+            est = np.array([oracle.rabitq_est_float(codes[v], bits, d, float(meta[v, 0]), float(meta[v, 1]), q64[a_]) for v in row])
+            top = row[np.lexsort((row, est))[:40]]
+            hit_flt += len(set(top.tolist()) & set(gta[i].tolist()))
+            hit_int += len(set(fi[i, :40].tolist()) & set(gta[i].tolist()))
+        r_flt, r_int = hit_flt / (10 * len(sub)), hit_int / (10 * len(sub))
+        print(f"workload 4 stage cap at L={Lw}: in frontier {in_front:.4f}, in first 40 by integer-query estimate "
+              f"{in_40:.4f} (sample {r_int:.4f}), by float-query double estimate {r_flt:.4f}", flush=True)
+        assert abs(r_flt - r_int) <= 0.03, (r_flt, r_int)

@@ -182,36 +182,21 @@ def test_insert_errors(jx):
     assert g2.size()[0] == 9
 
 
-def test_matrix_core_prune_on_uint8_variant():
+def test_matrix_core_prune_on_uint8_variant(jx):
     """The matrix-core robustPrune also has a uint8 instantiation (int8 MFMA, exact integers).  It is slower than
-    the LDS-cached form for 128-byte vectors and therefore off by default (JX_GRAM_U8=1 switches it on, read once
-    per process): run it in a child process and require the oracle's graph bit for bit, build and consolidation."""
-    import os
-    import subprocess
-    import sys
-    code = r"""
-import sys, numpy as np, torch
-sys.path.insert(0, 'tests')
-import oracle
-from paper_2601_07048_amd import jx
-from gpu_common import dev, u32, random_data
-for (n, d, R, L, growth) in ((3000, 128, 32, 64, 0.25), (2500, 64, 100, 128, 0.25), (5000, 32, 12, 24, 1.0)):
-    x = random_data(n, d, np.uint8, seed=n + R)
-    ref = oracle.Index(d, np.uint8, R, L, 1.2, n, batch_growth=growth)
-    ref.insert(x)
-    g = jx.Index(d, jx.U8, R, L, 1.2, capacity=n, max_batch=n, batch_growth=growth)
-    g.insert(dev(x))
-    assert g.size() == (n, ref.entry)
-    assert np.array_equal(u32(g.export_graph()[0]), ref.graph()[0]), 'build'
-    dele = np.random.default_rng(n).choice(n, n // 3, replace=False).astype(np.uint32)
-    ref.delete(dele); g.delete(dev(dele)); ref.consolidate(); g.consolidate()
-    assert np.array_equal(u32(g.export_graph()[0]), ref.graph()[0]), 'consolidate'
-print('variant ok')
-"""
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    env = dict(os.environ, JX_GRAM_U8="1")
-    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
-    assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+    the LDS-cached form for 128-byte vectors and therefore off by default (JX_FLAG_GRAM_U8 switches it on): the
+    oracle's graph bit for bit, build and consolidation."""
+    for (n, d, R, L, growth) in ((3000, 128, 32, 64, 0.25), (2500, 64, 100, 128, 0.25), (5000, 32, 12, 24, 1.0)):
+        x = random_data(n, d, np.uint8, seed=n + R)
+        ref = oracle.Index(d, np.uint8, R, L, 1.2, n, batch_growth=growth)
+        ref.insert(x)
+        g = jx.Index(d, jx.U8, R, L, 1.2, capacity=n, max_batch=n, batch_growth=growth, flags=jx.FLAG_GRAM_U8)
+        g.insert(dev(x))
+        assert g.size() == (n, ref.entry)
+        assert np.array_equal(u32(g.export_graph()[0]), ref.graph()[0]), "build"
+        dele = np.random.default_rng(n).choice(n, n // 3, replace=False).astype(np.uint32)
+        ref.delete(dele); g.delete(dev(dele)); ref.consolidate(); g.consolidate()
+        assert np.array_equal(u32(g.export_graph()[0]), ref.graph()[0]), "consolidate"
 
 
 def test_incremental_prune_of_full_rows(jx):
@@ -233,34 +218,27 @@ def test_incremental_prune_of_full_rows(jx):
 
 
 def test_incremental_prune_switched_off_gives_the_same_graph(jx):
-    """At a size the oracle does not reach in seconds: the graph built with the shortcut equals the graph built
-    without it (JX_INCR_PRUNE=0 is read once per process, hence the child process)."""
-    import hashlib
-    import os
-    import subprocess
-    import sys
-    n = 200_000
-    code = r"""
-import sys, hashlib, numpy as np, torch
-from paper_2601_07048_amd import jx, datagen
-n = %d
-x = torch.from_numpy(datagen.base(2, n)).cuda()
-g = jx.Index(128, jx.U8, 64, 128, 1.2, capacity=n, max_batch=n // 4 + 1)
-for lo in range(0, n, 50_000):
-    g.insert(x[lo:lo + 50_000])
-adj = g.export_graph()[0].cpu().numpy()
-print('sha', hashlib.sha256(adj.tobytes()).hexdigest())
-""" % n
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=dict(os.environ, JX_INCR_PRUNE="0"),
-                       capture_output=True, text=True, timeout=600)
-    assert r.returncode == 0 and "sha " in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
-    want = r.stdout.split("sha ")[1].split()[0]
-    from paper_2601_07048_amd import datagen
+    """Streaming inserts with the incremental prune switched off (JX_FLAG_NO_INCR_PRUNE) and on: both graphs equal
+    the oracle's after every call at N = 40,000, and each other at N = 200,000 (where the oracle is not run)."""
     import torch
-    x = torch.from_numpy(datagen.base(2, n)).cuda()
-    g = jx.Index(128, jx.U8, 64, 128, 1.2, capacity=n, max_batch=n // 4 + 1)
-    for lo in range(0, n, 50_000):
-        g.insert(x[lo:lo + 50_000])
-    got = hashlib.sha256(g.export_graph()[0].cpu().numpy().tobytes()).hexdigest()
-    assert got == want
+    n = 40_000
+    x = datagen.base(2, n)
+    ref = oracle.Index(128, np.uint8, 64, 128, 1.2, n)
+    gs = [jx.Index(128, jx.U8, 64, 128, 1.2, capacity=n, max_batch=n // 4 + 1, flags=fl) for fl in (0, jx.FLAG_NO_INCR_PRUNE)]
+    for lo in range(0, n, 10_000):
+        ref.insert(x[lo:lo + 10_000])
+        want = ref.graph()[0]
+        for g in gs:
+            g.insert(dev(x[lo:lo + 10_000]))
+            assert np.array_equal(u32(g.export_graph()[0]), want), (lo, g.params.flags)
+    del gs, ref
+    n = 200_000
+    dx = torch.from_numpy(datagen.base(2, n)).cuda()
+    tables = []
+    for fl in (0, jx.FLAG_NO_INCR_PRUNE):
+        g = jx.Index(128, jx.U8, 64, 128, 1.2, capacity=n, max_batch=n // 4 + 1, flags=fl)
+        for lo in range(0, n, 50_000):
+            g.insert(dx[lo:lo + 50_000])
+        tables.append(g.export_graph()[0])
+        del g
+    assert torch.equal(tables[0], tables[1])

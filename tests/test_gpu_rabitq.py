@@ -169,7 +169,7 @@ def test_quantize_end_to_end(jx, bits, d, n, rule):
     differ where a coordinate sits on a rounding boundary."""
     wl = 3 if bits == 4 else 4
     x = datagen.base(wl, n)
-    q = datagen.queries(wl, 300)
+    q = datagen.queries(wl, 2000)
     P = datagen.rotation(wl)
     ix, g = _quantized_pair(jx, x, P, bits, 8, R=32, L=64, rule=rule)
     wc, wm, wcen = ix.codes()
@@ -196,15 +196,39 @@ def test_quantize_end_to_end(jx, bits, d, n, rule):
     m = ids == ref["F_ids"]
     assert m.mean() > 0.9
     assert np.allclose(dist[m], ref["F_dist"][m], rtol=1e-3, atol=1e-3 * np.abs(ref["F_dist"]).mean())
-    # re-ranked results: exact distances, recall close to the oracle's
+    # The chain behind an estimate, on the GPU's own intermediate results: the oracle's query preparation fed with
+    # the GPU's float32 rotation of the query, and the oracle's integer estimator on the GPU's codes, must give the
+    # GPU's estimate bit for bit.  And where the oracle's own chain (double rotation) arrives at the same integer
+    # query and the same code, the two estimates agree to 1e-4 relative (only lo and delta differ, by rounding).
+    qs = 60
+    qr_gpu = g.rotate(dev(q[:qs])).cpu().numpy()
+    qr_ref, _ = oracle.rabitq_rotate(q[:qs], P, wcen)
+    scale = np.abs(ref["F_dist"]).mean()
+    n_bit, n_tol = 0, 0
+    for i in range(qs):
+        qint_g, m4_g = oracle.rabitq_query_prep(qr_gpu[i], bits, 8)
+        qint_o, m4_o = oracle.rabitq_query_prep(qr_ref[i], bits, 8)
+        for j in (0, 3, 17, 40, 63):
+            v = int(ids[i, j])
+            if v == 0xFFFFFFFF:
+                continue
+            e_chain = oracle.rabitq_est_int(gc[v], bits, d, gm[v, 0], gm[v, 1], qint_g, m4_g)
+            assert np.float32(e_chain) == np.float32(dist[i, j]), (i, j)
+            n_bit += 1
+            if np.array_equal(qint_g, qint_o) and np.array_equal(gc[v], wc[v]):
+                e_ref = oracle.rabitq_est_int(wc[v], bits, d, wm[v, 0], wm[v, 1], qint_o, m4_o)
+                assert abs(e_ref - dist[i, j]) <= 1e-4 * abs(e_ref) + 1e-6 * scale, (i, j, e_ref, dist[i, j])
+                n_tol += 1
+    assert n_bit >= 4 * qs and n_tol >= qs // 2, (n_bit, n_tol)
+    # re-ranked results: exact distances, recall within 0.002 of the oracle's (2,000 queries)
     gt, gd = oracle.bruteforce(x, q, 10)
     rr = ix.search(q, 10, 64, mode=1, rerank=40)
     gi, gdist, st = g.search(dev(q), 10, 64, mode=jx.RABITQ, rerank=40, stats=True)
     gi, gdist = u32(gi), gdist.cpu().numpy().astype(np.float64)
     r_gpu, r_ref = oracle.recall_at_k(gi, gt), oracle.recall_at_k(rr["ids"], gt)
-    assert abs(r_gpu - r_ref) <= 0.004, (r_gpu, r_ref)
+    assert abs(r_gpu - r_ref) <= 0.002, (r_gpu, r_ref)
     assert st["rerank_bytes"] == 40 * len(q) * d * 4
-    for i in range(0, len(q), 13):
+    for i in range(0, len(q), 97):
         for j in range(10):
             assert abs(gdist[i, j] - oracle.l2sq(q[i], x[gi[i, j]])) <= 1e-4 * gdist[i, j]
         keys = list(zip(gdist[i].tolist(), gi[i].tolist()))
@@ -283,7 +307,7 @@ def test_rabitq_on_uint8_data(jx):
     rotation the estimated-distance frontier equals the oracle's bit for bit; re-rank distances are exact integers."""
     n, d, R, L = 3000, 128, 32, 64
     x = random_data(n, d, np.uint8, seed=17)
-    q = random_data(100, d, np.uint8, seed=18)
+    q = random_data(2000, d, np.uint8, seed=18)
     ix = oracle_index(x, R, L)
     P = datagen.random_orthogonal(d, seed=4).astype(np.float32)
     g = gpu_index_from_oracle(jx, x, ix, R, L, quant_bits=4)
@@ -299,7 +323,7 @@ def test_rabitq_on_uint8_data(jx):
     ids, dist = g.search(dev(q), 10, L, mode=jx.RABITQ, rerank=40)
     want = ix.search(q, 10, L, mode=1, rerank=40)
     r_g, r_o = oracle.recall_at_k(u32(ids), gt), oracle.recall_at_k(want["ids"], gt)
-    assert abs(r_g - r_o) <= 0.005 and r_g > 0.6
+    assert abs(r_g - r_o) <= 0.002 and r_g > 0.6, (r_g, r_o)
     same = (u32(ids) == want["ids"]).all(axis=1)
     assert same.mean() > 0.95
     assert np.array_equal(dist.cpu().numpy().astype(np.float64)[same], want["dist"][same])  # exact integers
@@ -309,6 +333,7 @@ def test_rabitq_on_uint8_data(jx):
     ix.quantize(4, Pp, centroid=zero)
     oc, om, _ = ix.codes()
     g.import_codes(4, dev(Pp), dev(zero), dev(oc), dev(om))
+    q = q[:100]
     ref = ix.search(q, 1, 50, mode=1, want_frontier=True)
     fi, fd = g.beam_frontier(dev(q), 50, mode=jx.RABITQ)
     assert np.array_equal(u32(fi), ref["F_ids"])
@@ -318,10 +343,11 @@ def test_rabitq_on_uint8_data(jx):
 @pytest.mark.parametrize("bits,d,n", [(2, 960, 3000), (8, 960, 3000), (2, 1536, 2000), (8, 128, 3000)])
 def test_quantize_end_to_end_other_widths(jx, bits, d, n):
     """2- and 8-bit codes, whole path (rotation on the GPU in float32, oracle in double): codes at most one level
-    apart on rare coordinates, re-ranked recall within 0.005 of the oracle's, estimates close where ranks agree."""
+    apart on rare coordinates, re-ranked recall within 0.002 of the oracle's (2,000 queries), estimates close where
+    ranks agree."""
     wl = 3 if d == 960 else (4 if d == 1536 else 1)
     x = datagen.base(wl, n)
-    q = datagen.queries(wl, 200)
+    q = datagen.queries(wl, 2000)
     P = datagen.rotation(wl)
     ix, g = _quantized_pair(jx, x, P, bits, 8, R=32, L=64, rule=1)
     wc, wm, wcen = ix.codes()
@@ -335,7 +361,7 @@ def test_quantize_end_to_end_other_widths(jx, bits, d, n):
     rr = ix.search(q, 10, 64, mode=1, rerank=40)
     gi, _ = g.search(dev(q), 10, 64, mode=jx.RABITQ, rerank=40)
     r_gpu, r_ref = oracle.recall_at_k(u32(gi), gt), oracle.recall_at_k(rr["ids"], gt)
-    assert abs(r_gpu - r_ref) <= 0.005, (r_gpu, r_ref)
+    assert abs(r_gpu - r_ref) <= 0.002, (r_gpu, r_ref)
     ref = ix.search(q, 10, 64, mode=1, want_frontier=True)
     ids, dist = g.beam_frontier(dev(q), 64, mode=jx.RABITQ)
     ids, dist = u32(ids), dist.cpu().numpy().astype(np.float64)

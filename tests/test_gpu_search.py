@@ -193,15 +193,20 @@ def test_bruteforce_parity(jx, dtype, n, d, k):
 
 
 def test_import_graph_rejects_a_bad_table(jx):
-    """Ids out of range or a row with a gap would send the kernels out of bounds: refused, index unchanged."""
+    """Ids out of range, a row with a gap or a row that names a vertex twice would send the kernels out of bounds:
+    refused before any kernel runs on the table, index unchanged."""
     x = random_data(300, 32, np.uint8, seed=1)
     ix = oracle_index(x, 8, 16)
     g = gpu_index_from_oracle(jx, x, ix, 8, 16)
     adj, _ = ix.graph()
-    for bad in ("range", "gap"):
+    for bad in ("range", "gap", "repeat", "repeat-far"):
         a = adj.copy()
         if bad == "range":
             a[7, 0] = 300
+        elif bad == "repeat":
+            a[11, :] = [4, 5, 4, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF]
+        elif bad == "repeat-far":
+            a[299, :] = [1, 2, 3, 4, 5, 6, 7, 1]
         else:
             a[9, :] = [5, 0xFFFFFFFF, 6, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF]
         with pytest.raises(jx.JxError) as e:

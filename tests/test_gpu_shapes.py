@@ -31,10 +31,10 @@ def test_search_k_values_u8_bit_exact(jx, k, L):
 
 @pytest.mark.parametrize("k", [1, 50, 100])
 def test_search_k_values_rabitq_rerank(jx, k):
-    """Estimated-distance search with re-rank of max(k, 40): recall@k within 0.01 of the oracle's."""
+    """Estimated-distance search with re-rank of max(k, 40): recall@k within 0.002 of the oracle's (2,000 queries)."""
     n, d, L = 4000, 128, 128
     x = random_data(n, d, np.float32, seed=70 + k)
-    q = random_data(120, d, np.float32, seed=71 + k)
+    q = random_data(2000, d, np.float32, seed=71 + k)
     ref = oracle_index(x, 32, 64)
     g = gpu_index_from_oracle(jx, x, ref, 32, 64, quant_bits=4)
     P = datagen.random_orthogonal(d, seed=9).astype(np.float32)
@@ -45,7 +45,7 @@ def test_search_k_values_rabitq_rerank(jx, k):
     want = ref.search(q, k, L, mode=1, rerank=rr)["ids"]
     gt = oracle.bruteforce(x, q, k)[0]
     r_g, r_o = oracle.recall_at_k(u32(ids), gt), oracle.recall_at_k(want, gt)
-    assert abs(r_g - r_o) <= 0.01 and r_g > 0.6
+    assert abs(r_g - r_o) <= 0.002 and r_g > 0.6, (r_g, r_o)
     assert (u32(ids) == want).all(axis=1).mean() > 0.9
 
 
@@ -53,7 +53,7 @@ def test_deep_like_96d_build_and_search(jx):
     """Workload 6 (96-d float32, unit norm): GPU build and search against the oracle's, through recall."""
     n = 20000
     x = datagen.base(6, n)
-    q = datagen.queries(6, 500)
+    q = datagen.queries(6, 2000)
     ref = oracle.Index(96, np.float32, 32, 64, 1.2, n)
     ref.insert(x)
     g = jx.Index(96, jx.F32, 32, 64, 1.2, capacity=n, max_batch=n)
@@ -63,7 +63,7 @@ def test_deep_like_96d_build_and_search(jx):
     for L in (32, 64):
         r_o = oracle.recall_at_k(ref.search(q, 10, L)["ids"], gt)
         r_g = oracle.recall_at_k(u32(g.search(dev(q), 10, L)[0]), gt)
-        assert abs(r_o - r_g) <= 0.004, (L, r_o, r_g)
+        assert abs(r_o - r_g) <= 0.002, (L, r_o, r_g)
     assert r_g >= 0.95
     # same graph on both sides: ids agree except where float32 rounding reorders near-ties
     adj, _ = ref.graph()
@@ -77,7 +77,7 @@ def test_mips_augment_parity_and_search(jx):
     then build + search on the augmented vectors; the ground truth is the plain inner product."""
     n, d, dout = 20000, 200, 204
     x = datagen.base(7, n)
-    q = datagen.queries(7, 300)
+    q = datagen.queries(7, 2000)
     norms = jx.mips_augment(dev(x), want_norms=True).cpu().numpy()
     want_norms = np.linalg.norm(x.astype(np.float64), axis=1)
     assert np.allclose(norms, want_norms, rtol=1e-6)
@@ -99,4 +99,4 @@ def test_mips_augment_parity_and_search(jx):
     ref.insert(oxa)
     r_o = oracle.recall_at_k(ref.search(oqa, 10, 64)["ids"], gt)
     r_g = oracle.recall_at_k(u32(g.search(qa, 10, 64)[0]), gt)
-    assert abs(r_o - r_g) <= 0.01 and r_g > 0.8, (r_o, r_g)
+    assert abs(r_o - r_g) <= 0.002 and r_g > 0.8, (r_o, r_g)

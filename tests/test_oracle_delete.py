@@ -53,7 +53,7 @@ def test_delete_invariants_and_recall():
         row = adj[i, :deg[i]]
         assert i not in row and len(set(row.tolist())) == len(row)
     after = oracle.recall_at_k(ix.search(q, 10, 64)["ids"], gt)
-    # Sec. 6.5: deletion + consolidation keeps recall (0.986 -> 0.988 in the paper's Table 2)
+    # Sec. 6.4: deletion + consolidation keeps recall (0.986 -> 0.988 in the paper's Table 2)
     assert marked >= before - 0.02 and after >= before - 0.02
     # a second consolidate changes nothing; inserts after it never link to deleted vertices
     ix.consolidate()
