@@ -32,6 +32,8 @@ def test_bench_json_contract(extra):
     rf = d["roofline"]
     assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3 and rf["achieved"] > 0 and rf["kernel_ms"] > 0
+    assert rf["kernel"].startswith("beam_search") and rf["traffic"] is None and "traffic_source" in rf
+    assert d["config"]["recall_target_met"] == (d["config"]["recall_at_10"] >= 0.95)
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and "sample" in cb
     # the oracle on the exported graph returns what the GPU returned
@@ -39,6 +41,20 @@ def test_bench_json_contract(extra):
     assert abs(d["value"] - 512 / (d["ms_per_step"] * 1e-3)) / d["value"] < 0.02
     dl = d["config"]["delete"]
     assert dl["deleted"] == int(0.1 * int(n)) and dl["consolidate_s"] > 0 and dl["compact_s"] >= 0
+
+
+def test_bench_default_run_covers_the_other_configurations():
+    """The default run measures configurations 1, 3, 4 and 5 after the headline; here at 2 % of their sizes."""
+    r = _run(["--n", "60000", "--nq", "512", "--steps", "3", "--warmup", "1", "--cpu-queries", "0", "--others-scale", "0.02"], timeout=600)
+    assert r.returncode == 0, r.stderr[-3000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.strip()][-1])
+    others = d["config"]["others"]
+    assert [o["workload"].split(":")[0] for o in others] == ["workload 1", "workload 3", "workload 4", "workload 5"]
+    for o in others:
+        assert o["queries_per_s"] > 0 and 0 < o["recall_at_10"] <= 1 and o["roofline"]["kernel"].startswith("beam_search")
+        assert o["roofline"]["kernel_ms"] > 0 and o["roofline"]["bytes_per_launch"] > 0
+    assert others[3]["stream"][-1]["N"] == 200000 and others[3]["stream"][-1]["batch_inserts_per_s"] > 0
+    assert "centres N(0,0.1^2)" in others[1]["workload"] and "i^-1.0" in others[1]["workload"]
 
 
 def test_bench_refuses_more_than_one_gpu():
