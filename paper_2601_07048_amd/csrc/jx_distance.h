@@ -21,6 +21,22 @@ __device__ __forceinline__ float hdot2(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), c, false);
 }
 
+// RaBitQ records whose code chunks are covered exactly by T lanes x 3 chunks: the lanes hold code chunks only and
+// every lane reads the record's meta chunk (data_add, data_rescale, code sum) with a load of its own.  For the
+// 208-byte 1-bit records of d = 1536 (12 code chunks + meta) this is 4 lanes x 3 chunks, 16 records per pass, against
+// 8 lanes x 2 chunk slots of which 3 in 16 are idle and the meta lane counts bits of zero planes.
+template <int KIND, int CPL>
+constexpr bool sep_meta() {
+    return (KIND == 2 || KIND == 3) && CPL == 3;
+}
+
+// popcount(x) + acc in one instruction (the compiler prefers popcount-to-zero plus three-operand adds)
+__device__ __forceinline__ uint32_t bcnt_acc(uint32_t x, uint32_t acc) {
+    uint32_t r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(acc));
+    return r;
+}
+
 template <int KIND, int CPL, int QB>
 struct QueryRegs {
     static constexpr int PLANES = (KIND == K_RQ4) ? 2 : (KIND == K_RQ1 ? QB : 1);
@@ -33,19 +49,31 @@ struct QueryRegs {
     float lo, delta, qadd, qsumq;
 };
 
-template <int KIND, int T, int CPL, int QB>
+// TILED (exact kinds; the load ablation of Sec. 4.4): register m of a lane holds the 4-byte element lig + T * m of
+// the vector -- consecutive lanes of a group read consecutive elements, one element per load ("tiled") -- instead of
+// the four elements of 16-byte chunk lig + T * (m / 4) ("chunked").  Query and records use the same assignment, so
+// the distance is the same sum.
+template <int KIND, int T, int CPL, int QB, bool TILED = false>
 __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const DistSrc& a, int64_t qi, int lig) {
     const uint8_t* base = a.qrecs + qi * a.qrec_stride;
     if constexpr (KIND == K_U8 || KIND == K_F32 || KIND == K_F16) {
+        if constexpr (TILED) {
 #pragma unroll
-        for (int j = 0; j < CPL; j++) {
-            int ch = lig + T * j;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (ch < a.nch) v = load16(base + (size_t)ch * 16);
-            q.w[4 * j + 0] = v.x;
-            q.w[4 * j + 1] = v.y;
-            q.w[4 * j + 2] = v.z;
-            q.w[4 * j + 3] = v.w;
+            for (int m = 0; m < 4 * CPL; m++) {
+                const int e = lig + T * m;
+                q.w[m] = e < 4 * a.nch ? reinterpret_cast<const uint32_t*>(base)[e] : 0u;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < CPL; j++) {
+                int ch = lig + T * j;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (ch < a.nch) v = load16(base + (size_t)ch * 16);
+                q.w[4 * j + 0] = v.x;
+                q.w[4 * j + 1] = v.y;
+                q.w[4 * j + 2] = v.z;
+                q.w[4 * j + 3] = v.w;
+            }
         }
         if constexpr (KIND == K_U8) {
             int32_t s = 0;
@@ -91,30 +119,49 @@ __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const Di
 // lane has to be masked.  Lane groups beyond the last candidate of a batch read
 // the last candidate's record again (same cache lines, no extra traffic) and
 // drop the result; this keeps the gathers free of per-lane predication.
-template <int KIND, int T, int CPL, int QB, int U, bool FULL = false>
+template <int KIND, int T, int CPL, int QB, int U, bool FULL = false, bool TILED = false>
 __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, const DistSrc& a, int s0, int n_new,
                                            const uint32_t* cand_id, uint64_t* cand_key, int g, int lig) {
     constexpr int G = 64 / T;
+    constexpr bool SEP = sep_meta<KIND, CPL>();
     uint4 data[U][CPL];
+    uint4 mdat[SEP ? U : 1];
     uint32_t ids[U];
 #pragma unroll
     for (int u = 0; u < U; u++) {
         int c = s0 + u * G + g;
         ids[u] = cand_id[c < n_new ? c : n_new - 1];
     }
+    const int nload = SEP ? a.meta_chunk : a.nch;  // chunks that the lanes' chunk slots cover
 #pragma unroll
     for (int u = 0; u < U; u++) {
         if (s0 + u * G < n_new) {  // wave-uniform
+            const uint8_t* rec = a.recs + (size_t)ids[u] * (size_t)a.rec_stride;
+            if constexpr (TILED) {
+                const uint32_t* el = reinterpret_cast<const uint32_t*>(rec);
+#pragma unroll
+                for (int j = 0; j < CPL; j++) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        const int e = lig + T * (4 * j + c);
+                        w[c] = (FULL || e < 4 * a.nch) ? el[e] : 0u;
+                    }
+                    data[u][j] = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+                continue;
+            }
 #pragma unroll
             for (int j = 0; j < CPL; j++) {
                 int ch = lig + T * j;
                 if constexpr (FULL) {
-                    data[u][j] = load16(a.recs + (size_t)ids[u] * (size_t)a.rec_stride + (size_t)ch * 16);
+                    data[u][j] = load16(rec + (size_t)ch * 16);
                 } else {
                     data[u][j] = make_uint4(0, 0, 0, 0);
-                    if (ch < a.nch) data[u][j] = load16(a.recs + (size_t)ids[u] * (size_t)a.rec_stride + (size_t)ch * 16);
+                    if (ch < nload) data[u][j] = load16(rec + (size_t)ch * 16);
                 }
             }
+            if constexpr (SEP) mdat[u] = load16(rec + (size_t)a.meta_chunk * 16);
         }
     }
 #pragma unroll
@@ -181,11 +228,17 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
             uint32_t I = 0, S = 0;
             float m_add = 0.f, m_rescale = 0.f;
             const int mj = a.meta_chunk / T, ml = a.meta_chunk % T;
-            writer = (lig == ml);
+            if constexpr (SEP) {
+                m_add = __uint_as_float(mdat[u].x);
+                m_rescale = __uint_as_float(mdat[u].y);
+                S = mdat[u].z;
+            } else {
+                writer = (lig == ml);
+            }
 #pragma unroll
             for (int j = 0; j < CPL; j++) {
                 const uint4 v = data[u][j];
-                if (j == mj) {
+                if (!SEP && j == mj) {
                     m_add = __uint_as_float(v.x);
                     m_rescale = __uint_as_float(v.y);
                     S = v.z;
@@ -206,13 +259,18 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
                     }
                     I += ((QB == 8) ? (16u * ih + il) : il) << q.ps[j];
                 } else {
+                    // sum_b 2^b popcount(code & plane_b): one AND and one accumulating popcount per dword and plane
+                    uint32_t Ij = 0;
 #pragma unroll
-                    for (int b = 0; b < QB; b++) {
+                    for (int b = QB - 1; b >= 0; b--) {
                         const uint32_t* qp = &q.w[(b * CPL + j) * 4];
-                        uint32_t cnt = __builtin_popcount(v.x & qp[0]) + __builtin_popcount(v.y & qp[1]) +
-                                       __builtin_popcount(v.z & qp[2]) + __builtin_popcount(v.w & qp[3]);
-                        I += cnt << (b + q.ps[j]);
+                        uint32_t cnt = bcnt_acc(v.x & qp[0], 0u);
+                        cnt = bcnt_acc(v.y & qp[1], cnt);
+                        cnt = bcnt_acc(v.z & qp[2], cnt);
+                        cnt = bcnt_acc(v.w & qp[3], cnt);
+                        Ij = (Ij << 1) + cnt;  // Horner over the planes
                     }
+                    I += Ij << q.ps[j];
                 }
             }
             I = group_sum<T>(I);

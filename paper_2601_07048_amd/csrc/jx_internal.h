@@ -46,6 +46,8 @@ struct BeamArgs {
 };
 // kernel_name (may be NULL): receives the name of the instance that was launched, at most 96 bytes
 hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st, char* kernel_name = nullptr);
+// ablation instances (JX_FLAG_TILED_LOADS, JX_FLAG_QPW_*, JX_FLAG_WAVES_*); hipErrorInvalidValue where none exists
+hipError_t launch_beam_variant(int kind, const BeamArgs& a, hipStream_t st, char* kernel_name);
 
 // ---- batch insertion -------------------------------------------------------
 struct InsertArgs {

@@ -143,7 +143,9 @@ def _quantized_pair(jx, x, P, bits, qbits, R=24, L=48, centroid=None, inject=Fal
 
 
 @pytest.mark.parametrize("bits,qbits,d", [(4, 8, 960), (1, 8, 1536), (4, 4, 128), (1, 4, 256), (1, 8, 96), (4, 8, 1536),
-                                          (2, 4, 960), (2, 8, 96), (2, 4, 1536), (8, 8, 96), (8, 8, 960), (8, 4, 1536)])
+                                          (2, 4, 960), (2, 8, 96), (2, 4, 1536), (8, 8, 96), (8, 8, 960), (8, 4, 1536),
+                                          # 9 to 12 code chunks with B_q = 4: four lanes x three code chunks, meta chunk apart
+                                          (1, 4, 1536), (1, 4, 1280), (2, 4, 768), (1, 4, 1152)])
 def test_estimated_beam_bit_exact_on_injected_codes(jx, bits, qbits, d):
     """beamSearch + estimator stage: oracle codes injected, rotation a signed
     permutation and c = 0 (so both sides see identical rotated queries).  The

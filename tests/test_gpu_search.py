@@ -214,3 +214,60 @@ def test_import_graph_rejects_a_bad_table(jx):
         assert e.value.code == -1
     got, _ = g.export_graph()
     assert np.array_equal(u32(got), adj)
+
+
+def test_ablation_variants_uint8_bit_exact(jx, u8_case):
+    """The kernel variants of the ablation (jx_set_flags) on 128-byte uint8 vectors: every visited-filter, lane,
+    load and workgroup variant returns the oracle's frontier (ids, distances) and expansion count."""
+    x, q, ix, g = u8_case
+    variants = [0, jx.FLAG_NO_PAIR, jx.FLAG_VISITED_IDS, jx.FLAG_VISITED_NONE, jx.FLAG_LANES_WIDE, jx.FLAG_LANES_NARROW,
+                jx.FLAG_TILED_LOADS, jx.FLAG_QPW_2, jx.FLAG_QPW_4, jx.FLAG_QPW_4 | jx.FLAG_VISITED_NONE,
+                jx.FLAG_TILED_LOADS | jx.FLAG_VISITED_IDS]
+    names = set()
+    try:
+        for L in (10, 64, 100, 200):
+            ref = ix.search(q, 1, L, want_frontier=True)
+            nof = ix.search(q, 1, L, filter=oracle.FILTER_NONE)
+            for fl in variants:
+                g.set_flags(fl)
+                ids, dist, st = g.beam_frontier(dev(q), L, stats=True)
+                names.add(st["beam_kernel"].split("<")[0] + "<" + ",".join(st["beam_kernel"].split("<")[1].split(",")[:3]))
+                assert np.array_equal(u32(ids), ref["F_ids"]), (fl, L)
+                assert np.array_equal(dist.cpu().numpy().astype(np.float64), ref["F_dist"]), (fl, L)
+                assert st["hops"] == ref["hops"], (fl, L)
+                if fl & jx.FLAG_VISITED_NONE:
+                    assert st["dist_evals"] == nof["evals"], (fl, L)   # Alg. 2 as printed
+                else:
+                    assert ref["evals"] <= st["dist_evals"] <= nof["evals"], (fl, L)
+        # a combination without an instance fails loudly instead of running something else
+        g.set_flags(jx.FLAG_TILED_LOADS | jx.FLAG_QPW_2)
+        with pytest.raises(jx.JxError):
+            g.beam_frontier(dev(q), 64)
+    finally:
+        g.set_flags(0)
+    assert {"beam_search_pair_kernel<0,4,2", "beam_search_kernel<0,4,2", "beam_search_kernel<0,8,1", "beam_search_kernel<0,2,4",
+            "beam_search_variant_kernel<0,4,2"} <= names, names
+
+
+@pytest.mark.parametrize("d", [96, 960, 1536])
+def test_ablation_variants_float32_bit_exact(jx, d):
+    """Tiled loads and wavefront teams on float32 vectors of the sizes the ablation measures.  Points on a dyadic grid
+    make every partial sum exact, so each variant must give the oracle's frontier bit for bit."""
+    n = 1200
+    x = datagen.dyadic_grid(n, d, seed=d, step=0.25, lim=2.0)
+    q = datagen.dyadic_grid(33, d, seed=d + 1, step=0.25, lim=2.0)
+    ix = oracle_index(x, 20, 40)
+    g = gpu_index_from_oracle(jx, x, ix, 20, 40)
+    variants = [0, jx.FLAG_TILED_LOADS, jx.FLAG_VISITED_NONE] + ([jx.FLAG_WAVES_2, jx.FLAG_WAVES_4, jx.FLAG_WAVES_4 | jx.FLAG_VISITED_NONE] if d >= 960 else [])
+    if d == 1536:
+        variants.remove(jx.FLAG_TILED_LOADS)   # no tiled instance for 384-chunk records
+    for L in (8, 64, 150):
+        ref = ix.search(q, 1, L, want_frontier=True)
+        for fl in variants:
+            g.set_flags(fl)
+            ids, dist, st = g.beam_frontier(dev(q), L, stats=True)
+            assert np.array_equal(u32(ids), ref["F_ids"]), (fl, L, st["beam_kernel"])
+            assert np.array_equal(dist.cpu().numpy().astype(np.float64), ref["F_dist"]), (fl, L)
+            assert st["hops"] == ref["hops"], (fl, L)
+            if fl & (jx.FLAG_WAVES_2 | jx.FLAG_WAVES_4):
+                assert st["beam_kernel"].startswith("beam_search_team_kernel<1,64,")
