@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0
 TRAFFIC_SOURCE = {2: "profiles/beam_search_u8_N1M_L96.md", 3: "profiles/build_search_f32_d960_4bit_N1M.md",
                   4: "profiles/build_search_f32_d1536_1bit_N1M.md", 5: "profiles/streaming_insert_u8_N5M.md"}
 
-SWEEP_SMALL = [16, 24, 32, 48, 64, 96, 128, 256]
+SWEEP_SMALL = [10, 12, 16, 20, 24, 32, 48, 64, 96, 128, 256]
 SWEEP_WIDE = [64, 96, 128, 192, 256, 384, 512]
 SPEC = {
     1: dict(u8=False, bits=0, sweep=[16, 24, 32, 48, 64], R=32, L_build=64, n=10_000, nq=1_000,
@@ -80,8 +80,9 @@ def recall_of(ids, gt_np, k):
     return hit / (k * len(a))
 
 
-def measure(wl, args, headline):
+def measure(wl, args, headline, cand=None):
     """Build workload `wl` on the GPU, pick L, time K search steps; returns (config, roofline, cpu_baseline, timing)."""
+    cand = cand or args.cand_mode
     import numpy as np
     import torch
 
@@ -93,10 +94,11 @@ def measure(wl, args, headline):
     gen_wl = sp.get("gen", wl)
     R, L_build, alpha, k = sp.get("R", 64), sp.get("L_build", 128), 1.2, 10
     d = datagen.spec(gen_wl)["d"]
-    n = (args.n if headline and args.n else 0) or sp.get("n", 1_000_000)
-    if not headline and args.others_scale != 1.0:
+    own = headline or wl == args.workload     # --n / --nq size the workload named on the command line
+    n = (args.n if own and args.n else 0) or sp.get("n", 1_000_000)
+    if not own and args.others_scale != 1.0:
         n = max(2000, int(n * args.others_scale))   # rehearsal of the default run at reduced sizes
-    nq = (args.nq if headline and args.nq else 0) or sp.get("nq", 10_000)
+    nq = (args.nq if own and args.nq else 0) or sp.get("nq", 10_000)
     steps, warmup = (args.steps, args.warmup) if headline else (5, 1)
     rabitq = sp["bits"] > 0
     query_bits = (args.query_bits if headline else 0) or (4 if sp["bits"] in (1, 2) else 8)
@@ -133,8 +135,16 @@ def measure(wl, args, headline):
     log(f"[bench] workload {wl}: generated {n}x{d} base + {nq} queries in {time.time() - t0:.1f}s")
 
     batch = 100_000 if wl == 5 else n
-    g = jx.Index(d, jx.U8 if sp["u8"] else (jx.F16 if f16 else jx.F32), R, L_build, alpha, capacity=n,
-                 max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"])
+    cand_mode = jx.CAND_VISITED if cand == "visited" else jx.CAND_FRONTIER
+    try:
+        g = jx.Index(d, jx.U8 if sp["u8"] else (jx.F16 if f16 else jx.F32), R, L_build, alpha, capacity=n,
+                     max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"], cand_mode=cand_mode)
+    except jx.JxError:
+        if cand_mode != jx.CAND_VISITED:
+            raise
+        cand_mode = jx.CAND_FRONTIER   # the expansion-list mode is not offered for this record shape
+        g = jx.Index(d, jx.U8 if sp["u8"] else (jx.F16 if f16 else jx.F32), R, L_build, alpha, capacity=n,
+                     max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"], cand_mode=cand_mode)
 
     stream_log = []
     torch.cuda.synchronize()
@@ -203,8 +213,10 @@ def measure(wl, args, headline):
     if forced_L:
         L_star = forced_L
     elif not L_star:
-        # the sweep ends below the target: time the beam width with the best recall and say so
-        L_star = max(sweep, key=lambda L: (sweep[L], -L))
+        # the sweep ends below the target: time the smallest beam width within half a point of the best recall
+        # (the ceiling) and say so
+        best = max(sweep.values())
+        L_star = min(L for L in sweep if sweep[L] >= best - 0.005)
     log(f"[bench] recall@10 sweep {sweep} -> L = {L_star}{'' if target_met or forced_L else ' (target not reached)'}")
 
     out = (torch.empty((nq, k), dtype=torch.int32, device="cuda"), torch.empty((nq, k), dtype=torch.float32, device="cuda"))
@@ -278,7 +290,8 @@ def measure(wl, args, headline):
         roofline["gather_ceiling"] = gather
 
     cfg = {"workload": f"workload {wl}: N={n} {generator_text(datagen, gen_wl)}; {sp['text']}{' (stored as binary16)' if f16 else ''}; "
-                       f"{nq} queries; Vamana R={R} L_build={L_build} alpha=1.2 built on the GPU, candidates = final frontier, batch_growth=0.25",
+                       f"{nq} queries; Vamana R={R} L_build={L_build} alpha=1.2 built on the GPU, robustPrune candidates = "
+                       f"{'expansion list V (Alg. 4 as printed)' if cand_mode == jx.CAND_VISITED else 'final frontier F (Alg. 2 output)'}, batch_growth=0.25",
            "L": L_star, "recall_at_10": round(rec, 4), "recall_target": args.recall, "recall_target_met": bool(rec >= args.recall),
            "recall_sweep": sweep, "build_inserts_per_s": round(n / t_build, 1), "build_s": round(t_build, 2)}
     if t_quant is not None:
@@ -394,6 +407,103 @@ def delete_leg(g, dq, gt_np, n, nq, k, L_star, mode, rerank, rec, frac):
     return out
 
 
+def ablate(args):
+    """Kernel-variant ablation (the paper's Sec. 6.5 "Ablation study" and its Block-Size, Tile Size and Load
+    microbenchmarks, on this kernel's own axes): every variant is a JX_FLAG_* switch of the library, returns the same
+    results as the default (the parity tests check that), and is timed here on the same index, one 10,000-query
+    beamSearch launch per cell, median of `--steps` launches (HIP events around the kernel)."""
+    import numpy as np
+    import torch
+
+    from paper_2601_07048_amd import datagen, jx
+
+    k, nq, reps = 10, 10_000, max(3, min(args.steps, 7))
+    scale = args.others_scale
+
+    def build(wl, bits=0):
+        d = datagen.spec(wl)["d"]
+        u8 = datagen.spec(wl)["dtype"] == np.uint8
+        n = max(2000, int(1_000_000 * scale))
+        dx = torch.empty((n, d), dtype=torch.uint8 if u8 else torch.float32, device="cuda")
+        step = 16 * datagen.CHUNK
+        for s0 in range(0, n, step):
+            m = min(step, n - s0)
+            dx[s0:s0 + m] = torch.from_numpy(datagen.base(wl, m, start=s0)).cuda()
+        dq = torch.from_numpy(datagen.queries(wl, nq)).cuda()
+        g = jx.Index(d, jx.U8 if u8 else jx.F32, 64, 128, 1.2, capacity=n, max_batch=max(n // 4 + 1, nq), quant_bits=bits)
+        g.insert(dx)
+        if bits:
+            g.quantize(bits, torch.from_numpy(datagen.rotation(wl)).cuda(), None, query_bits=8 if bits == 4 else 4)
+        gt = g.bruteforce(dq, k)[0].cpu().numpy()
+        torch.cuda.synchronize()
+        log(f"[ablate] workload {wl}: N={n} built")
+        return g, dq, gt, n
+
+    def cell(g, dq, gt, L, flags, mode=0, rerank=0):
+        g.set_flags(flags)
+        try:
+            ids, _ = g.search(dq, k, L, mode=mode, rerank=rerank)
+            ms = []
+            for _ in range(reps):
+                _, _, st = g.search(dq, k, L, mode=mode, rerank=rerank, stats=True)
+                ms.append(st["beam_ms"])
+        finally:
+            g.set_flags(0)
+        m = float(np.median(ms))
+        return {"L": L, "kernel": st["beam_kernel"], "beam_ms": round(m, 4), "queries_per_s_kernel": round(nq / m * 1e3, 1),
+                "dist_evals_per_query": round(st["dist_evals"] / nq, 1), "hops_per_query": round(st["hops"] / nq, 1),
+                "recall_at_10": round(recall_of(ids, gt, k), 4)}
+
+    table = []
+
+    def rows(tag, g, dq, gt, Ls, variants, mode=0, rerank=0):
+        for name, fl in variants:
+            for L in Ls:
+                table.append(dict({"workload": tag, "variant": name}, **cell(g, dq, gt, L, fl, mode, min(rerank, L))))
+            log(f"[ablate] {tag}: {name}: " + ", ".join(f"L={r['L']} {r['beam_ms']} ms" for r in table[-len(Ls):]))
+
+    F = jx
+    # --- 128-byte uint8 vectors (the paper's BigANN axis)
+    g, dq, gt, n = build(2)
+    rows(f"workload 2 (N={n}, d=128 uint8, exact)", g, dq, gt, (32, 96, 256), [
+        ("default: tag table, 4 lanes x 2 chunks, chunked loads, 1 query per workgroup, two expansions per round where it applies", 0),
+        ("one expansion per round", F.FLAG_NO_PAIR),
+        ("visited: direct-mapped table of full ids", F.FLAG_VISITED_IDS | F.FLAG_NO_PAIR),
+        ("visited: none (Alg. 2 as printed)", F.FLAG_VISITED_NONE),
+        ("lanes per vector: 8 x 1 chunk", F.FLAG_LANES_WIDE | F.FLAG_NO_PAIR),
+        ("lanes per vector: 2 x 4 chunks", F.FLAG_LANES_NARROW),
+        ("tiled (4-byte strided) loads", F.FLAG_TILED_LOADS),
+        ("2 queries per workgroup", F.FLAG_QPW_2),
+        ("4 queries per workgroup", F.FLAG_QPW_4)])
+    del g
+    torch.cuda.empty_cache()
+    # --- 3,840-byte float32 vectors (the paper's GIST axis), exact and on 4-bit codes
+    g, dq, gt, n = build(3, bits=4)
+    rows(f"workload 3 (N={n}, d=960 float32, exact)", g, dq, gt, (32, 128), [
+        ("default: 64 lanes x 4 chunks, chunked loads, 1 wavefront per query", 0),
+        ("visited: none (Alg. 2 as printed)", F.FLAG_VISITED_NONE),
+        ("tiled (4-byte strided) loads", F.FLAG_TILED_LOADS),
+        ("2 wavefronts per query", F.FLAG_WAVES_2),
+        ("4 wavefronts per query", F.FLAG_WAVES_4)])
+    rows(f"workload 3 (N={n}, d=960 float32, 4-bit RaBitQ codes + re-rank 40)", g, dq, gt, (32, 128), [
+        ("default: 16 lanes x 2 chunks", 0), ("32 lanes x 1 chunk", F.FLAG_LANES_WIDE), ("visited: none (Alg. 2 as printed)", F.FLAG_VISITED_NONE)],
+        mode=jx.RABITQ, rerank=40)
+    del g
+    torch.cuda.empty_cache()
+    # --- 6,144-byte float32 vectors: wavefronts per query
+    g, dq, gt, n = build(4, bits=1)
+    rows(f"workload 4 (N={n}, d=1536 float32, exact)", g, dq, gt, (32, 128), [
+        ("default: 64 lanes x 6 chunks, 1 wavefront per query", 0),
+        ("2 wavefronts per query", F.FLAG_WAVES_2),
+        ("4 wavefronts per query", F.FLAG_WAVES_4)])
+    rows(f"workload 4 (N={n}, d=1536 float32, 1-bit RaBitQ codes + re-rank 40)", g, dq, gt, (32, 128), [
+        ("default: 4 lanes x 3 code chunks, meta chunk apart", 0), ("16 lanes x 1 chunk", F.FLAG_LANES_WIDE),
+        ("visited: none (Alg. 2 as printed)", F.FLAG_VISITED_NONE)], mode=jx.RABITQ, rerank=40)
+    del g
+    return {"metric": "beamSearch kernel-variant ablation: kernel time per 10,000-query launch", "unit": "ms", "n_gpus": 1,
+            "launches_per_cell": reps, "data": "synthetic", "table": table}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -414,6 +524,9 @@ def main():
                          "rates, queries/s and recall before / after (Sec. 4.6, Table 2 of the paper)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
+    ap.add_argument("--cand-mode", choices=["frontier", "visited"], default="visited",
+                    help="what beamSearch hands to robustPrune during the build: the final frontier F (Alg. 2's output) or the "
+                         "expansion list V (Alg. 4 as printed)")
     ap.add_argument("--no-others", action="store_true", help="skip the brief measurements of the other configurations")
     ap.add_argument("--others", type=str, default="1,3,4,5", help="configurations measured briefly after the headline (default run only)")
     ap.add_argument("--others-scale", type=float, default=1.0, help="scale the sizes of the other configurations (rehearsals and tests)")
@@ -431,6 +544,14 @@ def main():
         return
     with_others = args.workload == 2 and not (args.no_others or args.L or args.bits or args.f16 or args.delete_frac)
     cfg, roofline, cpu, tm = measure(args.workload, args, headline=True)
+    if with_others and args.cand_mode == "visited":
+        # the same headline workload on the graph built from final frontiers (the candidate set of the first round's
+        # figures): shows what the choice of robustPrune's candidate set is worth
+        c, r, _, t = measure(args.workload, args, headline=False, cand="frontier")
+        cfg["graph_from_final_frontier"] = {"workload": c["workload"], "L": c["L"], "recall_at_10": c["recall_at_10"],
+                                            "recall_sweep": c["recall_sweep"], "queries_per_s": t["value"], "ms_per_step": t["ms_per_step"],
+                                            "steps": t["steps"], "build_inserts_per_s": c["build_inserts_per_s"],
+                                            "roofline": {key: r[key] for key in ("kernel", "bytes_per_launch", "kernel_ms", "achieved", "frac")}}
     if with_others:
         others = []
         for wl in [int(t) for t in args.others.split(",") if t]:

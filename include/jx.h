@@ -46,7 +46,11 @@ extern "C" {
 #define JX_RABITQ 1 /* RaBitQ-estimated distances on the codes (needs jx_quantize) */
 
 /* what beamSearch hands to robustPrune during insertion */
-#define JX_CAND_FRONTIER 0 /* the final frontier F (Alg. 2's output) */
+#define JX_CAND_FRONTIER 0 /* the final frontier F (Alg. 2's output): at most L_build candidates */
+#define JX_CAND_VISITED 1  /* the expansion list V (Alg. 1's output, which Alg. 4 step 2 prunes): every vertex the
+                              search expanded, F included -- the first min(512, 4 L_build rounded up to a power of
+                              two) of them in expansion order.  Offered for L_build <= 128 on uint8 vectors of at
+                              most 128 bytes and float32 vectors of at most 512 or of 2,049..6,144 bytes */
 
 /* rule that picks the m-bit code for m > 1 (Sec. 5.1 says only "simple scalar
  * quantization") */
@@ -108,7 +112,7 @@ typedef struct {
     int32_t R;         /* maximum out-degree (Sec. 3.1), 1..JX_MAX_R */
     int32_t L_build;   /* beam width used by insertion (Alg. 4), R.. JX_MAX_L is not required; 1..JX_MAX_L */
     float alpha;       /* robustPrune factor, applied to squared distances (Alg. 3) */
-    int32_t cand_mode; /* JX_CAND_FRONTIER */
+    int32_t cand_mode; /* JX_CAND_FRONTIER | JX_CAND_VISITED */
     int64_t capacity;  /* maximum number of points; rows are preallocated */
     int64_t max_batch; /* largest number of points linked by one internal batch
                           and largest number of queries processed at once

@@ -526,8 +526,14 @@ static void insert_subbatch(orc_index *x, const uint32_t *ids, int64_t B, int nt
     const int R = x->R, L = x->L_build, d = x->d;
     const size_t vs = (size_t)d * esize(x->dtype);
     const int64_t nsnap = x->capacity; /* bitmap covers every possible id */
+    /* Expansion-list mode (Alg. 4 step 2 prunes V, the output of Alg. 1): the list keeps the first
+       min(512, 4 L rounded up to a power of two) expanded vertices in expansion order (a search expands about
+       1.2 L to 1.5 L vertices; the bound fixes the buffer of the GPU implementation, which uses the same one). */
     int V_cap = 0;
-    if (x->cand_mode == ORC_CAND_VISITED) V_cap = 1 << 16;
+    if (x->cand_mode == ORC_CAND_VISITED) {
+        V_cap = 64;
+        while (V_cap < 4 * L && V_cap < 512) V_cap *= 2;
+    }
     uint32_t *newrows = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)B * R);
     memset(newrows, 0xFF, sizeof(uint32_t) * (size_t)B * R);
     orc_edge *edges = (orc_edge *)malloc(sizeof(orc_edge) * (size_t)B * R + 16);
@@ -564,6 +570,7 @@ static void insert_subbatch(orc_index *x, const uint32_t *ids, int64_t B, int nt
             } else {
                 int m = nV < V_cap ? nV : V_cap;
                 for (int i = 0; i < m; i++) {
+                    if (x->deleted && x->deleted[V[i].id]) continue; /* Sec. 4.6: never an output, so never a neighbour */
                     cid[nc] = V[i].id;
                     cd[nc] = V[i].d;
                     nc++;

@@ -132,9 +132,59 @@ __device__ __forceinline__ void frontier_merge(uint64_t (&fk)[NREG], uint64_t* f
     worst = fr[L - 1] | 1ull;
 }
 
+// The expansion list of one query (Alg. 1's set V; what Alg. 4 hands to robustPrune), kept in LDS in expansion order:
+// sort its first n entries by key = (distance, id) -- a bitonic network over cap (a power of two) slots, padded with
+// the largest key, four compare-exchanges per lane and stage at cap = 512 -- then write the ids and distances of the
+// entries that are not logically deleted to out_ids / out_dist [qi][out_k], padded with JX_NONE / +inf.
+template <int KIND>
+__device__ __forceinline__ void write_visited(const BeamArgs& a, const int64_t qi, uint64_t* vis, const int n, const int lane) {
+    const int cap = a.vis_cap;
+    for (int i = n + lane; i < cap; i += 64) vis[i] = JX_EMPTY_KEY;
+    wave_sync();
+    for (int k = 2; k <= cap; k <<= 1) {
+        for (int j = k >> 1; j >= 1; j >>= 1) {
+            for (int p = lane; p < cap / 2; p += 64) {
+                const int i = ((p & ~(j - 1)) << 1) | (p & (j - 1));  // p with a zero bit inserted at bit log2(j)
+                const int m = i | j;
+                const uint64_t x = vis[i], y = vis[m];
+                const bool up = (i & k) == 0;
+                if ((x > y) == up) {
+                    vis[i] = y;
+                    vis[m] = x;
+                }
+            }
+            wave_sync();
+        }
+    }
+    int base_pos = 0;
+    for (int p0 = 0; p0 < cap; p0 += 64) {
+        const uint64_t k = vis[p0 + lane];
+        const uint32_t id = key_id(k);
+        bool keep = p0 + lane < n;
+        if (keep && a.deleted) keep = a.deleted[id] == 0;
+        const uint64_t km = ballot(keep);
+        const int pos = base_pos + prefix_count(km);
+        if (keep && pos < a.out_k) {
+            const uint32_t dc = key_dist(k);
+            float d;
+            if constexpr (KIND == K_U8)
+                d = (float)dc;
+            else
+                d = ordered_to_f32(dc);
+            a.out_ids[qi * a.out_k + pos] = id;
+            a.out_dist[qi * a.out_k + pos] = d;
+        }
+        base_pos += __builtin_popcountll(km);
+    }
+    for (int p = base_pos + lane; p < a.out_k; p += 64) {
+        a.out_ids[qi * a.out_k + p] = JX_NONE_ID;
+        a.out_dist[qi * a.out_k + p] = __builtin_inff();
+    }
+}
+
 // One query per wavefront, WPB wavefronts (queries) per workgroup; TILED selects the element-strided loads of the
-// load ablation (jx_distance.h).
-template <int KIND, int T, int CPL, int NREG, int QB, int WPB, bool TILED>
+// load ablation (jx_distance.h); VIS returns the expansion list instead of the frontier (BeamArgs::vis_cap).
+template <int KIND, int T, int CPL, int NREG, int QB, int WPB, bool TILED, bool VIS = false>
 __device__ __forceinline__ void beam_search_body(const BeamArgs& a) {
     constexpr int G = 64 / T;
     constexpr int UMAX = (KIND == K_RQ1) ? JX_UMAX_RQ1 : ((KIND == K_U8) ? JX_UMAX_EXACT : ((KIND == K_RQ4) ? JX_UMAX_RQ4 : 8));  // 16-byte loads in flight per lane (the 1-bit path keeps its bit planes in registers)
@@ -151,12 +201,13 @@ __device__ __forceinline__ void beam_search_body(const BeamArgs& a) {
     const int H = a.hash_slots;
     const int tag_bits = a.tag_bits;  // > 0: 16-bit entries (slot and tag together name the id exactly)
     const uint32_t id_mask = tag_bits ? ((1u << (tag_bits + 30 - __builtin_clz((uint32_t)H))) - 1u) : 0u;  // H / 2 sets
-    const size_t per_wave = (size_t)FCAP * 8 + 64 * 8 + 64 * 4 + (size_t)H * (tag_bits ? 2 : 4);
+    const size_t per_wave = (size_t)FCAP * 8 + 64 * 8 + 64 * 4 + (size_t)H * (tag_bits ? 2 : 4) + (VIS ? (size_t)a.vis_cap * 8 : 0);
     unsigned char* my = smem + per_wave * wave;
     uint64_t* fr = reinterpret_cast<uint64_t*>(my);
     uint64_t* cand_key = fr + FCAP;
     uint32_t* cand_id = reinterpret_cast<uint32_t*>(cand_key + 64);
     uint32_t* tab = cand_id + 64;
+    uint64_t* vis = reinterpret_cast<uint64_t*>(my + per_wave) - (VIS ? a.vis_cap : 0);  // behind the table (8-byte aligned)
 
     for (int i = lane; i < (tag_bits ? H / 2 : H); i += 64) tab[i] = JX_NONE_ID;
     for (int i = lane; i < FCAP; i += 64) fr[i] = JX_EMPTY_KEY;
@@ -210,8 +261,12 @@ __device__ __forceinline__ void beam_search_body(const BeamArgs& a) {
 #pragma unroll
         for (int r = 0; r < NREG; r++) {
             if (r == sel_r) {
-                u = key_id(readlane64(fk[r], sel_lane));
+                const uint64_t ukey = readlane64(fk[r], sel_lane);
+                u = key_id(ukey);
                 if (lane == sel_lane) fk[r] |= 1ull;
+                if constexpr (VIS) {
+                    if (lane == 0 && hops < (uint32_t)a.vis_cap) vis[hops] = ukey | 1ull;
+                }
             }
         }
         hops++;
@@ -265,7 +320,15 @@ __device__ __forceinline__ void beam_search_body(const BeamArgs& a) {
         }
     }
 
-    write_results<KIND, NREG>(a, qi, fk, count, lane, hops, evals);
+    if constexpr (VIS) {
+        write_visited<KIND>(a, qi, vis, (int)(hops < (uint32_t)a.vis_cap ? hops : (uint32_t)a.vis_cap), lane);
+        if (a.stats && lane == 0) {
+            atomicAdd(&a.stats[0], (unsigned long long)hops);
+            atomicAdd(&a.stats[1], (unsigned long long)evals);
+        }
+    } else {
+        write_results<KIND, NREG>(a, qi, fk, count, lane, hops, evals);
+    }
 }
 
 template <int KIND, int T, int CPL, int NREG, int QB>
@@ -279,6 +342,12 @@ template <int KIND, int T, int CPL, int NREG, int WPB, bool TILED>
 __global__ void __launch_bounds__(WPB * 64) __attribute__((amdgpu_waves_per_eu((NREG <= 2 && CPL <= 2) ? JX_WPE_EXACT : 1, 8)))
 beam_search_variant_kernel(BeamArgs a) {
     beam_search_body<KIND, T, CPL, NREG, 0, WPB, TILED>(a);
+}
+
+// Insertion with the expansion list as candidate set (exact distances; see BeamArgs::vis_cap)
+template <int KIND, int T, int CPL, int NREG>
+__global__ void __launch_bounds__(64) beam_search_visited_kernel(BeamArgs a) {
+    beam_search_body<KIND, T, CPL, NREG, 0, 1, false, true>(a);
 }
 
 // ------------------------------------------------------------------ two expansions per round

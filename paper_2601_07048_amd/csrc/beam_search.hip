@@ -134,6 +134,7 @@ static hipError_t launch_shape(const BeamArgs& a, hipStream_t st, char* name) {
 hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st, char* kernel_name) {
     if (kernel_name) kernel_name[0] = 0;
     if (a.nq <= 0) return hipSuccess;
+    if (a.vis_cap) return launch_beam_visited(kind, a, st, kernel_name);
     if (a.flags & (JX_FLAG_TILED_LOADS | JX_FLAG_QPW_2 | JX_FLAG_QPW_4 | JX_FLAG_WAVES_2 | JX_FLAG_WAVES_4))
         return launch_beam_variant(kind, a, st, kernel_name);
     switch (kind) {

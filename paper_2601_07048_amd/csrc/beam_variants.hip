@@ -178,6 +178,40 @@ static hipError_t launch_team(const BeamArgs& a, hipStream_t st, char* name) {
     return hipErrorInvalidValue;
 }
 
+// ------------------------------------------------------------------ expansion list as output (JX_CAND_VISITED)
+
+template <int KIND, int T, int CPL>
+static hipError_t launch_visited_shape(const BeamArgs& a, hipStream_t st, char* name) {
+    const int nreg = (a.L + 63) / 64;
+    const size_t tail = 64 * 8 + 64 * 4 + (size_t)a.hash_slots * (a.tag_bits ? 2 : 4) + (size_t)a.vis_cap * 8;
+    if (name) snprintf(name, 96, "beam_search_visited_kernel<%d,%d,%d,%d>", KIND, T, CPL, nreg <= 1 ? 1 : 2);
+    if (nreg <= 1)
+        hipLaunchKernelGGL((beam_search_visited_kernel<KIND, T, CPL, 1>), dim3((unsigned)a.nq), dim3(64), mirror_entries<1>() * 8 + tail, st, a);
+    else
+        hipLaunchKernelGGL((beam_search_visited_kernel<KIND, T, CPL, 2>), dim3((unsigned)a.nq), dim3(64), mirror_entries<2>() * 8 + tail, st, a);
+    return hipGetLastError();
+}
+
+// Offered for the record shapes of the five workload configurations -- uint8 vectors of at most 128 bytes, float32
+// vectors of at most 512 bytes or of 2,049 to 6,144 bytes -- with L_build <= 128.
+bool visited_list_offered(int kind, int nch, int L, int R) {
+    (void)R;
+    if (L > 128) return false;
+    if (kind == K_U8) return nch <= 8;
+    if (kind == K_F32) return nch <= 32 || (nch > 128 && nch <= 384);
+    return false;
+}
+
+hipError_t launch_beam_visited(int kind, const BeamArgs& a, hipStream_t st, char* kernel_name) {
+    const int nch = a.ds.nch;
+    if (!visited_list_offered(kind, nch, a.L, a.R) || a.vis_cap < 64 || a.vis_cap > 512 || (a.vis_cap & (a.vis_cap - 1)))
+        return hipErrorInvalidValue;
+    if (kind == K_U8) return launch_visited_shape<K_U8, 4, 2>(a, st, kernel_name);
+    if (nch <= 32) return launch_visited_shape<K_F32, 16, 2>(a, st, kernel_name);
+    if (nch <= 256) return launch_visited_shape<K_F32, 64, 4>(a, st, kernel_name);
+    return launch_visited_shape<K_F32, 64, 6>(a, st, kernel_name);
+}
+
 // Instances exist for the shapes the ablation measures: 128-byte uint8 vectors, float32 vectors of at most 512 bytes
 // (tiled loads) and of 2,049 to 6,144 bytes (tiled loads, wavefront teams), beam widths up to 256.  Anything else:
 // hipErrorInvalidValue, which the C ABI reports as a failed launch.

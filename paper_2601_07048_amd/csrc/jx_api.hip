@@ -59,7 +59,9 @@ int check_params(const jx_params* p) {
     if (p->R < 1 || p->R > JX_MAX_R) return fail(JX_EINVAL, "R out of range");
     if (p->L_build < 1 || p->L_build > JX_MAX_L) return fail(JX_EINVAL, "L_build out of range");
     if (!(p->alpha >= 1.0f)) return fail(JX_EINVAL, "alpha must be >= 1");
-    if (p->cand_mode != JX_CAND_FRONTIER) return fail(JX_EINVAL, "only JX_CAND_FRONTIER is supported");
+    if (p->cand_mode != JX_CAND_FRONTIER && p->cand_mode != JX_CAND_VISITED) return fail(JX_EINVAL, "unknown cand_mode");
+    if (p->cand_mode == JX_CAND_VISITED && !jx::visited_list_offered(exact_kind(p->dtype), vb / 16, p->L_build, p->R))
+        return fail(JX_EINVAL, "JX_CAND_VISITED is offered for L_build <= 128 on uint8 vectors of at most 128 bytes and float32 vectors of at most 512 or of 2049..6144 bytes");
     if (p->capacity < 1 || p->capacity > 0x7FFFFFFELL) return fail(JX_EINVAL, "capacity out of range");
     if (p->max_batch < 1) return fail(JX_EINVAL, "max_batch must be positive");
     if ((int64_t)p->max_batch * p->R >= 0x7FFFFFFFLL) return fail(JX_EINVAL, "max_batch * R must stay below 2^31");
@@ -76,18 +78,22 @@ struct InsertWork {
     int64_t cand_ids, cand_dist, keys0, keys1, vals0, vals1, heads, dead, table, counters, partial, mean, dist, total;
 };
 
+// candidates per new point that beamSearch hands to robustPrune: the frontier, or the expansion list
+int cand_len(const jx_params* p) { return p->cand_mode == JX_CAND_VISITED ? jx::visited_cap(p->L_build) : p->L_build; }
+
 int64_t insert_work(const jx_params* p, int64_t B, InsertWork* w) {
     int64_t off = 0;
     const int64_t E = B * p->R;
+    const int64_t Lc = cand_len(p);
     auto take = [&](int64_t bytes) { int64_t o = off; off += align256(bytes); return o; };
-    w->cand_ids = take(B * p->L_build * 4);
-    w->cand_dist = take(B * p->L_build * 4);
+    w->cand_ids = take(B * Lc * 4);
+    w->cand_dist = take(B * Lc * 4);
     w->keys0 = take(E * 8);
     w->keys1 = take(E * 8);
     w->vals0 = take(E * 4);
     w->vals1 = take(E * 4);
     w->heads = take(E * 4);
-    w->dead = take(B * (p->R > p->L_build ? p->R : p->L_build));
+    w->dead = take(B * (p->R > Lc ? p->R : Lc));
     w->table = take((256 * (E / 4096 + 2) + 256) * 4);  // radix sort: [digit][tile] counters and one total per digit
     w->counters = take(256);
     w->partial = take((int64_t)512 * p->dim * 8);
@@ -642,9 +648,11 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     b.entry = idx->entry;
     visited_table_for(idx->flags, p.L_build, n_after, &b.hash_slots, &b.tag_bits);
     b.flags = idx->flags;
+    const int Lc = cand_len(&p);
     b.out_ids = (uint32_t*)(W + w.cand_ids);
     b.out_dist = (float*)(W + w.cand_dist);
-    b.out_k = p.L_build;
+    b.out_k = Lc;
+    b.vis_cap = p.cand_mode == JX_CAND_VISITED ? Lc : 0;
     b.stats = nullptr;
     b.deleted = idx->any_delete ? idx->d_deleted : nullptr;  // new points never link to deleted vertices
     JX_HIP(jx::launch_beam_search(exact_kind(p.dtype), 0, b, st));
@@ -654,7 +662,7 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     a.ds = ds;
     a.adj = idx->d_adj;
     a.R = p.R;
-    a.L = p.L_build;
+    a.L = Lc;
     a.alpha = p.alpha;
     a.B = B;
     a.id_base = id_base;

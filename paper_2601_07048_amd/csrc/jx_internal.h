@@ -43,11 +43,23 @@ struct BeamArgs {
     unsigned long long* stats;  // {hops, dist_evals} or NULL
     const uint8_t* deleted;     // [N] 1 = logically deleted (never returned), or NULL
     uint32_t flags;             // JX_FLAG_* switches that select a kernel variant
+    int vis_cap;                // > 0 (a power of two <= 512): instead of the frontier, out_ids / out_dist [nq][vis_cap]
+                                // receive the expanded vertices (Alg. 1's set V), the first vis_cap of them in
+                                // expansion order, sorted by (distance, id)
 };
 // kernel_name (may be NULL): receives the name of the instance that was launched, at most 96 bytes
 hipError_t launch_beam_search(int kind, int qbits, const BeamArgs& a, hipStream_t st, char* kernel_name = nullptr);
 // ablation instances (JX_FLAG_TILED_LOADS, JX_FLAG_QPW_*, JX_FLAG_WAVES_*); hipErrorInvalidValue where none exists
 hipError_t launch_beam_variant(int kind, const BeamArgs& a, hipStream_t st, char* kernel_name);
+// beamSearch that returns the expansion list (BeamArgs::vis_cap); instances: see visited_list_offered()
+hipError_t launch_beam_visited(int kind, const BeamArgs& a, hipStream_t st, char* kernel_name);
+bool visited_list_offered(int kind, int nch, int L, int R);
+// length of the expansion list kept per query for beam width L: 4 L rounded up to a power of two, 64..512
+inline int visited_cap(int L) {
+    int c = 64;
+    while (c < 4 * L && c < 512) c *= 2;
+    return c;
+}
 
 // ---- batch insertion -------------------------------------------------------
 struct InsertArgs {

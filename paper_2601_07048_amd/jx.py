@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("JX_LIB", os.path.join(_HERE, "libjx.so"))
 NONE = 0xFFFFFFFF
 U8, F32, F16 = 0, 1, 2
 EXACT, RABITQ = 0, 1
-CAND_FRONTIER = 0
+CAND_FRONTIER, CAND_VISITED = 0, 1
 RULE_MAXCOS, RULE_MAXABS, RULE_DEFAULT = 0, 1, -1
 # jx_params.flags / jx_set_flags (see include/jx.h)
 FLAG_NO_PAIR, FLAG_NO_INCR_PRUNE, FLAG_NO_GRAM, FLAG_GRAM_U8 = 1 << 0, 1 << 1, 1 << 2, 1 << 3

@@ -18,12 +18,12 @@ def jx():
     return m
 
 
-def _build_both(jx, x, R, L, calls=None, alpha=1.2, growth=0.25):
+def _build_both(jx, x, R, L, calls=None, alpha=1.2, growth=0.25, cand_mode=0):
     n, d = x.shape
     dt = jx.U8 if x.dtype == np.uint8 else jx.F32
     calls = calls or [n]
-    ref = oracle.Index(d, x.dtype, R, L, alpha, n, batch_growth=growth)
-    g = jx.Index(d, dt, R, L, alpha, capacity=n, max_batch=n, batch_growth=growth)
+    ref = oracle.Index(d, x.dtype, R, L, alpha, n, batch_growth=growth, cand_mode=cand_mode)
+    g = jx.Index(d, dt, R, L, alpha, capacity=n, max_batch=n, batch_growth=growth, cand_mode=cand_mode)
     pos = 0
     for c in calls:
         ref.insert(x[pos:pos + c])
@@ -242,3 +242,76 @@ def test_incremental_prune_switched_off_gives_the_same_graph(jx):
         tables.append(g.export_graph()[0])
         del g
     assert torch.equal(tables[0], tables[1])
+
+
+@pytest.mark.parametrize("n,d,R,L,calls,growth", [
+    (700, 32, 8, 16, None, 0.25),            # expansion list of 64
+    (3000, 128, 32, 64, None, 0.25),         # 256
+    (3000, 128, 32, 64, [1, 1, 2, 996, 2000], 0.5),
+    (2500, 128, 64, 128, [1500, 1000], 0.25),  # 512: the benchmark's R and L_build
+    (4000, 64, 16, 100, [1500, 2500], 1.0),
+    (3000, 128, 12, 5, None, 0.25),          # the list is cut at 64 expansions of a narrow beam
+])
+def test_insert_visited_candidates_u8_graph_bit_exact(jx, n, d, R, L, calls, growth):
+    """JX_CAND_VISITED: robustPrune receives the expansion list V of Alg. 1 (what Alg. 4 prunes) instead of the final
+    frontier.  Whole adjacency tables against the oracle in the same mode, and they differ from the frontier mode's."""
+    x = random_data(n, d, np.uint8, seed=n + R + 1)
+    ref, g = _build_both(jx, x, R, L, calls, growth=growth, cand_mode=jx.CAND_VISITED)
+    oadj, odeg, adj, deg = _graphs(ref, g)
+    assert g.size() == (n, ref.entry)
+    bad = np.nonzero((adj != oadj).any(axis=1))[0]
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+    if n >= 2500:
+        ref_f = oracle.Index(d, np.uint8, R, L, 1.2, n, batch_growth=growth)
+        pos = 0
+        for c in (calls or [n]):
+            ref_f.insert(x[pos:pos + c])
+            pos += c
+        assert not np.array_equal(ref_f.graph()[0], oadj)
+
+
+def test_insert_visited_candidates_with_deletions(jx):
+    n = 3000
+    x = random_data(n, 128, np.uint8, seed=99)
+    ref = oracle.Index(128, np.uint8, 24, 48, 1.2, n, cand_mode=oracle.CAND_VISITED)
+    g = jx.Index(128, jx.U8, 24, 48, 1.2, capacity=n, max_batch=n, cand_mode=jx.CAND_VISITED)
+    ref.insert(x[:2000])
+    g.insert(dev(x[:2000]))
+    dele = np.random.default_rng(7).choice(2000, 600, replace=False).astype(np.uint32)
+    ref.delete(dele)
+    g.delete(dev(dele))
+    ref.insert(x[2000:])
+    g.insert(dev(x[2000:]))
+    oadj, odeg, adj, deg = _graphs(ref, g)
+    assert np.array_equal(adj, oadj)
+    assert not np.isin(adj[2000:][adj[2000:] != 0xFFFFFFFF], dele).any()
+
+
+def test_insert_visited_candidates_float32(jx):
+    """Dyadic-grid float32 data (exact partial sums): bit parity in the expansion-list mode, at d = 64 and d = 960."""
+    for n, d, R, L in ((3000, 64, 24, 48), (1200, 960, 16, 32)):
+        x = datagen.dyadic_grid(n, d, seed=13 + d, step=0.25 if d > 64 else 0.125, lim=2.0 if d > 64 else 4.0)
+        ref, g = _build_both(jx, x, R, L, [n // 3, n - n // 3], cand_mode=jx.CAND_VISITED)
+        oadj, odeg, adj, deg = _graphs(ref, g)
+        assert g.size() == (n, ref.entry)
+        assert np.array_equal(adj, oadj), d
+
+
+def test_workload1_frontier_vs_visited_candidates(jx):
+    """Workload 1 (N = 10,000, R = 32, L_build = 64, seeded insertion order), both candidate modes on the GPU and in
+    the oracle: recall@10 at L = 64 agrees with the oracle's within 0.002 in each mode; the difference between the
+    modes is printed (Alg. 4 step 2 prunes V, Alg. 2 returns F)."""
+    n = 10_000
+    x = datagen.base(1, n)[datagen.insertion_order(1, n)]
+    q = datagen.queries(1, 1000)
+    gt, _ = oracle.bruteforce(x, q, 10)
+    out = {}
+    for name, mode in (("frontier", 0), ("visited", 1)):
+        ref, g = _build_both(jx, x, 32, 64, None, cand_mode=mode)
+        for L in (32, 64):
+            r_o = oracle.recall_at_k(ref.search(q, 10, L)["ids"], gt)
+            r_g = oracle.recall_at_k(u32(g.search(dev(q), 10, L)[0]), gt)
+            assert abs(r_o - r_g) <= 0.002, (name, L, r_o, r_g)
+            out[(name, L)] = (round(r_g, 4), round(r_o, 4), round(float(u32(g.export_graph()[1]).mean()), 1))
+    print("workload 1, recall@10 (GPU, oracle, mean degree):", out, flush=True)
+    assert out[("visited", 64)][0] >= 0.95 and out[("frontier", 64)][0] >= 0.95

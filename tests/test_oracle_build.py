@@ -189,7 +189,7 @@ def test_workload1_recall_target():
 # internal batches of min(remaining, max(1, floor(batch_growth * linked))) points; these pins fix what the
 # batching may and may not change.
 
-def _sequential_vamana(x, R, L, alpha, entry):
+def _sequential_vamana(x, R, L, alpha, entry, v_cap=0):
     """One-at-a-time insertion written out from Sec. 3.1 / Alg. 3-4 with batches of one, from the separately pinned
     primitives (beamSearch, robustPrune, distance): search from the entry point on the graph as it stands, prune the
     frontier into the new row, then add the reverse edge to every kept neighbour -- appended while the row has room,
@@ -200,8 +200,11 @@ def _sequential_vamana(x, R, L, alpha, entry):
     for p in range(n):
         if p == entry:
             continue
-        res = oracle.beam_search(adj, x, x[p], L, entry)
-        row = oracle.robust_prune(p, res["F_ids"], res["F_dist"], x, R, alpha)
+        res = oracle.beam_search(adj, x, x[p], L, entry, V_cap=v_cap)
+        if v_cap:   # Alg. 4 step 2 as printed: prune the expansion list V (its first v_cap entries)
+            row = oracle.robust_prune(p, res["V_ids"], res["V_dist"], x, R, alpha)
+        else:       # Alg. 2's output: the final frontier
+            row = oracle.robust_prune(p, res["F_ids"], res["F_dist"], x, R, alpha)
         adj[p, : len(row)] = row
         deg[p] = len(row)
         for v in row.tolist():
@@ -241,6 +244,12 @@ def test_all_ones_schedule_is_sequential_insertion(dtype):
     iy = oracle.Index(d, dtype, R, L, 1.2, n, batch_growth=1.0)
     iy.insert(x)
     assert not np.array_equal(iy.graph()[0], want)
+    # expansion-list candidates (the list holds min(512, 4 L rounded up to a power of two) = 64 entries for L = 12)
+    iv = oracle.Index(d, dtype, R, L, 1.2, n, batch_growth=0.0, cand_mode=oracle.CAND_VISITED)
+    iv.insert(x)
+    want_v = _sequential_vamana(x, R, L, 1.2, iv.entry, v_cap=64)
+    assert np.array_equal(iv.graph()[0], want_v)
+    assert not np.array_equal(want_v, want)
 
 
 def _edge_set(adj):
