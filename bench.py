@@ -138,13 +138,13 @@ def measure(wl, args, headline, cand=None):
     cand_mode = jx.CAND_VISITED if cand == "visited" else jx.CAND_FRONTIER
     try:
         g = jx.Index(d, jx.U8 if sp["u8"] else (jx.F16 if f16 else jx.F32), R, L_build, alpha, capacity=n,
-                     max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"], cand_mode=cand_mode)
+                     max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"], cand_mode=cand_mode, flags=args.flags)
     except jx.JxError:
         if cand_mode != jx.CAND_VISITED:
             raise
         cand_mode = jx.CAND_FRONTIER   # the expansion-list mode is not offered for this record shape
         g = jx.Index(d, jx.U8 if sp["u8"] else (jx.F16 if f16 else jx.F32), R, L_build, alpha, capacity=n,
-                     max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"], cand_mode=cand_mode)
+                     max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"], cand_mode=cand_mode, flags=args.flags)
 
     stream_log = []
     torch.cuda.synchronize()
@@ -227,12 +227,17 @@ def measure(wl, args, headline, cand=None):
         for _ in range(warmup):
             g.search(dq, k, L, mode=mode, rerank=rr, out=out)
         torch.cuda.synchronize()
-        # timed region 1: K whole jx_search calls back to back -> value
+        # timed region 1: K whole jx_search calls back to back -> value; two HIP events on the launch stream (torch's
+        # current stream is the one the binding hands to the library) bracket the same region
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         t1 = time.perf_counter()
+        ev[0].record()
         for _ in range(steps):
             g.search(dq, k, L, mode=mode, rerank=rr, out=out)
+        ev[1].record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t1
+        region_ms = ev[0].elapsed_time(ev[1]) / steps
         # timed region 2: the same K calls, each with the library's HIP events around every stage (recorded on the
         # launch stream; the call then synchronises) -> duration of the beamSearch kernel alone
         stage = {"rotate_ms": 0.0, "prep_ms": 0.0, "beam_ms": 0.0, "rerank_ms": 0.0}
@@ -240,10 +245,15 @@ def measure(wl, args, headline, cand=None):
             _, _, st = g.search(dq, k, L, mode=mode, rerank=rr, out=out, stats=True)
             for key in stage:
                 stage[key] += st[key] / steps
-        return rec, wall * 1e3 / steps, nq * steps / wall, stage, st
+        return rec, wall * 1e3 / steps, nq * steps / wall, stage, dict(st, region_ms=region_ms)
 
     rec, ms_per_step, qps, stage, st = timed(L_star, rerank)
-    beam_ms = stage["beam_ms"]
+    # duration of one beamSearch launch.  Exact search: a step is that one kernel, so the HIP events around the K
+    # back-to-back steps of the timed region give its average launch duration (start to start, launch gap included).
+    # Code search: a step is four kernels; the beamSearch share comes from the library's own events around each stage
+    # in the second loop.  The isolated figure (an event pair and a synchronisation per launch) is reported beside it:
+    # for sub-millisecond kernels it is longer, the GPU idles between launches and the counters' atomics are on.
+    beam_ms = stage["beam_ms"] if rabitq else st["region_ms"]
 
     if headline and args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -283,7 +293,9 @@ def measure(wl, args, headline, cand=None):
     roofline = {"bound": "hbm", "kernel": st["beam_kernel"], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "traffic_source": TRAFFIC_SOURCE.get(wl),
                 "bytes_per_launch": int(alg_bytes), "kernel_ms": round(beam_ms, 4),
-                "kernel_ms_source": "HIP events on the launch stream around the kernel, mean over a second loop of the same K calls",
+                "kernel_ms_source": ("HIP events around each stage inside the library, second loop of the same K calls" if rabitq else
+                                     "HIP events on the launch stream around the K back-to-back launches of the timed region, divided by K"),
+                "kernel_ms_isolated": round(stage["beam_ms"], 4),
                 "hops_per_query": round(st["hops"] / nq, 1), "dist_evals_per_query": round(st["dist_evals"] / nq, 1),
                 "stage_ms": {k2: round(v, 4) for k2, v in stage.items()}}
     if gather:
@@ -302,10 +314,15 @@ def measure(wl, args, headline, cand=None):
         # the same search with every frontier entry re-ranked: shows whether the 40-candidate re-rank is what caps recall
         sweep_all, L_all = sweep_for(lambda L: L)
         if L_all:
-            rec_a, ms_a, qps_a, stage_a, _ = timed(L_all, L_all)
+            rec_a, ms_a, qps_a, stage_a, st_a = timed(L_all, L_all)
+            bytes_a = st_a["adj_bytes"] + st_a["vec_bytes"] + nq * qrec + nq * L_all * 8
             cfg["rerank_whole_frontier"] = {"L": L_all, "rerank": L_all, "recall_at_10": round(rec_a, 4), "recall_sweep": sweep_all,
                                             "queries_per_s": round(qps_a, 1), "ms_per_step": round(ms_a, 4),
-                                            "stage_ms": {k2: round(v, 4) for k2, v in stage_a.items()}}
+                                            "stage_ms": {k2: round(v, 4) for k2, v in stage_a.items()},
+                                            "roofline": {"kernel": st_a["beam_kernel"], "bytes_per_launch": int(bytes_a),
+                                                         "kernel_ms": round(stage_a["beam_ms"], 4),
+                                                         "achieved": round(bytes_a / stage_a["beam_ms"] / 1e6, 1),
+                                                         "frac": round(bytes_a / stage_a["beam_ms"] / 1e6 / HBM_PEAK_GBS, 4)}}
         else:
             cfg["rerank_whole_frontier"] = {"recall_sweep": sweep_all, "recall_target_met": False}
         log(f"[bench] re-rank of the whole frontier: {cfg['rerank_whole_frontier']}")
@@ -430,7 +447,8 @@ def ablate(args):
             m = min(step, n - s0)
             dx[s0:s0 + m] = torch.from_numpy(datagen.base(wl, m, start=s0)).cuda()
         dq = torch.from_numpy(datagen.queries(wl, nq)).cuda()
-        g = jx.Index(d, jx.U8 if u8 else jx.F32, 64, 128, 1.2, capacity=n, max_batch=max(n // 4 + 1, nq), quant_bits=bits)
+        g = jx.Index(d, jx.U8 if u8 else jx.F32, 64, 128, 1.2, capacity=n, max_batch=max(n // 4 + 1, nq), quant_bits=bits,
+                     cand_mode=jx.CAND_VISITED if args.cand_mode == "visited" else jx.CAND_FRONTIER)
         g.insert(dx)
         if bits:
             g.quantize(bits, torch.from_numpy(datagen.rotation(wl)).cuda(), None, query_bits=8 if bits == 4 else 4)
@@ -465,7 +483,7 @@ def ablate(args):
     F = jx
     # --- 128-byte uint8 vectors (the paper's BigANN axis)
     g, dq, gt, n = build(2)
-    rows(f"workload 2 (N={n}, d=128 uint8, exact)", g, dq, gt, (32, 96, 256), [
+    rows(f"workload 2 (N={n}, d=128 uint8, exact)", g, dq, gt, (16, 32, 96), [
         ("default: tag table, 4 lanes x 2 chunks, chunked loads, 1 query per workgroup, two expansions per round where it applies", 0),
         ("one expansion per round", F.FLAG_NO_PAIR),
         ("visited: direct-mapped table of full ids", F.FLAG_VISITED_IDS | F.FLAG_NO_PAIR),
@@ -501,7 +519,7 @@ def ablate(args):
         ("visited: none (Alg. 2 as printed)", F.FLAG_VISITED_NONE)], mode=jx.RABITQ, rerank=40)
     del g
     return {"metric": "beamSearch kernel-variant ablation: kernel time per 10,000-query launch", "unit": "ms", "n_gpus": 1,
-            "launches_per_cell": reps, "data": "synthetic", "table": table}
+            "launches_per_cell": reps, "data": "synthetic", "graphs_built_from": args.cand_mode, "table": table}
 
 
 def main():
@@ -527,6 +545,7 @@ def main():
     ap.add_argument("--cand-mode", choices=["frontier", "visited"], default="visited",
                     help="what beamSearch hands to robustPrune during the build: the final frontier F (Alg. 2's output) or the "
                          "expansion list V (Alg. 4 as printed)")
+    ap.add_argument("--flags", type=int, default=0, help="JX_FLAG_* switches of the library (include/jx.h), e.g. 1 = one expansion per round")
     ap.add_argument("--no-others", action="store_true", help="skip the brief measurements of the other configurations")
     ap.add_argument("--others", type=str, default="1,3,4,5", help="configurations measured briefly after the headline (default run only)")
     ap.add_argument("--others-scale", type=float, default=1.0, help="scale the sizes of the other configurations (rehearsals and tests)")
@@ -542,7 +561,7 @@ def main():
     if args.ablate:
         print(json.dumps(ablate(args)), flush=True)
         return
-    with_others = args.workload == 2 and not (args.no_others or args.L or args.bits or args.f16 or args.delete_frac)
+    with_others = args.workload == 2 and not (args.no_others or args.L or args.bits or args.f16 or args.delete_frac or args.flags)
     cfg, roofline, cpu, tm = measure(args.workload, args, headline=True)
     if with_others and args.cand_mode == "visited":
         # the same headline workload on the graph built from final frontiers (the candidate set of the first round's

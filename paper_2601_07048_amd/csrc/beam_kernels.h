@@ -53,8 +53,10 @@ __device__ __forceinline__ void write_results(const BeamArgs& a, const int64_t q
         a.out_dist[qi * a.out_k + p] = __builtin_inff();
     }
     if (a.stats && lane == 0) {
-        atomicAdd(&a.stats[0], (unsigned long long)hops);
-        atomicAdd(&a.stats[1], (unsigned long long)evals);
+        // 64 stripes of counters, one 128-byte line each: ten thousand same-address atomics would serialise
+        unsigned long long* sp = a.stats + (size_t)(qi & 63) * 16;
+        atomicAdd(&sp[0], (unsigned long long)hops);
+        atomicAdd(&sp[1], (unsigned long long)evals);
     }
 }
 
@@ -323,8 +325,9 @@ __device__ __forceinline__ void beam_search_body(const BeamArgs& a) {
     if constexpr (VIS) {
         write_visited<KIND>(a, qi, vis, (int)(hops < (uint32_t)a.vis_cap ? hops : (uint32_t)a.vis_cap), lane);
         if (a.stats && lane == 0) {
-            atomicAdd(&a.stats[0], (unsigned long long)hops);
-            atomicAdd(&a.stats[1], (unsigned long long)evals);
+            unsigned long long* sp = a.stats + (size_t)(qi & 63) * 16;
+            atomicAdd(&sp[0], (unsigned long long)hops);
+            atomicAdd(&sp[1], (unsigned long long)evals);
         }
     } else {
         write_results<KIND, NREG>(a, qi, fk, count, lane, hops, evals);

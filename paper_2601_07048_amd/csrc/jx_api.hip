@@ -37,7 +37,7 @@ int fail(int code, const char* fmt, ...) {
 inline int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 
 struct Layout {
-    int64_t vecs, adj, codes, P, centroid, stats, deleted, clean, work, work_bytes, total;
+    int64_t vecs, adj, codes, P, centroid, stats, stripes, deleted, clean, work, work_bytes, total;
     int vec_bytes, code_bytes, meta_chunk, code_stride, plane_chunks, plane_shift;
 };
 
@@ -152,6 +152,8 @@ void layout(const jx_params* p, Layout* L) {
     off += align256((int64_t)p->dim * 4);
     L->stats = off;
     off += 256;
+    L->stripes = off;
+    off += 64 * 16 * 8;
     L->deleted = off;
     off += align256((int64_t)p->capacity + 4);
     L->clean = off;
@@ -299,6 +301,7 @@ int jx_create(const jx_params* p, void* d_arena, int64_t arena_bytes, void* stre
     x->d_P = (float*)(x->d_arena + L.P);
     x->d_centroid = (float*)(x->d_arena + L.centroid);
     x->d_stats = (unsigned long long*)(x->d_arena + L.stats);
+    x->d_stripes = (unsigned long long*)(x->d_arena + L.stripes);
     x->d_deleted = x->d_arena + L.deleted;
     x->d_clean = x->d_arena + L.clean;
     x->d_work = x->d_arena + L.work;
@@ -433,7 +436,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     if (mode == JX_RABITQ && !idx->quantized) return fail(JX_ESTATE, "index is not quantised");
     if (nq == 0) return JX_OK;
     const jx_params& p = idx->p;
-    if (h_stats) JX_HIP(jx::launch_fill_u32((uint32_t*)idx->d_stats, 16, 0u, st));
+    if (h_stats) JX_HIP(jx::launch_fill_u32((uint32_t*)idx->d_stripes, 64 * 16 * 2, 0u, st));
     jx::BeamArgs a;
     memset(&a, 0, sizeof a);
     a.adj = idx->d_adj;
@@ -443,7 +446,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     a.entry = idx->entry;
     visited_table_for(idx->flags, L, idx->n, &a.hash_slots, &a.tag_bits);
     a.flags = idx->flags;
-    a.stats = h_stats ? idx->d_stats : nullptr;
+    a.stats = h_stats ? idx->d_stripes : nullptr;
     a.deleted = idx->any_delete ? idx->d_deleted : nullptr;
     StageTimer tm(h_stats != nullptr, st);
     char kname[96] = "";
@@ -516,7 +519,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
                 r.k = out_k;
                 r.out_ids = d_out_ids + (size_t)q0 * out_k;
                 r.out_dist = d_out_dist + (size_t)q0 * out_k;
-                r.stats = h_stats ? idx->d_stats : nullptr;
+                r.stats = h_stats ? idx->d_stripes : nullptr;
                 tm.begin();
                 JX_HIP(jx::launch_rerank(p.dtype, r, st));
                 tm.end(3);
@@ -524,9 +527,11 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
         }
     }
     if (h_stats) {
-        unsigned long long hs[3];
-        JX_HIP(hipMemcpyAsync(hs, idx->d_stats, sizeof hs, hipMemcpyDeviceToHost, st));
+        unsigned long long stripes[64 * 16], hs[3] = {0, 0, 0};
+        JX_HIP(hipMemcpyAsync(stripes, idx->d_stripes, sizeof stripes, hipMemcpyDeviceToHost, st));
         JX_HIP(hipStreamSynchronize(st));
+        for (int i = 0; i < 64; i++)
+            for (int c = 0; c < 3; c++) hs[c] += stripes[i * 16 + c];
         memset(h_stats, 0, sizeof *h_stats);
         h_stats->hops = hs[0];
         h_stats->dist_evals = hs[1];

@@ -40,7 +40,7 @@ struct BeamArgs {
     uint32_t* out_ids;     // [nq][out_k]
     float* out_dist;       // [nq][out_k]
     int out_k;
-    unsigned long long* stats;  // {hops, dist_evals} or NULL
+    unsigned long long* stats;  // NULL, or 64 stripes of 16 counters (query i adds to stripe i % 64): [0] hops, [1] dist_evals
     const uint8_t* deleted;     // [N] 1 = logically deleted (never returned), or NULL
     uint32_t flags;             // JX_FLAG_* switches that select a kernel variant
     int vis_cap;                // > 0 (a power of two <= 512): instead of the frontier, out_ids / out_dist [nq][vis_cap]
@@ -126,7 +126,7 @@ struct RerankArgs {
     int cand_stride, rr, k;
     uint32_t* out_ids;       // [nq][k]
     float* out_dist;
-    unsigned long long* stats;  // [2] += number of vectors read
+    unsigned long long* stats;  // the same stripes: [2] += number of vectors read
 };
 
 hipError_t launch_rotate(const void* in, int in_dtype, long long n, int d, const float* P, const float* c, float* out,
@@ -214,7 +214,8 @@ struct jx_index {
     float* d_centroid;   // [dim]
     uint8_t* d_work;     // workspace shared by the phases
     int64_t work_bytes;
-    unsigned long long* d_stats;  // [8] search counters, [8] = vertices marked deleted so far
+    unsigned long long* d_stats;  // [8] = vertices marked deleted so far, [10] scratch of jx_import_graph
+    unsigned long long* d_stripes;  // [64][16] search counters (BeamArgs::stats)
     uint8_t* d_deleted;  // [capacity] 1 = logically deleted
     uint8_t* d_clean;    // [capacity] see InsertArgs::clean
     int any_delete;      // a delete call has been made since the graph was created / imported

@@ -683,7 +683,7 @@ __global__ void __launch_bounds__(256) rerank_kernel(RerankArgs a) {
             a.out_dist[qi * a.k + rank] = (KIND == K_U8) ? (float)dc : ordered_to_f32(dc);
         }
     }
-    if (a.stats && lane == 0) atomicAdd(&a.stats[2], (unsigned long long)m);
+    if (a.stats && lane == 0) atomicAdd(&a.stats[(size_t)(qi & 63) * 16 + 2], (unsigned long long)m);
 }
 
 template <int KIND>
