@@ -452,6 +452,8 @@ __global__ void __launch_bounds__(INS_WPB * 64) forward_prune_kernel(InsertArgs 
     B.id_stride = 1;
     B.d_stride = 1;
     B.dead = a.dead + (size_t)i * a.L;
+    // lists longer than 128: the block-row Gram-matrix kernel has run first and marks what it has done
+    if (a.gram && a.L > 128 && B.dead[0] == 0xFF) return;
     // the frontier is filled from the left: count its valid entries
     int nB = 0;
     for (int c0 = 0; c0 < a.L; c0 += 64) {
@@ -609,12 +611,25 @@ __global__ void __launch_bounds__(INS_WPB * 64) reverse_merge_kernel(InsertArgs 
             B.dbits = reinterpret_cast<const uint32_t*>(a.keys + lo);
             B.id_stride = 1;
             B.d_stride = 2;
-            B.n = m;
             B.dead = a.dead + lo;
-            for (int j = lane; j < m; j += 64) B.dead[j] = 0;
-            __threadfence_block();
-            wave_sync();
-            nsel = robust_prune_wave<KIND, T, CPL, false>(a.ds, L, deg, B, a.R, a.alpha);
+            // A hub (the entry point, vertices near it) can receive thousands of reverse edges in one batch, and every
+            // selection of the loop below passes over all live candidates.  Alg. 3 visits candidates in (distance, id)
+            // order, stops at R selections, and what happens to a candidate depends on earlier ones only: prune a
+            // prefix of the sorted new edges first; if the R-th selection comes no later than the last included new
+            // edge, the excluded ones could not have mattered and the result is exact.  Otherwise take four times as many.
+            int mp = m < 512 ? m : 512;
+            for (;;) {
+                B.n = mp;
+                for (int j = lane; j < mp; j += 64) B.dead[j] = 0;
+                for (int j = lane; j < deg; j += 64) L->a_dead[j] = 0;
+                __threadfence_block();
+                wave_sync();
+                nsel = robust_prune_wave<KIND, T, CPL, false>(a.ds, L, deg, B, a.R, a.alpha);
+                if (mp == m) break;
+                const uint64_t tau = ((uint64_t)B.dbits[(size_t)(mp - 1) * 2] << 32) | B.ids[mp - 1];
+                if (nsel >= a.R && (((uint64_t)L->sel_dist[nsel - 1] << 32) | L->sel_id[nsel - 1]) <= tau) break;
+                mp = (long long)mp * 4 < m ? mp * 4 : m;
+            }
         }
         for (int j = lane; j < a.R; j += 64) row[j] = j < nsel ? L->sel_id[j] : JX_NONE_ID;
         if (a.clean && lane == 0) a.clean[v] = (uint8_t)(nsel < 255 ? nsel : 255);
@@ -1016,9 +1031,11 @@ __device__ __forceinline__ int multi_pivot_prune_u8(FwdLds<MAXC>* F, const uint8
     return nsel;
 }
 
+// N = 128 (final frontiers of L_build <= 128) or 512 (expansion lists)
+template <int N>
 __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a) {
-    __shared__ FwdLds<128> lds;
-    FwdLds<128>* F = &lds;
+    __shared__ FwdLds<N> lds;
+    FwdLds<N>* F = &lds;
     const int lane = lane_id();
     const long long i = blockIdx.x;
     if (i >= a.B) return;
@@ -1026,9 +1043,9 @@ __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a)
     if (xid >= a.id_skip) xid++;
     const uint32_t* ids = a.cand_ids + (size_t)i * a.L;
     const uint32_t* dbits = a.cand_dist + (size_t)i * a.L;
-    uint64_t alive[2];
+    uint64_t alive[N / 64];
 #pragma unroll
-    for (int h = 0; h < 2; h++) {
+    for (int h = 0; h < N / 64; h++) {
         const int j = h * 64 + lane;
         uint32_t id = JX_NONE_ID;
         if (j < a.L) id = ids[j];
@@ -1040,7 +1057,7 @@ __global__ void __launch_bounds__(64) forward_prune_u8_lean_kernel(InsertArgs a)
         alive[h] = ballot(valid);  // the frontier is filled from the left
     }
     wave_sync();
-    const int nsel = multi_pivot_prune_u8<128>(F, a.ds.recs, alive, a.R, a.alpha);
+    const int nsel = multi_pivot_prune_u8<N>(F, a.ds.recs, alive, a.R, a.alpha);
     uint32_t* row = a.adj + (size_t)xid * a.R;
     for (int j = lane; j < a.R; j += 64) {
         const bool on = j < nsel;
@@ -1406,8 +1423,11 @@ hipError_t launch_forward_prune(int dtype, const InsertArgs& a, hipStream_t st) 
         hipError_t e = launch_forward_prune_gram(dtype, a, st);
         if (e != hipSuccess || a.L <= 128) return e;  // wider frontiers: the list-based kernel takes the rest
     }
-    if (dtype == JX_U8 && !a.gram && a.ds.rec_stride == 128 && a.ds.nch == 8 && a.L <= 128) {
-        hipLaunchKernelGGL(forward_prune_u8_lean_kernel, dim3((unsigned)a.B), dim3(64), 0, st, a);
+    if (dtype == JX_U8 && !a.gram && a.ds.rec_stride == 128 && a.ds.nch == 8 && a.L <= 512) {
+        if (a.L <= 128)
+            hipLaunchKernelGGL(forward_prune_u8_lean_kernel<128>, dim3((unsigned)a.B), dim3(64), 0, st, a);
+        else
+            hipLaunchKernelGGL(forward_prune_u8_lean_kernel<512>, dim3((unsigned)a.B), dim3(64), 0, st, a);
         return hipGetLastError();
     }
     if (dtype == JX_U8) return launch_prune_shape<K_U8>(true, a, st);

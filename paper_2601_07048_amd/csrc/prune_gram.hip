@@ -421,15 +421,17 @@ struct GramBigLds {
     uint32_t kill[GB_MAX * GB_NB];
     uint32_t kb[GB_MAX * GB_NB];
     uint32_t sel_id[GB_MAX];
+    uint32_t sel_dist[GB_MAX];  // float bits of d(p, selected), selection order
     uint16_t order[GB_MAX];
 };
 
-// L->id[0..M): n_fixed existing neighbours, then new candidates whose (distance bits << 32 | ...) keys are
-// new_keys[0..M-n_fixed), ascending.  truncated: further new candidates exist beyond the pool.  Returns the number
-// selected, or -1 if the pool did not suffice.
+// L->id[0..M): n_fixed existing neighbours, then new candidates, ascending, whose distances to p are the low words of
+// new_keys[0..M-n_fixed) (edge keys) or, if new_keys is null, new_dbits[0..M-n_fixed) (float bits).  truncated: further
+// new candidates exist beyond the pool.  Returns the number selected, or -1 if the pool did not suffice.
 template <int DT>
 __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride, int vec_bytes, GramBigLds* L, int M, uint32_t p,
-                                              int R, float alpha, int n_fixed, const uint64_t* new_keys, bool truncated) {
+                                              int R, float alpha, int n_fixed, const uint64_t* new_keys, bool truncated,
+                                              const uint32_t* new_dbits = nullptr) {
     const int lane = lane_id(), col = lane & 31, half = lane >> 5;
     const int nb = (M + 31) >> 5;
     const uint8_t* pp = recs + (size_t)p * stride;
@@ -514,7 +516,8 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
             }
             L->nrm[i] = i < M ? nstore : 0.f;
             // a new candidate keeps the distance it was sorted by
-            if (i >= n_fixed && i < M) d = __uint_as_float((uint32_t)(new_keys[i - n_fixed] & 0xFFFFFFFFull));
+            if (i >= n_fixed && i < M)
+                d = __uint_as_float(new_keys ? (uint32_t)(new_keys[i - n_fixed] & 0xFFFFFFFFull) : new_dbits[i - n_fixed]);
             L->dp[i] = d;
             if (i < M) L->key[i] = ((uint64_t)__float_as_uint(d) << 32) | L->id[i];
         }
@@ -683,7 +686,10 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
         for (int t = 1; t < GB_NB; t++)
             if (t > w && t < nb) gone = gone || (L->kb[c * GB_NB + t] & S[t]) != 0u;
         if (gone) continue;
-        if (lane == 0) L->sel_id[nsel] = cid;
+        if (lane == 0) {
+            L->sel_id[nsel] = cid;
+            L->sel_dist[nsel] = __float_as_uint(L->dp[c]);
+        }
         nsel++;
 #pragma unroll
         for (int t = 0; t < GB_NB; t++) {
@@ -694,6 +700,47 @@ __device__ __forceinline__ int gram_prune_big(const uint8_t* recs, size_t stride
     wave_sync();
     if (nsel >= R) short_pool = false;
     return short_pool ? -1 : nsel;
+}
+
+// ---- forward prune of candidate lists of 129 .. 256 entries, or of the closest 256 of a longer list (expansion
+// lists as candidate sets hold 150 - 200 vertices).  Every point of the batch gets a mark in a.dead[i * a.L]: 0xFF =
+// row and reverse edges written here, 0 = left to the list-based kernel (which also owns lists of at most 128, the
+// one-pass kernels' share).
+template <int DT>
+__global__ void __launch_bounds__(GP_WPB * 64) forward_prune_gram_big_kernel(InsertArgs a) {
+    extern __shared__ __align__(16) unsigned char gb_dyn[];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    GramBigLds* L = reinterpret_cast<GramBigLds*>(gb_dyn) + wave;
+    const long long i = (long long)blockIdx.x * GP_WPB + wave;
+    if (i >= a.B) return;
+    long long xid = a.id_base + i;
+    if (xid >= a.id_skip) xid++;
+    const uint32_t* ids = a.cand_ids + (size_t)i * a.L;
+    const uint32_t* dbits = a.cand_dist + (size_t)i * a.L;
+    int nB = 0;
+    for (int c0 = 0; c0 < a.L; c0 += 64) {
+        const int j = c0 + lane;
+        const bool valid = j < a.L && ids[j] != JX_NONE_ID;  // the list is filled from the left
+        nB += __builtin_popcountll(ballot(valid));
+    }
+    if (lane == 0) a.dead[(size_t)i * a.L] = 0;
+    if (nB <= GP_MAX) return;
+    const int M = nB < GB_MAX ? nB : GB_MAX;
+    for (int j = lane; j < M; j += 64) L->id[j] = ids[j];
+    wave_sync();
+    const int nsel = gram_prune_big<DT>(a.ds.recs, (size_t)a.ds.rec_stride, a.ds.nch * 16, L, M, (uint32_t)xid, a.R, a.alpha, 0, nullptr,
+                                        M < nB, dbits);
+    if (nsel < 0) return;  // the closest 256 did not yield R neighbours
+    uint32_t* row = a.adj + (size_t)xid * a.R;
+    for (int j = lane; j < a.R; j += 64) {
+        const bool on = j < nsel;
+        const uint32_t v = on ? L->sel_id[j] : JX_NONE_ID;
+        row[j] = v;
+        a.keys[(size_t)i * a.R + j] = on ? (((uint64_t)v << 32) | L->sel_dist[j]) : JX_EMPTY_KEY;
+        a.vals[(size_t)i * a.R + j] = on ? (uint32_t)xid : JX_NONE_ID;
+    }
+    if (a.clean && lane == 0) a.clean[xid] = (uint8_t)(nsel < 255 ? nsel : 255);
+    if (lane == 0) a.dead[(size_t)i * a.L] = 0xFF;
 }
 
 template <int DT>
@@ -748,6 +795,12 @@ static hipError_t launch_forward_gram_dt(const InsertArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((forward_prune_gram_kernel<DT, 2>), grid, block, 0, st, a);
     if (a.L > 64) hipLaunchKernelGGL((forward_prune_gram_kernel<DT, 3>), grid, block, 0, st, a);
     if (a.L > 96) hipLaunchKernelGGL((forward_prune_gram_kernel<DT, 4>), grid, block, 0, st, a);
+    if (a.L > GP_MAX) {  // longer lists (expansion lists): block-row form on the closest 256
+        const size_t sh = sizeof(GramBigLds) * GP_WPB;
+        hipError_t e = hipFuncSetAttribute((const void*)forward_prune_gram_big_kernel<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((forward_prune_gram_big_kernel<DT>), grid, block, sh, st, a);
+    }
     return hipGetLastError();
 }
 

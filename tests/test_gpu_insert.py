@@ -288,8 +288,9 @@ def test_insert_visited_candidates_with_deletions(jx):
 
 
 def test_insert_visited_candidates_float32(jx):
-    """Dyadic-grid float32 data (exact partial sums): bit parity in the expansion-list mode, at d = 64 and d = 960."""
-    for n, d, R, L in ((3000, 64, 24, 48), (1200, 960, 16, 32)):
+    """Dyadic-grid float32 data (exact partial sums): bit parity in the expansion-list mode, at d = 64, 960 and 1536;
+    lists of 256 and 512 slots go through the block-row Gram-matrix forward prune."""
+    for n, d, R, L in ((3000, 64, 24, 48), (1200, 960, 16, 32), (1500, 960, 16, 48), (1200, 1536, 12, 100)):
         x = datagen.dyadic_grid(n, d, seed=13 + d, step=0.25 if d > 64 else 0.125, lim=2.0 if d > 64 else 4.0)
         ref, g = _build_both(jx, x, R, L, [n // 3, n - n // 3], cand_mode=jx.CAND_VISITED)
         oadj, odeg, adj, deg = _graphs(ref, g)
