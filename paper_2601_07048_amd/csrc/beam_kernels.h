@@ -17,6 +17,9 @@ namespace jx {
 #ifndef JX_UMAX_RQ4
 #define JX_UMAX_RQ4 8
 #endif
+#ifndef JX_WPE_RQ1
+#define JX_WPE_RQ1 5  // wavefronts per SIMD the 1-bit kernel with its query planes in LDS is held to (96 VGPRs)
+#endif
 #ifndef JX_WPE_EXACT
 #define JX_WPE_EXACT 6
 #endif
@@ -203,9 +206,10 @@ __device__ __forceinline__ void beam_search_body(const BeamArgs& a) {
     const int H = a.hash_slots;
     const int tag_bits = a.tag_bits;  // > 0: 16-bit entries (slot and tag together name the id exactly)
     const uint32_t id_mask = tag_bits ? ((1u << (tag_bits + 30 - __builtin_clz((uint32_t)H))) - 1u) : 0u;  // H / 2 sets
-    const size_t per_wave = (size_t)FCAP * 8 + 64 * 8 + 64 * 4 + (size_t)H * (tag_bits ? 2 : 4) + (VIS ? (size_t)a.vis_cap * 8 : 0);
+    constexpr int QL = query_lds_bytes<KIND, T, CPL, QB>();  // query bit planes kept in LDS (jx_distance.h)
+    const size_t per_wave = (size_t)QL + (size_t)FCAP * 8 + 64 * 8 + 64 * 4 + (size_t)H * (tag_bits ? 2 : 4) + (VIS ? (size_t)a.vis_cap * 8 : 0);
     unsigned char* my = smem + per_wave * wave;
-    uint64_t* fr = reinterpret_cast<uint64_t*>(my);
+    uint64_t* fr = reinterpret_cast<uint64_t*>(my + QL);
     uint64_t* cand_key = fr + FCAP;
     uint32_t* cand_id = reinterpret_cast<uint32_t*>(cand_key + 64);
     uint32_t* tab = cand_id + 64;
@@ -215,7 +219,7 @@ __device__ __forceinline__ void beam_search_body(const BeamArgs& a) {
     for (int i = lane; i < FCAP; i += 64) fr[i] = JX_EMPTY_KEY;
 
     QueryRegs<KIND, CPL, QB> q;
-    load_query<KIND, T, CPL, QB, TILED>(q, a.ds, qi + (qi >= a.q_skip ? 1 : 0), lig);
+    load_query<KIND, T, CPL, QB, TILED>(q, a.ds, qi + (qi >= a.q_skip ? 1 : 0), lig, reinterpret_cast<uint4*>(my));
 
     uint64_t fk[NREG];
 #pragma unroll
@@ -335,7 +339,7 @@ __device__ __forceinline__ void beam_search_body(const BeamArgs& a) {
 }
 
 template <int KIND, int T, int CPL, int NREG, int QB>
-__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu(((KIND <= K_F32 || KIND == K_F16) && NREG <= 2 && CPL <= 2) ? JX_WPE_EXACT : 1, 8)))
+__global__ void __launch_bounds__(JX_BEAM_WPB * 64) __attribute__((amdgpu_waves_per_eu(((KIND <= K_F32 || KIND == K_F16) && NREG <= 2 && CPL <= 2) ? JX_WPE_EXACT : ((query_in_lds<KIND, CPL, QB>() && NREG <= 4) ? JX_WPE_RQ1 : 1), 8)))
 beam_search_kernel(BeamArgs a) {
     beam_search_body<KIND, T, CPL, NREG, QB, JX_BEAM_WPB, false>(a);
 }

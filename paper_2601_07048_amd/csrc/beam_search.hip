@@ -55,7 +55,7 @@ static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st, char* name) {
     }
 #define JX_LAUNCH(NR)                                                                                   \
     {                                                                                                   \
-        size_t sh = ((size_t)mirror_entries<NR>() * 8 + 64 * 8 + 64 * 4 + (size_t)H * (a.tag_bits ? 2 : 4)) * JX_BEAM_WPB; \
+        size_t sh = ((size_t)query_lds_bytes<KIND, T, CPL, QB>() + (size_t)mirror_entries<NR>() * 8 + 64 * 8 + 64 * 4 + (size_t)H * (a.tag_bits ? 2 : 4)) * JX_BEAM_WPB; \
         auto kern = beam_search_kernel<KIND, T, CPL, NR, QB>;                                           \
         if (sh > 48 * 1024) {                                                                           \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh); \

@@ -37,11 +37,26 @@ __device__ __forceinline__ uint32_t bcnt_acc(uint32_t x, uint32_t acc) {
     return r;
 }
 
+// 1-bit codes covered by 3 chunks per lane against four query bit planes: the planes (48 registers per lane) stay in
+// LDS, one 16-byte read per chunk and plane in the inner loop, which lets a fifth wavefront fit each SIMD
+#ifndef JX_RQ1_QLDS
+#define JX_RQ1_QLDS 1
+#endif
+template <int KIND, int CPL, int QB>
+constexpr bool query_in_lds() {
+    return JX_RQ1_QLDS && KIND == 3 && CPL == 3 && QB == 4;
+}
+template <int KIND, int T, int CPL, int QB>
+constexpr int query_lds_bytes() {
+    return query_in_lds<KIND, CPL, QB>() ? QB * CPL * T * 16 : 0;
+}
+
 template <int KIND, int CPL, int QB>
 struct QueryRegs {
     static constexpr int PLANES = (KIND == K_RQ4) ? 2 : (KIND == K_RQ1 ? QB : 1);
-    static constexpr int N = 4 * CPL * PLANES;
+    static constexpr int N = query_in_lds<KIND, CPL, QB>() ? 1 : 4 * CPL * PLANES;
     uint32_t w[N];
+    const uint4* lq;      // query_in_lds: planes in LDS, entry (plane * CPL + chunk slot) * T + lane in group
     uint32_t ps[CPL];     // RaBitQ: left shift of this chunk slot's integer dot product (high code plane)
     // per-query scalars
     int32_t qq;           // U8: sum q^2
@@ -54,8 +69,10 @@ struct QueryRegs {
 // the four elements of 16-byte chunk lig + T * (m / 4) ("chunked").  Query and records use the same assignment, so
 // the distance is the same sum.
 template <int KIND, int T, int CPL, int QB, bool TILED = false>
-__device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const DistSrc& a, int64_t qi, int lig) {
+__device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const DistSrc& a, int64_t qi, int lig,
+                                           uint4* lds_planes = nullptr) {
     const uint8_t* base = a.qrecs + qi * a.qrec_stride;
+    q.lq = lds_planes;
     if constexpr (KIND == K_U8 || KIND == K_F32 || KIND == K_F16) {
         if constexpr (TILED) {
 #pragma unroll
@@ -105,12 +122,17 @@ __device__ __forceinline__ void load_query(QueryRegs<KIND, CPL, QB>& q, const Di
                 // the high code plane meets the same query planes as the low one
                 const int qch = ch >= a.plane_chunks ? ch - a.plane_chunks : ch;
                 if (ch < a.meta_chunk) v = load16(base + 16 + (size_t)p * a.qplane_stride + (size_t)qch * 16);
-                q.w[(p * CPL + j) * 4 + 0] = v.x;
-                q.w[(p * CPL + j) * 4 + 1] = v.y;
-                q.w[(p * CPL + j) * 4 + 2] = v.z;
-                q.w[(p * CPL + j) * 4 + 3] = v.w;
+                if constexpr (query_in_lds<KIND, CPL, QB>()) {
+                    if (lane_id() < T) lds_planes[(p * CPL + j) * T + lig] = v;
+                } else {
+                    q.w[(p * CPL + j) * 4 + 0] = v.x;
+                    q.w[(p * CPL + j) * 4 + 1] = v.y;
+                    q.w[(p * CPL + j) * 4 + 2] = v.z;
+                    q.w[(p * CPL + j) * 4 + 3] = v.w;
+                }
             }
         }
+        if constexpr (query_in_lds<KIND, CPL, QB>()) wave_sync();
     }
 }
 
@@ -263,11 +285,16 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
                     uint32_t Ij = 0;
 #pragma unroll
                     for (int b = QB - 1; b >= 0; b--) {
-                        const uint32_t* qp = &q.w[(b * CPL + j) * 4];
-                        uint32_t cnt = bcnt_acc(v.x & qp[0], 0u);
-                        cnt = bcnt_acc(v.y & qp[1], cnt);
-                        cnt = bcnt_acc(v.z & qp[2], cnt);
-                        cnt = bcnt_acc(v.w & qp[3], cnt);
+                        uint4 qp;
+                        if constexpr (query_in_lds<KIND, CPL, QB>())
+                            qp = q.lq[(b * CPL + j) * T + lig];
+                        else
+                            qp = make_uint4(q.w[(b * CPL + j) * 4 + 0], q.w[(b * CPL + j) * 4 + 1], q.w[(b * CPL + j) * 4 + 2],
+                                            q.w[(b * CPL + j) * 4 + 3]);
+                        uint32_t cnt = bcnt_acc(v.x & qp.x, 0u);
+                        cnt = bcnt_acc(v.y & qp.y, cnt);
+                        cnt = bcnt_acc(v.z & qp.z, cnt);
+                        cnt = bcnt_acc(v.w & qp.w, cnt);
                         Ij = (Ij << 1) + cnt;  // Horner over the planes
                     }
                     I += Ij << q.ps[j];
