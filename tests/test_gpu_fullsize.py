@@ -211,6 +211,62 @@ def test_streaming_inserts_of_100k_match_oracle(jx):
     assert oracle.recall_at_k(u32(ids)[:2000], u32(gt)[:2000]) >= 0.95
 
 
+def test_fullsize_expansion_list_build_step_and_search_against_oracle(jx):
+    """The configuration bench.py's headline runs on: the 1M-point graph built with JX_CAND_VISITED (robustPrune of the
+    expansion list, Alg. 4 as printed).  (i) One full-size insertion step: the GPU builds 900,000 points, the oracle
+    takes over that graph, both insert the next 100,000 as one batch, and the two 1M x 64 tables must be equal -- this
+    is the step where the vertices around the entry point receive thousands of reverse edges.  (ii) The graph of one
+    1M-point jx_insert call, as the benchmark builds it: sampled queries at the headline's beam widths against the
+    oracle's beamSearch on the exported graph, bit for bit, and the recall the headline quotes."""
+    n0 = 900_000
+    x = datagen.base(2, N)
+    q = datagen.queries(2, NQ)
+    dx = dev(x)
+    g = jx.Index(128, jx.U8, R, LB, 1.2, capacity=N, max_batch=N // 4 + 1, cand_mode=jx.CAND_VISITED)
+    g.insert(dx[:n0])
+    adj0, _ = g.export_graph()
+    ref = oracle.Index(128, np.uint8, R, LB, 1.2, N, cand_mode=oracle.CAND_VISITED)
+    ref.set_graph(x[:n0], u32(adj0), g.size()[1])
+    del adj0
+    g.insert(dx[n0:])
+    ref.insert(x[n0:])
+    adj, deg = g.export_graph()
+    oadj, _ = ref.graph()
+    assert g.size() == (N, ref.entry)
+    bad = np.nonzero((u32(adj) != oadj).any(axis=1))[0]
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+    print("expansion-list step parity ok; mean degree", float(deg.float().mean()), flush=True)
+    del g, ref, oadj
+
+    g = jx.Index(128, jx.U8, R, LB, 1.2, capacity=N, max_batch=N // 4 + 1, cand_mode=jx.CAND_VISITED)
+    g.insert(dx)
+    adj, deg = g.export_graph()
+    assert 40 < float(deg.float().mean()) < 50
+    ref = oracle.Index(128, np.uint8, R, LB, 1.2, N)
+    ref.set_graph(x, u32(adj), g.size()[1])
+    sample = np.random.default_rng(16).choice(NQ, 300, replace=False)
+    dq = dev(q)
+    for L in (10, 16, 32):
+        ids, dist, st = g.search(dq, 10, L, stats=True)
+        assert st["beam_kernel"].startswith("beam_search_kernel<0,4,2,1,")
+        want = ref.search(q[sample], 10, L)
+        assert np.array_equal(u32(ids)[sample], want["ids"]), L
+        assert np.array_equal(dist.cpu().numpy().astype(np.float64)[sample], want["dist"]), L
+        one = g.search(dev(q[sample]), 10, L, stats=True)[2]
+        assert one["hops"] == want["hops"], L
+    gt, _ = g.bruteforce(dq, 10)
+    ids, _ = g.search(dq, 10, 16)
+    assert oracle.recall_at_k(u32(ids), u32(gt)) >= 0.95
+    # (iii) the whole table of that one-call build against the oracle's build in the same mode (the oracle prunes
+    # every hub's full candidate set: about a minute of host time)
+    ref = oracle.Index(128, np.uint8, R, LB, 1.2, N, cand_mode=oracle.CAND_VISITED)
+    ref.insert(x)
+    oadj, _ = ref.graph()
+    assert ref.entry == g.size()[1]
+    bad = np.nonzero((u32(adj) != oadj).any(axis=1))[0]
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+
+
 def _device_base(workload, n, d):
     dx = torch.empty((n, d), dtype=torch.float32, device="cuda")
     step = 16 * datagen.CHUNK
