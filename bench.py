@@ -564,8 +564,8 @@ def main():
     with_others = args.workload == 2 and not (args.no_others or args.L or args.bits or args.f16 or args.delete_frac or args.flags)
     cfg, roofline, cpu, tm = measure(args.workload, args, headline=True)
     if with_others and args.cand_mode == "visited":
-        # the same headline workload on the graph built from final frontiers (the candidate set of the first round's
-        # figures): shows what the choice of robustPrune's candidate set is worth
+        # the same headline workload on the graph built from final frontiers (the library's default candidate
+        # set): shows what the choice of robustPrune's candidate set is worth
         c, r, _, t = measure(args.workload, args, headline=False, cand="frontier")
         cfg["graph_from_final_frontier"] = {"workload": c["workload"], "L": c["L"], "recall_at_10": c["recall_at_10"],
                                             "recall_sweep": c["recall_sweep"], "queries_per_s": t["value"], "ms_per_step": t["ms_per_step"],
