@@ -16,7 +16,11 @@
  *     enqueueing unless stated otherwise ("blocks" = synchronises the stream).
  *   - A handle is not thread-safe.  Inserts, quantisation and searches on one
  *     index run in phases and must not overlap (Sec. 4.5: a batch of inserts
- *     completes before queries resume, and vice versa).
+ *     completes before queries resume, and vice versa).  One exception:
+ *     jx_search calls in JX_EXACT mode with h_stats == NULL only read the index
+ *     and write their own outputs, so several of them may be in flight on
+ *     different streams of the device (from one host thread); JX_RABITQ
+ *     searches use the index's workspace and must not overlap anything.
  *   - Ids are uint32, assigned in insertion order starting at 0; at most
  *     2^31 - 2 points.  0xFFFFFFFF (JX_NONE) marks an empty slot.
  *   - Distances are SQUARED Euclidean distances (App. B: the square root is

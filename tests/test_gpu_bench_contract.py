@@ -39,6 +39,10 @@ def test_bench_json_contract(extra):
     # the oracle on the exported graph returns what the GPU returned
     assert "identical to the GPU's: 1.0000" in cb["sample"] or extra, cb["sample"]
     assert abs(d["value"] - 512 / (d["ms_per_step"] * 1e-3)) / d["value"] < 0.02
+    if "two_batches_in_flight" in d["config"]:   # exact-mode lines: context, never the headline value
+        tb = d["config"]["two_batches_in_flight"]
+        assert tb["results_equal"] is True and tb["streams"] == 2 and tb["queries_per_s"] > 0
+        assert d["value"] != tb["queries_per_s"]
     dl = d["config"]["delete"]
     assert dl["deleted"] == int(0.1 * int(n)) and dl["consolidate_s"] > 0 and dl["compact_s"] >= 0
 
