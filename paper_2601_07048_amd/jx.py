@@ -3,6 +3,9 @@
 Argument marshalling only: every function here forwards torch tensors' device
 pointers and the current HIP stream to the entry point of the same name.  There
 is no CPU path; importing this module without a built ``libjx.so`` raises.
+
+The library is loaded from this directory; the environment variable ``JX_LIB`` names another build of it (a development
+aid for comparing builds; it changes which file is loaded, nothing else).
 """
 from __future__ import annotations
 
