@@ -227,9 +227,10 @@ int static_scratch(unsigned char** out) {
 
 // Visited table of beamSearch for beam width L on n vertices.  While ids fit slots x 2^15 the table holds 16-bit
 // tags (see BeamArgs::tag_bits): twice the slots in the same LDS, 16 % fewer repeated distance evaluations at L = 96.
-// 1,024 32-bit / 2,048 16-bit slots at least: measured optimum against the LDS footprint for L <= 256.
+// 1,024 32-bit / 2,048 16-bit slots at least: measured optimum against the LDS footprint for L <= 256 and records of
+// at most 256 bytes; twice / four times that for larger records (below).
 // JX_FLAG_VISITED_IDS keeps full ids; JX_FLAG_VISITED_NONE (slots = 0) switches the filter off.
-void visited_table_for(uint32_t flags, int L, int64_t n, int* slots, int* tag_bits) {
+void visited_table_for(uint32_t flags, int L, int64_t n, int rec_bytes, int* slots, int* tag_bits) {
     *tag_bits = 0;
     if (flags & JX_FLAG_VISITED_NONE) {
         *slots = 0;
@@ -239,6 +240,14 @@ void visited_table_for(uint32_t flags, int L, int64_t n, int* slots, int* tag_bi
     while (((int64_t)1 << id_bits) < n) id_bits++;
     int h = 1024;
     while (h < 4 * L && h < 4096) h *= 2;
+    // the table only ever forgets, so its size trades LDS (resident queries) against re-evaluated neighbours; a
+    // re-evaluation costs a record's bytes, so larger records buy a larger table (measured at N = 1M, L = 128:
+    // 496-byte code records -8 % evaluations / -5 % kernel time at 2x; 3,840- and 6,144-byte vectors -12..-17 %
+    // evaluations / -11..-17 % at 4x; 8x loses to occupancy, and records of at most 256 bytes lose at 2x already)
+    if (rec_bytes > 1024)
+        h *= 4;
+    else if (rec_bytes > 256)
+        h *= 2;
     *slots = h;
     if (!(flags & JX_FLAG_VISITED_IDS)) {
         int h16 = 2 * h, lg = 0;
@@ -444,7 +453,7 @@ static int search_common(jx_index* idx, const void* d_queries, int64_t nq, int32
     a.q_skip = 0x7FFFFFFFFFFFFFFFLL;
     a.L = L;
     a.entry = idx->entry;
-    visited_table_for(idx->flags, L, idx->n, &a.hash_slots, &a.tag_bits);
+    visited_table_for(idx->flags, L, idx->n, mode == JX_EXACT ? idx->vec_bytes : idx->code_stride, &a.hash_slots, &a.tag_bits);
     a.flags = idx->flags;
     a.stats = h_stats ? idx->d_stripes : nullptr;
     a.deleted = idx->any_delete ? idx->d_deleted : nullptr;
@@ -651,7 +660,7 @@ static int run_subbatch(jx_index* idx, const InsertWork& w, int64_t pos0, int64_
     b.q_skip = id_skip >= id_base ? id_skip - id_base : 0;
     b.L = p.L_build;
     b.entry = idx->entry;
-    visited_table_for(idx->flags, p.L_build, n_after, &b.hash_slots, &b.tag_bits);
+    visited_table_for(idx->flags, p.L_build, n_after, idx->vec_bytes, &b.hash_slots, &b.tag_bits);
     b.flags = idx->flags;
     const int Lc = cand_len(&p);
     b.out_ids = (uint32_t*)(W + w.cand_ids);
