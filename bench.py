@@ -80,8 +80,10 @@ def recall_of(ids, gt_np, k):
     return hit / (k * len(a))
 
 
-def measure(wl, args, headline, cand=None):
-    """Build workload `wl` on the GPU, pick L, time K search steps; returns (config, roofline, cpu_baseline, timing)."""
+def measure(wl, args, headline, cand=None, extras=False):
+    """Build workload `wl` on the GPU, pick L, time K search steps; returns (config, roofline, cpu_baseline, timing).
+    extras: also time the listed beam widths and two batches in flight (the default run; left out of single-workload
+    runs so that a profile of those holds the timed launches only)."""
     cand = cand or args.cand_mode
     import numpy as np
     import torch
@@ -309,7 +311,7 @@ def measure(wl, args, headline, cand=None):
            "recall_sweep": sweep, "build_inserts_per_s": round(n / t_build, 1), "build_s": round(t_build, 2)}
     if t_quant is not None:
         cfg["quantize_s"] = round(t_quant, 2)
-    if headline and wl == 2 and not forced_L:
+    if extras and headline and wl == 2 and not forced_L:
         # the beam widths the workload text lists, each timed like the headline (K back-to-back steps)
         listed = []
         for Lb in (32, 64, 128, 256):
@@ -319,7 +321,7 @@ def measure(wl, args, headline, cand=None):
                            "kernel": st_b["beam_kernel"], "kernel_ms": round(st_b["region_ms"], 4),
                            "frac": round(by / st_b["region_ms"] / 1e6 / HBM_PEAK_GBS, 4)})
         cfg["listed_beam_widths"] = listed
-    if not rabitq:
+    if extras and not rabitq:
         # Not the headline figure: the same K steps issued alternately on two streams (separate result buffers), as a
         # server with two batches in flight would.  A single launch ends with a few long searches on an emptying
         # machine; the next batch's launch fills that drain.  Exact-mode searches touch only their inputs and outputs,
@@ -581,6 +583,7 @@ def main():
                          "expansion list V (Alg. 4 as printed)")
     ap.add_argument("--flags", type=int, default=0, help="JX_FLAG_* switches of the library (include/jx.h), e.g. 1 = one expansion per round")
     ap.add_argument("--no-others", action="store_true", help="skip the brief measurements of the other configurations")
+    ap.add_argument("--extras", action="store_true", help="also time the listed beam widths and two batches in flight (always on in the default run)")
     ap.add_argument("--others", type=str, default="1,3,4,5", help="configurations measured briefly after the headline (default run only)")
     ap.add_argument("--others-scale", type=float, default=1.0, help="scale the sizes of the other configurations (rehearsals and tests)")
     ap.add_argument("--ablate", action="store_true", help="kernel-variant ablation instead of the benchmark (one JSON line with a table)")
@@ -596,11 +599,11 @@ def main():
         print(json.dumps(ablate(args)), flush=True)
         return
     with_others = args.workload == 2 and not (args.no_others or args.L or args.bits or args.f16 or args.delete_frac or args.flags)
-    cfg, roofline, cpu, tm = measure(args.workload, args, headline=True)
+    cfg, roofline, cpu, tm = measure(args.workload, args, headline=True, extras=with_others or args.extras)
     if with_others and args.cand_mode == "visited":
         # the same headline workload on the graph built from final frontiers (the library's default candidate
         # set): shows what the choice of robustPrune's candidate set is worth
-        c, r, _, t = measure(args.workload, args, headline=False, cand="frontier")
+        c, r, _, t = measure(args.workload, args, headline=False, cand="frontier", extras=True)
         cfg["graph_from_final_frontier"] = {"workload": c["workload"], "L": c["L"], "recall_at_10": c["recall_at_10"],
                                             "recall_sweep": c["recall_sweep"], "queries_per_s": t["value"], "ms_per_step": t["ms_per_step"],
                                             "steps": t["steps"], "build_inserts_per_s": c["build_inserts_per_s"],

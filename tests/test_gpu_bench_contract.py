@@ -52,6 +52,11 @@ def test_bench_default_run_covers_the_other_configurations():
     r = _run(["--n", "60000", "--nq", "512", "--steps", "3", "--warmup", "1", "--cpu-queries", "0", "--others-scale", "0.02"], timeout=600)
     assert r.returncode == 0, r.stderr[-3000:]
     d = json.loads([l for l in r.stdout.splitlines() if l.strip()][-1])
+    lw = d["config"]["listed_beam_widths"]
+    assert [e["L"] for e in lw] == [32, 64, 128, 256] and all(e["queries_per_s"] > 0 and e["kernel"].startswith("beam_search") for e in lw)
+    tb = d["config"]["two_batches_in_flight"]
+    assert tb["results_equal"] is True and tb["streams"] == 2 and tb["queries_per_s"] > 0
+    assert d["config"]["graph_from_final_frontier"]["two_batches_in_flight"]["results_equal"] is True
     others = d["config"]["others"]
     assert [o["workload"].split(":")[0] for o in others] == ["workload 1", "workload 3", "workload 4", "workload 5"]
     for o in others:
