@@ -41,15 +41,18 @@ static hipError_t launch_nreg(const BeamArgs& a, hipStream_t st, char* name) {
         // bandwidth, and the dropped second lists cost 12 % at d = 200, L = 128.
         // measured: +2..6 % for records of one 128-byte line from L = 64 (-3 % at L = 32); -8..-11 % for the 496- and
         // 208-byte records of d = 960 / 1536 codes, whose searches run at 7 TB/s and pay for every dropped list
-        if (nreg <= 2 && a.L >= 64 && a.R <= 64 && a.ds.rec_stride <= 128 && a.nq <= PAIR_MAX_QUERIES && H > 0 &&
+        if (nreg <= 4 && a.L >= 64 && a.R <= 64 && a.ds.rec_stride <= 128 && a.nq <= PAIR_MAX_QUERIES && H > 0 &&
             !(a.flags & JX_FLAG_NO_PAIR)) {
-            const size_t sh = (size_t)nreg * 64 * 8 + 128 * 8 + 128 * 4 + (size_t)H * (a.tag_bits ? 2 : 4);
+            const int pn = nreg <= 1 ? 1 : (nreg <= 2 ? 2 : 4);
+            const size_t sh = (size_t)pn * 64 * 8 + 128 * 8 + 128 * 4 + (size_t)H * (a.tag_bits ? 2 : 4);
             dim3 pgrid((unsigned)a.nq), pblock(64);
-            if (name) snprintf(name, 96, "beam_search_pair_kernel<%d,%d,%d,%d,%d>", KIND, T, CPL, nreg <= 1 ? 1 : 2, QB);
-            if (nreg <= 1)
+            if (name) snprintf(name, 96, "beam_search_pair_kernel<%d,%d,%d,%d,%d>", KIND, T, CPL, pn, QB);
+            if (pn == 1)
                 hipLaunchKernelGGL((beam_search_pair_kernel<KIND, T, CPL, 1, QB>), pgrid, pblock, sh, st, a);
-            else
+            else if (pn == 2)
                 hipLaunchKernelGGL((beam_search_pair_kernel<KIND, T, CPL, 2, QB>), pgrid, pblock, sh, st, a);
+            else
+                hipLaunchKernelGGL((beam_search_pair_kernel<KIND, T, CPL, 4, QB>), pgrid, pblock, sh, st, a);
             return hipGetLastError();
         }
     }

@@ -90,7 +90,7 @@ def test_fullsize_kernel_variants_against_oracle_and_each_other(jx, big):
                 "no visited filter": jx.FLAG_VISITED_NONE, "one chunk per lane": jx.FLAG_LANES_WIDE,
                 "four chunks per lane": jx.FLAG_LANES_NARROW | jx.FLAG_NO_PAIR}
     try:
-        for L in (64, 96, 128):
+        for L in (64, 96, 128, 256):   # 256: the four-register instance of the two-expansion kernel
             g.set_flags(0)
             ids0, dist0, st0 = g.search(dq, 10, L, stats=True)
             assert st0["beam_kernel"].startswith("beam_search_pair_kernel<0,4,2,")
