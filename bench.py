@@ -80,6 +80,9 @@ def recall_of(ids, gt_np, k):
     return hit / (k * len(a))
 
 
+_TWO_STREAMS = None
+
+
 def measure(wl, args, headline, cand=None, extras=False):
     """Build workload `wl` on the GPU, pick L, time K search steps; returns (config, roofline, cpu_baseline, timing).
     extras: also time the listed beam widths and two batches in flight (the default run; left out of single-workload
@@ -326,7 +329,10 @@ def measure(wl, args, headline, cand=None, extras=False):
         # server with two batches in flight would.  A single launch ends with a few long searches on an emptying
         # machine; the next batch's launch fills that drain.  Exact-mode searches touch only their inputs and outputs,
         # so they may overlap; code searches share the index workspace and may not.
-        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        global _TWO_STREAMS
+        if _TWO_STREAMS is None:   # one pair for the whole run: streams share a few hardware queues
+            _TWO_STREAMS = [torch.cuda.Stream(), torch.cuda.Stream()]
+        streams = _TWO_STREAMS
         outs = [out, (torch.empty_like(out[0]), torch.empty_like(out[1]))]
         best = None
         reps = max(steps, 20)
