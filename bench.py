@@ -620,12 +620,12 @@ def main():
         others = []
         for wl in [int(t) for t in args.others.split(",") if t]:
             t0 = time.time()
-            c, r, _, t = measure(wl, args, headline=False)
+            c, r, _, t = measure(wl, args, headline=False, extras=True)
             entry = {"workload": c["workload"], "L": c["L"], "recall_at_10": c["recall_at_10"], "recall_target_met": c["recall_target_met"],
                      "queries_per_s": t["value"], "ms_per_step": t["ms_per_step"], "steps": t["steps"], "dtype": t["dtype"],
                      "recall_sweep": c["recall_sweep"], "build_inserts_per_s": c["build_inserts_per_s"],
                      "roofline": {key: r[key] for key in ("kernel", "bytes_per_launch", "kernel_ms", "achieved", "frac", "stage_ms", "traffic_source")}}
-            for key in ("stream", "rerank_whole_frontier", "quantize_s"):
+            for key in ("stream", "rerank_whole_frontier", "quantize_s", "two_batches_in_flight"):
                 if key in c:
                     entry[key] = c[key]
             others.append(entry)
