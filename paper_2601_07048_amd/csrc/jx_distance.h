@@ -158,7 +158,8 @@ __device__ __forceinline__ void eval_batch(const QueryRegs<KIND, CPL, QB>& q, co
 #pragma unroll
     for (int u = 0; u < U; u++) {
         if (s0 + u * G < n_new) {  // wave-uniform
-            const uint8_t* rec = a.recs + (size_t)ids[u] * (size_t)a.rec_stride;
+            // the stride fits 32 bits (records are at most a few KB): one 32 x 32 -> 64-bit multiply-add per address
+            const uint8_t* rec = a.recs + (size_t)ids[u] * (uint32_t)a.rec_stride;
             if constexpr (TILED) {
                 const uint32_t* el = reinterpret_cast<const uint32_t*>(rec);
 #pragma unroll
