@@ -104,7 +104,7 @@ def measure(wl, args, headline, cand=None, extras=False):
     if not own and args.others_scale != 1.0:
         n = max(2000, int(n * args.others_scale))   # rehearsal of the default run at reduced sizes
     nq = (args.nq if own and args.nq else 0) or sp.get("nq", 10_000)
-    steps, warmup = (args.steps, args.warmup) if headline else (5, 1)
+    steps, warmup = (args.steps, args.warmup) if headline else (min(args.steps, 10), min(args.warmup, 2))
     rabitq = sp["bits"] > 0
     query_bits = (args.query_bits if headline else 0) or (4 if sp["bits"] in (1, 2) else 8)
     mode = jx.RABITQ if rabitq else jx.EXACT
