@@ -47,6 +47,13 @@ def test_header_constants_match_binding():
     assert int(consts["JX_RULE_MAXCOS"]) == jx.RULE_MAXCOS and int(consts["JX_RULE_MAXABS"]) == jx.RULE_MAXABS
     assert int(consts["JX_MAX_L"]) == jx.MAX_L and int(consts["JX_MAX_R"]) == jx.MAX_R
     assert int(consts["JX_MAX_BF_K"]) == jx.MAX_BF_K
+    assert int(consts["JX_CAND_FRONTIER"]) == jx.CAND_FRONTIER and int(consts["JX_CAND_VISITED"]) == jx.CAND_VISITED
+    assert int(consts["JX_RULE_DEFAULT"]) == jx.RULE_DEFAULT
+    # the kernel-variant switches: bit positions in the header and in the binding
+    flags = dict(re.findall(r"#define\s+(JX_FLAG_[A-Z0-9_]+)\s+\(1u << (\d+)\)", text))
+    assert len(flags) == 13
+    for name, bit in flags.items():
+        assert getattr(jx, name[3:]) == 1 << int(bit), name
 
 
 def _params(jx, **kw):
