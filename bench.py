@@ -125,6 +125,8 @@ def measure(wl, args, headline, cand=None, extras=False):
         for s0 in range(0, n, step):
             m = min(step, n - s0)
             dx[s0:s0 + m] = torch.from_numpy(datagen.base(gen_wl, m, start=s0)).cuda().to(tdt)
+            if n >= 20_000_000 and (s0 // step) % 40 == 39:
+                log(f"[bench] generated {s0 + m:,} of {n:,} base vectors")
     if sp.get("mips"):
         # inner-product data: one extra coordinate (padded to a multiple of 4) makes it an L2 problem
         assert not f16, "--f16 is not offered for the inner-product workload"
@@ -140,16 +142,19 @@ def measure(wl, args, headline, cand=None, extras=False):
     log(f"[bench] workload {wl}: generated {n}x{d} base + {nq} queries in {time.time() - t0:.1f}s")
 
     batch = 100_000 if wl == 5 else n
+    # one jx_insert call takes the whole base set (internal batches grow to a quarter of the index) -- or, streaming,
+    # 100,000 points per call
+    max_batch = max(min(batch, n), nq) if wl == 5 else max(n // 4 + 1, nq)
     cand_mode = jx.CAND_VISITED if cand == "visited" else jx.CAND_FRONTIER
     try:
         g = jx.Index(d, jx.U8 if sp["u8"] else (jx.F16 if f16 else jx.F32), R, L_build, alpha, capacity=n,
-                     max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"], cand_mode=cand_mode, flags=args.flags)
+                     max_batch=max_batch, quant_bits=sp["bits"], cand_mode=cand_mode, flags=args.flags)
     except jx.JxError:
         if cand_mode != jx.CAND_VISITED:
             raise
         cand_mode = jx.CAND_FRONTIER   # the expansion-list mode is not offered for this record shape
         g = jx.Index(d, jx.U8 if sp["u8"] else (jx.F16 if f16 else jx.F32), R, L_build, alpha, capacity=n,
-                     max_batch=max(n // 4 + 1, min(batch, n), nq), quant_bits=sp["bits"], cand_mode=cand_mode, flags=args.flags)
+                     max_batch=max_batch, quant_bits=sp["bits"], cand_mode=cand_mode, flags=args.flags)
 
     stream_log = []
     torch.cuda.synchronize()
@@ -166,7 +171,7 @@ def measure(wl, args, headline, cand=None, extras=False):
             dt = time.perf_counter() - t1
             t_ins += dt
             done = s0 + m
-            if done % 1_000_000 == 0 or done == n:
+            if done % args.stream_every == 0 or done == n:
                 gt_c, _ = g.bruteforce(dq, k)
                 ids, _ = g.search(dq, k, 128)
                 torch.cuda.synchronize()
@@ -588,6 +593,7 @@ def main():
                     help="what beamSearch hands to robustPrune during the build: the final frontier F (Alg. 2's output) or the "
                          "expansion list V (Alg. 4 as printed)")
     ap.add_argument("--flags", type=int, default=0, help="JX_FLAG_* switches of the library (include/jx.h), e.g. 1 = one expansion per round")
+    ap.add_argument("--stream-every", type=int, default=1_000_000, help="streaming workload: points between two query batches")
     ap.add_argument("--no-others", action="store_true", help="skip the brief measurements of the other configurations")
     ap.add_argument("--extras", action="store_true", help="also time the listed beam widths and two batches in flight (always on in the default run)")
     ap.add_argument("--others", type=str, default="1,3,4,5", help="configurations measured briefly after the headline (default run only)")
