@@ -64,6 +64,29 @@ def test_search_topk_is_frontier_prefix_and_deterministic(jx, u8_case):
     assert np.array_equal(u32(a_ids), ref["ids"])
 
 
+def test_exact_searches_in_flight_on_two_streams(jx, u8_case):
+    """jx_search in JX_EXACT mode without statistics only reads the index and writes its own outputs: calls issued
+    alternately on two streams, with a result buffer each, overlap on the device and every one returns the oracle's
+    ids and distances."""
+    x, q, ix, g = u8_case
+    big = np.concatenate([q] * 40)   # 8,120 queries: long enough launches to overlap
+    dq = dev(big)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [(torch.empty((big.shape[0], 10), dtype=torch.int32, device="cuda"),
+             torch.empty((big.shape[0], 10), dtype=torch.float32, device="cuda")) for _ in range(4)]
+    torch.cuda.synchronize()
+    for i in range(8):
+        with torch.cuda.stream(streams[i & 1]):
+            g.search(dq, 10, 64 if i & 2 else 32, out=outs[i & 3])
+    torch.cuda.synchronize()
+    for L, pair in ((32, (0, 1)), (64, (2, 3))):
+        ref = ix.search(q, 10, L)
+        for o in pair:
+            ids, dist = outs[o]
+            assert np.array_equal(u32(ids)[:q.shape[0]], ref["ids"]) and np.array_equal(u32(ids)[-q.shape[0]:], ref["ids"])
+            assert np.array_equal(dist.cpu().numpy().astype(np.float64)[:q.shape[0]], ref["dist"])
+
+
 @pytest.mark.parametrize("L", [16, 64, 130])
 def test_beam_f32_tolerance(jx, f32_case, L):
     """float32 distances: within 1e-4 relative of the oracle's double result;
